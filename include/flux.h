@@ -1,0 +1,175 @@
+/*
+ * flux.h - C ABI of the MI355X (gfx950) library for tensor-parallel GEMMs with the
+ * communication fused in at tile granularity.
+ *
+ * Two operations are covered, both seen from ONE rank of an N_TP-way tensor-parallel group
+ * ("R virtual ranks": every peer buffer is a pointer into this GPU's own memory):
+ *
+ *   GEMM-ReduceScatter  (paper Alg. 1, Sec. 3.1, Sec. 4.1, Sec. 4.2 "Reduce")
+ *       out[r][i - r*S, n] = cvt( sum_k A[i,k] B[k,n]  +  sum_{j != rank} peer_j[i,n] ),
+ *       r = i / S, S = M / R.   One kernel: the reduction and the scatter to the owning
+ *       rank's row slice happen in the GEMM epilogue; tiles are visited slice by slice
+ *       starting after the local rank (rank-shifted TileCoord).
+ *
+ *   AllGather-GEMM      (paper Alg. 2 + Alg. 3 pull form, Sec. 3.2, Sec. 4.1, Sec. 4.3)
+ *       C = A_agg B,  A_agg = rows of chunk 0, chunk 1, ... chunk R-1.
+ *       A copy driver on `copy_stream` moves the remote chunks into A_agg in `arrival_order`
+ *       and sets one 32-bit signal per communication tile; the GEMM kernel on
+ *       `compute_stream` visits tiles in the same order and spins on the signals of the rows
+ *       a tile needs before touching them (WaitSignal in the prologue).
+ *
+ * plus the non-overlapped baseline used for the overlap-efficiency metric (Sec. 2.3, Eq. 1-2).
+ *
+ * Conventions
+ *   - All matrices are row-major and densely packed: A [M,K], B [K,N], partials / C [M,N],
+ *     slices [M/R,N].  A and B are bf16; partials and outputs are bf16 or f32 (flux_dtype_t).
+ *   - M % R == 0; N % 8 == 0; K % 8 == 0; every base pointer 16-byte aligned; R <= FLUX_MAX_RANKS.
+ *   - Every pointer marked "device" must be device memory of the current HIP device, allocated
+ *     and freed by the caller.  The library never allocates or frees device memory.  Pointer
+ *     *lists* (peer_partials, out_slices, A_chunks) and `arrival_order` are HOST arrays that
+ *     are read during the call only.
+ *   - Streams are hipStream_t passed as void* (NULL = the default stream).  All calls are
+ *     asynchronous: they validate, enqueue and return.  Nothing is enqueued when the
+ *     returned status is not FLUX_OK.
+ *   - Errors are returned as flux_status_t values; nothing throws or aborts.  A signal wait
+ *     that exceeds `spin_timeout_ticks` is reported through flux_query_status after the
+ *     stream has been synchronised (the kernel then leaves the affected tiles unwritten).
+ *   - Calls that share a workspace, an A_agg buffer or a signal array must not overlap in time.
+ */
+#ifndef FLUX_MI355_H_
+#define FLUX_MI355_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FLUX_MAX_RANKS 16
+#define FLUX_MAX_M_TILES 1024      /* ceil(M / tile height) must not exceed this */
+
+typedef enum {
+  FLUX_OK = 0,
+  FLUX_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, misaligned base */
+  FLUX_ERR_SHAPE = 2,         /* M % R != 0, N or K not a multiple of 8, sizes <= 0 or too large */
+  FLUX_ERR_UNSUPPORTED = 3,   /* valid request the library has no kernel for */
+  FLUX_ERR_WORKSPACE = 4,     /* workspace missing or smaller than flux_workspace_bytes */
+  FLUX_ERR_HIP = 5,           /* a HIP runtime call failed (flux_last_hip_error has the code) */
+  FLUX_ERR_TIMEOUT = 6        /* reported by flux_query_status only */
+} flux_status_t;
+
+typedef enum { FLUX_BF16 = 0, FLUX_F32 = 1 } flux_dtype_t;
+typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
+
+/* flux_problem_t.flags */
+#define FLUX_FLAG_NO_SWIZZLE   0x1u  /* natural tile order: no rank shift / arrival alignment, no die remap */
+#define FLUX_FLAG_NO_XCD_REMAP 0x2u  /* keep the visit order but do not regroup tiles per accelerator die */
+#define FLUX_FLAG_COPY_MEMCPY  0x4u  /* AG copy driver = hipMemcpyAsync + stream write-value per
+                                        communication tile instead of the copy kernel */
+
+/* flux_gemm_ref_unfused phases */
+#define FLUX_PHASE_GEMM 0x1
+#define FLUX_PHASE_COMM 0x2
+
+typedef struct flux_problem {
+  int32_t M, N, K;          /* this rank's GEMM: A[M,K] . B[K,N]  (Alg. 1 / Alg. 2 operands)      */
+  int32_t R, rank;          /* N_TP and rank_id                                                   */
+  int32_t partial_dtype;    /* RS: dtype of the peer partials (flux_dtype_t); ignored for AG      */
+  int32_t out_dtype;        /* dtype of out_slices / C (flux_dtype_t)                             */
+  int32_t tile_config;      /* 0 = library picks; else an id from flux_tile_config_info           */
+  int32_t split_k;          /* 0 = library picks; >1 cuts K over that many workgroups per tile    */
+  uint32_t flags;           /* FLUX_FLAG_*                                                        */
+  int32_t comm_tiles_per_chunk; /* AG: signals per chunk (Sec. 4.3 "communication tile size");
+                                   0 or 1 = one per chunk; must divide M/R                        */
+  int32_t copy_workgroups;  /* AG copy kernel grid size; 0 = library picks                        */
+  uint64_t spin_timeout_ticks;  /* AG: bound on one signal wait, in 100 MHz wall-clock ticks;
+                                   0 = library default (10 s).  The paper spins without bound.   */
+} flux_problem_t;
+
+/*
+ * GEMM-ReduceScatter, fused (Alg. 1 with the Reduce branch).
+ *   A, B            device, bf16, [M,K] and [K,N].
+ *   peer_partials   host array [R] of device pointers to [M,N] matrices of partial_dtype;
+ *                   entry [rank] is ignored (may be NULL).
+ *   out_slices      host array [R] of device pointers to [M/R,N] matrices of out_dtype, all
+ *                   written (every element exactly once).
+ *   workspace       device, >= flux_workspace_bytes(FLUX_OP_RS, p) bytes (may be NULL if 0).
+ */
+int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
+                 const void* const* peer_partials, void* const* out_slices,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * AllGather-GEMM, fused (Alg. 2 kernel + Alg. 3 host driver, pull form).
+ *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
+ *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
+ *                   at A_agg + rank*(M/R)*K the local chunk is not copied.
+ *   B, C            device, [K,N] bf16 and [M,N] out_dtype.
+ *   signals         device uint32[R * comm_tiles_per_chunk] ("signal_list"); contents on entry
+ *                   are ignored; on completion local ones hold 1, the others 0 (reset after
+ *                   the GEMM, ordered by stream + event as in Sec. 4.3 "Signals").
+ *   arrival_order   host int32[R-1]: the remote ranks in the order the copy driver transfers
+ *                   them; NULL = ring order starting after `rank` (Sec. 4.3).
+ *   workspace       device, >= flux_workspace_bytes(FLUX_OP_AG, p).
+ *   compute_stream  the GEMM kernel's stream; on return of the call it is ordered after the
+ *                   GEMM, the copy driver and the signal reset.
+ *   copy_stream     the copy driver's stream; must differ from compute_stream.
+ */
+int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_agg,
+                 const void* B, void* C, uint32_t* signals, const int32_t* arrival_order,
+                 void* workspace, size_t workspace_bytes,
+                 void* compute_stream, void* copy_stream);
+
+/*
+ * Non-overlapped baseline (Sec. 2.3: the reference point of Eq. 2), everything on one stream.
+ *   op = FLUX_OP_RS:  FLUX_PHASE_GEMM  C = A.B (C: device [M,N] of out_dtype, a temporary);
+ *                     FLUX_PHASE_COMM  out_slices[r] = C + sum peers (separate kernel).
+ *   op = FLUX_OP_AG:  FLUX_PHASE_COMM  copy all chunks into A_agg (no signals);
+ *                     FLUX_PHASE_GEMM  C = A_agg.B.
+ *   `phases` selects which of the two to enqueue (both: communication and GEMM in dependency
+ *   order).  Arguments not used by `op` may be NULL.  The GEMM kernel is the same tile
+ *   configuration the fused call would use, without prologue wait or reduce epilogue.
+ */
+int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p,
+                          const void* A, const void* const* A_chunks, void* A_agg,
+                          const void* B, const void* const* peer_partials,
+                          void* const* out_slices, void* C,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of device workspace the given problem needs (0 on invalid problems). */
+size_t flux_workspace_bytes(int op, const flux_problem_t* p);
+
+/*
+ * Reads the status block a finished flux_ag_gemm left in `workspace` (blocking device-to-host
+ * copy; synchronise the streams first).  code = FLUX_OK or FLUX_ERR_TIMEOUT, detail = index
+ * of the first signal that timed out.
+ */
+int flux_query_status(const void* workspace, int32_t* code, int32_t* detail);
+
+/*
+ * TileCoord of Alg. 1 / Alg. 2 as the kernels compute it (host function, for tests):
+ * linear workgroup id -> (m_tile, n_tile) for the tile configuration the call would use.
+ */
+int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_order,
+                    int32_t block, int32_t* m_tile, int32_t* n_tile);
+
+/* Tile configuration a call would use: tile sizes, K split and die count used for the remap. */
+int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* tile_n,
+                    int32_t* tile_k, int32_t* split_k, int32_t* n_xcd);
+
+/* Enumerates tile configurations: returns FLUX_OK and fills the sizes for ids 1..count. */
+int flux_tile_config_count(void);
+int flux_tile_config_info(int32_t id, int32_t* tile_m, int32_t* tile_n, int32_t* tile_k);
+
+/* Communication order of Sec. 4.3 (ring starting after the local rank): fills order[R-1]. */
+int flux_default_order(int32_t rank, int32_t R, int32_t* order);
+
+const char* flux_status_string(int status);
+int flux_last_hip_error(void);       /* hipError_t of the most recent FLUX_ERR_HIP on this thread */
+int flux_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLUX_MI355_H_ */

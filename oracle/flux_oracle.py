@@ -276,6 +276,32 @@ def gemm_rs(A, B, peers, R: int, rank: int, partial_dtype: str, out_dtype: str,
     return slices64, [round_to(s, out_dtype) for s in slices64]
 
 
+def gemm_rs_rows(A, B, peers, R: int, rank: int, partial_dtype: str, rows, ab_dtype: str = BF16):
+    """The same definition as `gemm_rs`, evaluated for a subset of global rows only (used where
+    the full problem is too large to finish in seconds).  Returns a list of
+    (owner_rank, local_row, values64[N]) in the order of `rows`."""
+    rows = [int(i) for i in rows]
+    a = to_f64(A, ab_dtype)
+    M = a.shape[0]
+    S = slice_rows(M, R)
+    vals = a[rows, :] @ to_f64(B, ab_dtype)
+    for j in range(R):
+        if j == rank:
+            continue
+        pj = peers[j]
+        if pj.shape[0] != M:
+            raise ValueError("peer partial has the wrong shape")
+        vals = vals + to_f64(pj[rows, :], partial_dtype)
+    return [(owner_of_row(i, M, R), local_row(i, M, R), vals[t]) for t, i in enumerate(rows)]
+
+
+def ag_gemm_rows(A_chunks, B, rows, ab_dtype: str = BF16) -> np.ndarray:
+    """`ag_gemm` for a subset of global rows: row i lives in chunk i // S at local row i % S."""
+    S = A_chunks[0].shape[0]
+    picked = np.stack([to_f64(A_chunks[int(i) // S][int(i) % S], ab_dtype) for i in rows])
+    return picked @ to_f64(B, ab_dtype)
+
+
 def rs_from_factors(A_list, B_list, ab_dtype: str = BF16) -> np.ndarray:
     """The reduce-scatter result written from its definition: sum over ranks of A_r . B_r,
     before scattering (Sec. 2.1: the second GEMM of the MLP is sharded along K)."""

@@ -1,0 +1,636 @@
+// Host side of the library: argument validation, TileCoord tables, the AllGather copy driver
+// (paper Alg. 3, pull form), the non-overlapped baseline and the C ABI declared in flux.h.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "flux_internal.h"
+
+namespace flux {
+
+// (not const: a const table of host function pointers would also be emitted for the device)
+CfgInfo g_cfgs[NUM_CFGS] = {
+    {256, 256, 64, launch_cfg1}, {256, 128, 64, launch_cfg2}, {128, 128, 64, launch_cfg3},
+    {64, 64, 64, launch_cfg4},   {64, 128, 64, launch_cfg5},  {32, 128, 64, launch_cfg6},
+};
+
+constexpr int N_XCD = 8;                       // accelerator dies of an MI355X, one L2 each
+constexpr unsigned long long DEFAULT_TIMEOUT_TICKS = 1000000000ull;   // 10 s at 100 MHz
+
+static thread_local int g_last_hip_error = 0;
+
+#define FLUX_HIP(expr)                                  \
+  do {                                                  \
+    hipError_t e__ = (expr);                            \
+    if (e__ != hipSuccess) {                            \
+      g_last_hip_error = (int)e__;                      \
+      (void)hipGetLastError();                          \
+      return FLUX_ERR_HIP;                              \
+    }                                                   \
+  } while (0)
+
+// ------------------------------------------------------------------------------------------
+// small kernels
+// ------------------------------------------------------------------------------------------
+
+// Puts the signal array in its preset state (local communication tiles 1, the others 0;
+// paper Sec. 4.3 "Signals") and optionally clears the workspace header.
+__global__ void preset_kernel(uint32_t* signals, int n_signals, int local_lo, int local_hi,
+                              uint32_t* header, int header_words) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (signals != nullptr && i < n_signals) signals[i] = (i >= local_lo && i < local_hi) ? 1u : 0u;
+  if (header != nullptr && i < header_words) header[i] = 0u;
+}
+
+struct CopyArgs {
+  const uint4* src[FLUX_MAX_RANKS];   // chunk sources, indexed by rank
+  uint4* dst;                         // A_agg
+  int32_t order[FLUX_MAX_RANKS];      // chunks to move, in transfer order
+  int32_t n_order;
+  int32_t tiles_per_chunk;            // communication tiles per chunk
+  unsigned long long chunk_vec;       // 16-byte vectors per chunk
+  unsigned long long tile_vec;        // 16-byte vectors per communication tile
+  uint32_t* signals;                  // may be null (baseline copy)
+  uint32_t* counters;
+};
+
+// Copy driver as one kernel: all workgroups move communication tile after communication tile
+// in transfer order (DataTransfer of Alg. 3); the workgroup that finishes a tile last sets its
+// signal (SetSignal) after every workgroup's stores have been released to device scope.
+__global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
+  const unsigned long long stride = (unsigned long long)gridDim.x * blockDim.x;
+  const unsigned long long t0 = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int n_tiles = c.n_order * c.tiles_per_chunk;
+  for (int idx = 0; idx < n_tiles; ++idx) {
+    const int chunk = c.order[idx / c.tiles_per_chunk];
+    const int t = idx % c.tiles_per_chunk;
+    const uint4* __restrict__ src = c.src[chunk] + (unsigned long long)t * c.tile_vec;
+    uint4* __restrict__ dst = c.dst + (unsigned long long)chunk * c.chunk_vec + (unsigned long long)t * c.tile_vec;
+    unsigned long long i = t0;
+    for (; i + 3 * stride < c.tile_vec; i += 4 * stride) {
+      const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+      dst[i] = v0; dst[i + stride] = v1; dst[i + 2 * stride] = v2; dst[i + 3 * stride] = v3;
+    }
+    for (; i < c.tile_vec; i += stride) dst[i] = src[i];
+    if (c.signals != nullptr) {
+      const int flag = chunk * c.tiles_per_chunk + t;
+      __threadfence();
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        const uint32_t prev = atomicAdd(c.counters + flag, 1u);
+        if (prev == gridDim.x - 1) {
+          c.counters[flag] = 0u;
+          __threadfence();
+          __hip_atomic_store(c.signals + flag, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+      }
+    }
+  }
+}
+
+struct ReduceArgs {
+  const void* C;                      // [M,N] out dtype
+  const void* peers[FLUX_MAX_RANKS];
+  void* outs[FLUX_MAX_RANKS];
+  int32_t M, N, R, rank, S, partial_f32, out_f32;
+};
+
+// Baseline reduce-scatter: out[r] = C + sum of peer partials, 8 columns per thread.
+__global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
+  const long long nvec = (long long)a.M * a.N / 8;
+  const int nv_row = a.N / 8;
+  for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (long long)gridDim.x * blockDim.x) {
+    const int gm = (int)(v / nv_row);
+    const int gn = (int)(v % nv_row) * 8;
+    const size_t off = (size_t)gm * a.N + gn;
+    float x[8];
+    if (a.out_f32) {
+      const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.C) + off);
+      const float4 u = p[0], w = p[1];
+      x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = w.x; x[5] = w.y; x[6] = w.z; x[7] = w.w;
+    } else {
+      const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const __bf16*>(a.C) + off);
+      x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+      x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
+    }
+    for (int j = 0; j < a.R; ++j) {
+      if (j == a.rank) continue;
+      if (a.partial_f32) {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.peers[j]) + off);
+        const float4 u = p[0], w = p[1];
+        x[0] += u.x; x[1] += u.y; x[2] += u.z; x[3] += u.w; x[4] += w.x; x[5] += w.y; x[6] += w.z; x[7] += w.w;
+      } else {
+        const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const __bf16*>(a.peers[j]) + off);
+        x[0] += bf16_lo(w.x); x[1] += bf16_hi(w.x); x[2] += bf16_lo(w.y); x[3] += bf16_hi(w.y);
+        x[4] += bf16_lo(w.z); x[5] += bf16_hi(w.z); x[6] += bf16_lo(w.w); x[7] += bf16_hi(w.w);
+      }
+    }
+    const int r = gm / a.S;
+    const size_t o = (size_t)(gm - r * a.S) * a.N + gn;
+    if (a.out_f32) {
+      float4* q = reinterpret_cast<float4*>(static_cast<float*>(a.outs[r]) + o);
+      q[0] = make_float4(x[0], x[1], x[2], x[3]);
+      q[1] = make_float4(x[4], x[5], x[6], x[7]);
+    } else {
+      uint4 w;
+      w.x = pack_bf16x2(x[0], x[1]); w.y = pack_bf16x2(x[2], x[3]);
+      w.z = pack_bf16x2(x[4], x[5]); w.w = pack_bf16x2(x[6], x[7]);
+      *reinterpret_cast<uint4*>(static_cast<__bf16*>(a.outs[r]) + o) = w;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// planning
+// ------------------------------------------------------------------------------------------
+
+struct Plan {
+  int cfg;          // index into g_cfgs
+  int bm, bn, bk;
+  int tiles_m, tiles_n;
+  int split_k, k_per_split;
+  int edge;
+  int n_xcd;
+  int ctpc;         // communication tiles per chunk
+};
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int validate_problem(int op, const flux_problem_t* p) {
+  if (p == nullptr) return FLUX_ERR_INVALID_ARG;
+  if (op != FLUX_OP_RS && op != FLUX_OP_AG) return FLUX_ERR_INVALID_ARG;
+  if (p->M <= 0 || p->N <= 0 || p->K <= 0) return FLUX_ERR_SHAPE;
+  if (p->R < 1 || p->R > FLUX_MAX_RANKS) return FLUX_ERR_SHAPE;
+  if (p->rank < 0 || p->rank >= p->R) return FLUX_ERR_INVALID_ARG;
+  if (p->M % p->R != 0 || p->N % 8 != 0 || p->K % 8 != 0) return FLUX_ERR_SHAPE;
+  if ((long long)p->M * p->N >= (1ll << 31) * 8ll || (long long)p->M * p->K >= (1ll << 31) * 8ll ||
+      (long long)p->K * p->N >= (1ll << 31) * 8ll) return FLUX_ERR_SHAPE;
+  if (p->out_dtype != FLUX_BF16 && p->out_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
+  if (op == FLUX_OP_RS && p->partial_dtype != FLUX_BF16 && p->partial_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
+  if (p->tile_config < 0 || p->tile_config > NUM_CFGS) return FLUX_ERR_INVALID_ARG;
+  if (p->split_k < 0 || p->split_k > 64) return FLUX_ERR_INVALID_ARG;
+  if (p->copy_workgroups < 0 || p->copy_workgroups > 4096) return FLUX_ERR_INVALID_ARG;
+  if (op == FLUX_OP_AG) {
+    const int ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
+    const int S = p->M / p->R;
+    if (S % ctpc != 0) return FLUX_ERR_SHAPE;
+    if ((long long)ctpc * p->R > MAX_COMM_TILES) return FLUX_ERR_UNSUPPORTED;
+  }
+  return FLUX_OK;
+}
+
+static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
+  int st = validate_problem(op, p);
+  if (st != FLUX_OK) return st;
+  int cfg;
+  if (p->tile_config > 0) {
+    cfg = p->tile_config - 1;
+  } else if (p->M <= 32) {
+    cfg = 5;
+  } else if (p->M <= 64) {
+    cfg = 4;
+  } else if ((long long)p->M * p->N <= 256ll * 1024) {
+    cfg = 3;
+  } else if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 2 * 256) {
+    cfg = 0;
+  } else {
+    cfg = 1;
+  }
+  pl->cfg = cfg;
+  pl->bm = g_cfgs[cfg].bm; pl->bn = g_cfgs[cfg].bn; pl->bk = g_cfgs[cfg].bk;
+  pl->tiles_m = (p->M + pl->bm - 1) / pl->bm;
+  pl->tiles_n = (p->N + pl->bn - 1) / pl->bn;
+  if (pl->tiles_m > FLUX_MAX_M_TILES) return FLUX_ERR_UNSUPPORTED;
+  const long long tiles = (long long)pl->tiles_m * pl->tiles_n;
+  if (tiles > (1ll << 24)) return FLUX_ERR_UNSUPPORTED;
+  const int kt = (p->K + pl->bk - 1) / pl->bk;
+  int split = p->split_k;
+  if (split <= 0) {
+    split = 1;
+    if (p->M <= 64 && tiles < 512) {            // decode: put enough workgroups on B's stream
+      split = (int)std::min<long long>((512 + tiles - 1) / tiles, 16);
+      split = std::max(1, std::min(split, kt / 4));
+    }
+  }
+  split = std::max(1, std::min(split, kt));
+  const int kt_per = (kt + split - 1) / split;
+  split = (kt + kt_per - 1) / kt_per;             // no empty splits
+  if (split > 1 && tiles > MAX_SPLITK_TILES) return FLUX_ERR_UNSUPPORTED;
+  pl->split_k = split;
+  pl->k_per_split = kt_per * pl->bk;
+  pl->edge = (p->M % pl->bm != 0) || (p->N % pl->bn != 0) || (p->K % pl->bk != 0);
+  pl->n_xcd = (p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_NO_XCD_REMAP)) ? 1 : N_XCD;
+  pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
+  return FLUX_OK;
+}
+
+static void ring_order(int rank, int R, int* order) {
+  for (int d = 1; d < R; ++d) order[d - 1] = (rank + d) % R;
+}
+
+static int check_arrival(const flux_problem_t* p, const int32_t* arrival, int* order) {
+  if (arrival == nullptr) { ring_order(p->rank, p->R, order); return FLUX_OK; }
+  bool seen[FLUX_MAX_RANKS] = {false};
+  for (int i = 0; i < p->R - 1; ++i) {
+    const int c = arrival[i];
+    if (c < 0 || c >= p->R || c == p->rank || seen[c]) return FLUX_ERR_INVALID_ARG;
+    seen[c] = true;
+    order[i] = c;
+  }
+  return FLUX_OK;
+}
+
+// Order in which m-tiles are scheduled: every m-tile gets a key and tiles are sorted by
+// (key, index).  ReduceScatter: key = position of the owner of the tile's first row in the
+// ring that starts after the local rank and ends on it.  AllGather: key = latest position, in
+// [local chunk, arrival order...], among the chunks the tile's rows touch.
+static void build_tile_map(int op, const flux_problem_t* p, const Plan& pl, const int* arrival, TileMap* tm) {
+  tm->tiles_m = pl.tiles_m;
+  tm->tiles_n = pl.tiles_n;
+  tm->n_xcd = pl.n_xcd;
+  const int S = p->M / p->R;
+  if (p->flags & FLUX_FLAG_NO_SWIZZLE) {
+    tm->band_h = 1;
+    for (int t = 0; t < pl.tiles_m; ++t) tm->m_order[t] = (uint16_t)t;
+    return;
+  }
+  tm->band_h = (S % pl.bm == 0) ? S / pl.bm : 1;
+  int pos[FLUX_MAX_RANKS];
+  if (op == FLUX_OP_RS) {
+    for (int d = 1; d < p->R; ++d) pos[(p->rank + d) % p->R] = d - 1;
+    pos[p->rank] = p->R - 1;
+  } else {
+    pos[p->rank] = 0;
+    for (int i = 0; i < p->R - 1; ++i) pos[arrival[i]] = i + 1;
+  }
+  std::vector<std::pair<int, int>> keyed(pl.tiles_m);
+  for (int t = 0; t < pl.tiles_m; ++t) {
+    const int r0 = t * pl.bm;
+    const int r1 = std::min(p->M, r0 + pl.bm) - 1;
+    int key;
+    if (op == FLUX_OP_RS) {
+      key = pos[r0 / S];
+    } else {
+      key = 0;
+      for (int c = r0 / S; c <= r1 / S; ++c) key = std::max(key, pos[c]);
+    }
+    keyed[t] = {key, t};
+  }
+  std::sort(keyed.begin(), keyed.end());
+  for (int t = 0; t < pl.tiles_m; ++t) tm->m_order[t] = (uint16_t)keyed[t].second;
+}
+
+static size_t workspace_need(const Plan& pl) {
+  size_t need = WS_HEADER_BYTES;
+  if (pl.split_k > 1)
+    need += (size_t)pl.split_k * pl.tiles_m * pl.tiles_n * pl.bm * pl.bn * sizeof(float);
+  return need;
+}
+
+static int check_workspace(const Plan& pl, int op, const void* ws, size_t bytes) {
+  const bool needed = op == FLUX_OP_AG || pl.split_k > 1;
+  if (!needed) return FLUX_OK;
+  if (ws == nullptr || bytes < workspace_need(pl)) return FLUX_ERR_WORKSPACE;
+  if (!aligned16(ws)) return FLUX_ERR_INVALID_ARG;
+  return FLUX_OK;
+}
+
+static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, void* ws) {
+  std::memset(a, 0, sizeof(*a));
+  a->M = p->M; a->N = p->N; a->K = p->K;
+  a->R = p->R; a->rank = p->rank; a->S = p->M / p->R;
+  a->partial_f32 = p->partial_dtype == FLUX_F32;
+  a->out_f32 = p->out_dtype == FLUX_F32;
+  a->split_k = pl.split_k;
+  a->k_per_split = pl.k_per_split;
+  a->rows_per_signal = std::max(1, (p->M / p->R) / pl.ctpc);
+  a->timeout_ticks = p->spin_timeout_ticks ? p->spin_timeout_ticks : DEFAULT_TIMEOUT_TICKS;
+  if (ws != nullptr) {
+    unsigned char* w = static_cast<unsigned char*>(ws);
+    a->status = reinterpret_cast<uint32_t*>(w + WS_STATUS_OFF);
+    a->sk_counters = reinterpret_cast<uint32_t*>(w + WS_TILECNT_OFF);
+    a->sk_partials = reinterpret_cast<float*>(w + WS_HEADER_BYTES);
+  }
+}
+
+static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hipStream_t s) {
+  const int grid = pl.tiles_m * pl.tiles_n * pl.split_k;
+  FLUX_HIP(g_cfgs[pl.cfg].launch(epi, wait, pl.edge, a, grid, s));
+  return FLUX_OK;
+}
+
+static int clear_header(void* ws, hipStream_t s) {
+  const int words = (int)(WS_HEADER_BYTES / 4);
+  hipLaunchKernelGGL(preset_kernel, dim3((words + 255) / 256), dim3(256), 0, s,
+                     (uint32_t*)nullptr, 0, 0, 0, static_cast<uint32_t*>(ws), words);
+  FLUX_HIP(hipGetLastError());
+  return FLUX_OK;
+}
+
+static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* const* chunks, void* A_agg,
+                       const int* order, int n_order, uint32_t* signals, void* ws, hipStream_t s) {
+  if (n_order == 0) return FLUX_OK;
+  CopyArgs c;
+  std::memset(&c, 0, sizeof(c));
+  const unsigned long long chunk_vec = (unsigned long long)(p->M / p->R) * p->K / 8;
+  for (int r = 0; r < p->R; ++r) c.src[r] = static_cast<const uint4*>(chunks[r]);
+  c.dst = static_cast<uint4*>(A_agg);
+  for (int i = 0; i < n_order; ++i) c.order[i] = order[i];
+  c.n_order = n_order;
+  c.tiles_per_chunk = signals ? pl.ctpc : 1;
+  c.chunk_vec = chunk_vec;
+  c.tile_vec = chunk_vec / c.tiles_per_chunk;
+  c.signals = signals;
+  c.counters = ws ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_COUNTER_OFF) : nullptr;
+  int wgs = p->copy_workgroups;
+  if (wgs <= 0) wgs = signals ? 64 : 1024;
+  const unsigned long long max_useful = (c.tile_vec + 255) / 256;
+  if ((unsigned long long)wgs > max_useful) wgs = (int)std::max<unsigned long long>(1, max_useful);
+  hipLaunchKernelGGL(ag_copy_kernel, dim3(wgs), dim3(256), 0, s, c);
+  FLUX_HIP(hipGetLastError());
+  return FLUX_OK;
+}
+
+static std::mutex g_event_mu;
+static hipEvent_t g_fork = nullptr, g_join = nullptr;
+
+static int get_events(hipEvent_t* fork, hipEvent_t* join) {
+  std::lock_guard<std::mutex> lk(g_event_mu);
+  if (g_fork == nullptr) {
+    FLUX_HIP(hipEventCreateWithFlags(&g_fork, hipEventDisableTiming));
+    FLUX_HIP(hipEventCreateWithFlags(&g_join, hipEventDisableTiming));
+  }
+  *fork = g_fork;
+  *join = g_join;
+  return FLUX_OK;
+}
+
+}  // namespace flux
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+using namespace flux;
+
+extern "C" {
+
+int flux_version(void) { return 1; }
+
+int flux_last_hip_error(void) { return g_last_hip_error; }
+
+const char* flux_status_string(int status) {
+  switch (status) {
+    case FLUX_OK: return "ok";
+    case FLUX_ERR_INVALID_ARG: return "invalid argument";
+    case FLUX_ERR_SHAPE: return "unsupported shape";
+    case FLUX_ERR_UNSUPPORTED: return "unsupported request";
+    case FLUX_ERR_WORKSPACE: return "workspace missing or too small";
+    case FLUX_ERR_HIP: return "HIP runtime error";
+    case FLUX_ERR_TIMEOUT: return "signal wait timed out";
+    default: return "unknown status";
+  }
+}
+
+int flux_tile_config_count(void) { return NUM_CFGS; }
+
+int flux_tile_config_info(int32_t id, int32_t* tile_m, int32_t* tile_n, int32_t* tile_k) {
+  if (id < 1 || id > NUM_CFGS || !tile_m || !tile_n || !tile_k) return FLUX_ERR_INVALID_ARG;
+  *tile_m = g_cfgs[id - 1].bm; *tile_n = g_cfgs[id - 1].bn; *tile_k = g_cfgs[id - 1].bk;
+  return FLUX_OK;
+}
+
+int flux_default_order(int32_t rank, int32_t R, int32_t* order) {
+  if (R < 1 || R > FLUX_MAX_RANKS || rank < 0 || rank >= R || (R > 1 && order == nullptr)) return FLUX_ERR_INVALID_ARG;
+  ring_order(rank, R, order);
+  return FLUX_OK;
+}
+
+size_t flux_workspace_bytes(int op, const flux_problem_t* p) {
+  Plan pl;
+  if (make_plan(op, p, &pl) != FLUX_OK) return 0;
+  if (op == FLUX_OP_RS && pl.split_k <= 1) return 0;
+  return workspace_need(pl);
+}
+
+int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* tile_n, int32_t* tile_k,
+                    int32_t* split_k, int32_t* n_xcd) {
+  Plan pl;
+  int st = make_plan(op, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (tile_m) *tile_m = pl.bm;
+  if (tile_n) *tile_n = pl.bn;
+  if (tile_k) *tile_k = pl.bk;
+  if (split_k) *split_k = pl.split_k;
+  if (n_xcd) *n_xcd = pl.n_xcd;
+  return FLUX_OK;
+}
+
+int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_order, int32_t block,
+                    int32_t* m_tile, int32_t* n_tile) {
+  Plan pl;
+  int st = make_plan(op, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (!m_tile || !n_tile || block < 0 || block >= pl.tiles_m * pl.tiles_n) return FLUX_ERR_INVALID_ARG;
+  int order[FLUX_MAX_RANKS];
+  if (op == FLUX_OP_AG) {
+    st = check_arrival(p, arrival_order, order);
+    if (st != FLUX_OK) return st;
+  }
+  static thread_local TileMap tm;
+  build_tile_map(op, p, pl, order, &tm);
+  int mt, nt;
+  tile_coord(tm, block, mt, nt);
+  *m_tile = mt; *n_tile = nt;
+  return FLUX_OK;
+}
+
+int flux_query_status(const void* workspace, int32_t* code, int32_t* detail) {
+  if (workspace == nullptr || code == nullptr) return FLUX_ERR_INVALID_ARG;
+  uint32_t h[2] = {0, 0};
+  FLUX_HIP(hipMemcpy(h, static_cast<const unsigned char*>(workspace) + WS_STATUS_OFF, sizeof(h), hipMemcpyDeviceToHost));
+  *code = (int32_t)h[0];
+  if (detail) *detail = (int32_t)h[1];
+  return FLUX_OK;
+}
+
+int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const void* const* peer_partials,
+                 void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream) {
+  Plan pl;
+  int st = make_plan(FLUX_OP_RS, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (!A || !B || !peer_partials || !out_slices || !aligned16(A) || !aligned16(B)) return FLUX_ERR_INVALID_ARG;
+  for (int r = 0; r < p->R; ++r) {
+    if (!out_slices[r] || !aligned16(out_slices[r])) return FLUX_ERR_INVALID_ARG;
+    if (r != p->rank && (!peer_partials[r] || !aligned16(peer_partials[r]))) return FLUX_ERR_INVALID_ARG;
+  }
+  st = check_workspace(pl, FLUX_OP_RS, workspace, workspace_bytes);
+  if (st != FLUX_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  GemmArgs a;
+  fill_common(&a, p, pl, pl.split_k > 1 ? workspace : nullptr);
+  a.A = static_cast<const __bf16*>(A);
+  a.B = static_cast<const __bf16*>(B);
+  for (int r = 0; r < p->R; ++r) { a.peers[r] = peer_partials[r]; a.outs[r] = out_slices[r]; }
+  build_tile_map(FLUX_OP_RS, p, pl, nullptr, &a.tm);
+  if (pl.split_k > 1) { st = clear_header(workspace, s); if (st != FLUX_OK) return st; }
+  return launch_gemm(pl, EPI_RS, 0, a, s);
+}
+
+int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_agg, const void* B, void* C,
+                 uint32_t* signals, const int32_t* arrival_order, void* workspace, size_t workspace_bytes,
+                 void* compute_stream, void* copy_stream) {
+  Plan pl;
+  int st = make_plan(FLUX_OP_AG, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (!A_chunks || !A_agg || !B || !C || !signals || !aligned16(A_agg) || !aligned16(B) || !aligned16(C)) return FLUX_ERR_INVALID_ARG;
+  if (compute_stream == copy_stream) return FLUX_ERR_INVALID_ARG;
+  const size_t chunk_elems = (size_t)(p->M / p->R) * p->K;
+  if ((chunk_elems / pl.ctpc) % 8 != 0) return FLUX_ERR_SHAPE;
+  for (int r = 0; r < p->R; ++r)
+    if (!A_chunks[r] || !aligned16(A_chunks[r])) return FLUX_ERR_INVALID_ARG;
+  int order[FLUX_MAX_RANKS];
+  st = check_arrival(p, arrival_order, order);
+  if (st != FLUX_OK) return st;
+  st = check_workspace(pl, FLUX_OP_AG, workspace, workspace_bytes);
+  if (st != FLUX_OK) return st;
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+  hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+  hipEvent_t ev_fork, ev_join;
+  st = get_events(&ev_fork, &ev_join);
+  if (st != FLUX_OK) return st;
+
+  GemmArgs a;
+  fill_common(&a, p, pl, workspace);
+  a.A = static_cast<const __bf16*>(A_agg);
+  a.B = static_cast<const __bf16*>(B);
+  a.C = C;
+  a.signals = signals;
+  build_tile_map(FLUX_OP_AG, p, pl, order, &a.tm);
+
+  // preset: local signals 1, the rest 0; counters and status cleared
+  const int n_sig = p->R * pl.ctpc;
+  const int words = (int)(WS_HEADER_BYTES / 4);
+  hipLaunchKernelGGL(preset_kernel, dim3((std::max(words, n_sig) + 255) / 256), dim3(256), 0, cs,
+                     signals, n_sig, p->rank * pl.ctpc, (p->rank + 1) * pl.ctpc,
+                     static_cast<uint32_t*>(workspace), words);
+  FLUX_HIP(hipGetLastError());
+  // local chunk (its signal is preset, so it must be in place before the kernel starts)
+  const __bf16* local_dst = static_cast<const __bf16*>(A_agg) + (size_t)p->rank * chunk_elems;
+  if (A_chunks[p->rank] != static_cast<const void*>(local_dst)) {
+    int self = p->rank;
+    st = launch_copy(p, pl, A_chunks, A_agg, &self, 1, nullptr, nullptr, cs);
+    if (st != FLUX_OK) return st;
+  }
+  // fork: the copy driver may start once everything queued so far on compute_stream is done
+  FLUX_HIP(hipEventRecord(ev_fork, cs));
+  FLUX_HIP(hipStreamWaitEvent(xs, ev_fork, 0));
+  if (p->flags & FLUX_FLAG_COPY_MEMCPY) {
+    const size_t tile_bytes = chunk_elems * 2 / pl.ctpc;
+    for (int i = 0; i < p->R - 1; ++i) {
+      const int c = order[i];
+      for (int t = 0; t < pl.ctpc; ++t) {
+        const unsigned char* src = static_cast<const unsigned char*>(A_chunks[c]) + (size_t)t * tile_bytes;
+        unsigned char* dst = static_cast<unsigned char*>(A_agg) + ((size_t)c * pl.ctpc + t) * tile_bytes;
+        FLUX_HIP(hipMemcpyAsync(dst, src, tile_bytes, hipMemcpyDeviceToDevice, xs));
+        FLUX_HIP(hipStreamWriteValue32(xs, signals + c * pl.ctpc + t, 1u, 0));
+      }
+    }
+  } else {
+    st = launch_copy(p, pl, A_chunks, A_agg, order, p->R - 1, signals, workspace, xs);
+    if (st != FLUX_OK) return st;
+  }
+  st = launch_gemm(pl, EPI_PLAIN, 1, a, cs);
+  if (st != FLUX_OK) return st;
+  // join + reset of the signals, ordered after both the GEMM and the copy driver
+  FLUX_HIP(hipEventRecord(ev_join, xs));
+  FLUX_HIP(hipStreamWaitEvent(cs, ev_join, 0));
+  hipLaunchKernelGGL(preset_kernel, dim3((n_sig + 255) / 256), dim3(256), 0, cs,
+                     signals, n_sig, p->rank * pl.ctpc, (p->rank + 1) * pl.ctpc, (uint32_t*)nullptr, 0);
+  FLUX_HIP(hipGetLastError());
+  return FLUX_OK;
+}
+
+int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const void* A, const void* const* A_chunks,
+                          void* A_agg, const void* B, const void* const* peer_partials, void* const* out_slices,
+                          void* C, void* workspace, size_t workspace_bytes, void* stream) {
+  Plan pl;
+  int st = make_plan(op, p, &pl);
+  if (st != FLUX_OK) return st;
+  if ((phases & (FLUX_PHASE_GEMM | FLUX_PHASE_COMM)) == 0 || (phases & ~(FLUX_PHASE_GEMM | FLUX_PHASE_COMM))) return FLUX_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool do_gemm = phases & FLUX_PHASE_GEMM, do_comm = phases & FLUX_PHASE_COMM;
+  if (!C || !aligned16(C)) return FLUX_ERR_INVALID_ARG;
+  if (do_gemm) {
+    if (!B || !aligned16(B)) return FLUX_ERR_INVALID_ARG;
+    if (pl.split_k > 1) {
+      if (workspace == nullptr || workspace_bytes < workspace_need(pl)) return FLUX_ERR_WORKSPACE;
+    }
+  }
+  GemmArgs a;
+  fill_common(&a, p, pl, pl.split_k > 1 ? workspace : nullptr);
+  a.B = static_cast<const __bf16*>(B);
+  a.C = C;
+  // natural tile order for the baseline GEMM, die remap kept
+  flux_problem_t q = *p;
+  q.flags |= FLUX_FLAG_NO_SWIZZLE;
+  Plan plq = pl;
+  build_tile_map(op, &q, plq, nullptr, &a.tm);
+  a.tm.n_xcd = pl.n_xcd;
+  a.tm.band_h = 1;
+
+  if (op == FLUX_OP_RS) {
+    if (do_gemm) {
+      if (!A || !aligned16(A)) return FLUX_ERR_INVALID_ARG;
+      a.A = static_cast<const __bf16*>(A);
+      if (pl.split_k > 1) { st = clear_header(workspace, s); if (st != FLUX_OK) return st; }
+      st = launch_gemm(pl, EPI_PLAIN, 0, a, s);
+      if (st != FLUX_OK) return st;
+    }
+    if (do_comm) {
+      if (!peer_partials || !out_slices) return FLUX_ERR_INVALID_ARG;
+      ReduceArgs r;
+      std::memset(&r, 0, sizeof(r));
+      for (int j = 0; j < p->R; ++j) {
+        if (!out_slices[j] || !aligned16(out_slices[j])) return FLUX_ERR_INVALID_ARG;
+        if (j != p->rank && (!peer_partials[j] || !aligned16(peer_partials[j]))) return FLUX_ERR_INVALID_ARG;
+        r.peers[j] = peer_partials[j];
+        r.outs[j] = out_slices[j];
+      }
+      r.C = C; r.M = p->M; r.N = p->N; r.R = p->R; r.rank = p->rank; r.S = p->M / p->R;
+      r.partial_f32 = p->partial_dtype == FLUX_F32;
+      r.out_f32 = p->out_dtype == FLUX_F32;
+      const long long nvec = (long long)p->M * p->N / 8;
+      const int grid = (int)std::min<long long>((nvec + 255) / 256, 256 * 8);
+      hipLaunchKernelGGL(rs_reduce_kernel, dim3(grid), dim3(256), 0, s, r);
+      FLUX_HIP(hipGetLastError());
+    }
+    return FLUX_OK;
+  }
+  // AllGather: copy every chunk, then the GEMM
+  if (!A_agg || !aligned16(A_agg)) return FLUX_ERR_INVALID_ARG;
+  if (do_comm) {
+    if (!A_chunks) return FLUX_ERR_INVALID_ARG;
+    int order[FLUX_MAX_RANKS];
+    int n = 0;
+    const size_t chunk_elems = (size_t)(p->M / p->R) * p->K;
+    if (chunk_elems % 8 != 0) return FLUX_ERR_SHAPE;
+    for (int r = 0; r < p->R; ++r) {
+      if (!A_chunks[r] || !aligned16(A_chunks[r])) return FLUX_ERR_INVALID_ARG;
+      const void* dst = static_cast<const __bf16*>(A_agg) + (size_t)r * chunk_elems;
+      if (A_chunks[r] != dst) order[n++] = r;
+    }
+    st = launch_copy(p, pl, A_chunks, A_agg, order, n, nullptr, nullptr, s);
+    if (st != FLUX_OK) return st;
+  }
+  if (do_gemm) {
+    a.A = static_cast<const __bf16*>(A_agg);
+    if (pl.split_k > 1) { st = clear_header(workspace, s); if (st != FLUX_OK) return st; }
+    st = launch_gemm(pl, EPI_PLAIN, 0, a, s);
+    if (st != FLUX_OK) return st;
+  }
+  return FLUX_OK;
+}
+
+}  // extern "C"

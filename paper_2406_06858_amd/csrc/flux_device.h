@@ -1,0 +1,420 @@
+// Device-side building blocks of the fused tensor-parallel GEMM kernels (gfx950 / CDNA4).
+//
+// One templated kernel serves the three entry points; what differs is the prologue
+// (AllGather-GEMM waits on signals, paper Alg. 2) and the epilogue (GEMM-ReduceScatter adds
+// the peer partial tiles and writes each row into its owner's slice, paper Alg. 1).
+//
+// Mapping to the hardware:
+//   * bf16 inputs, v_mfma_f32_32x32x16_bf16, fp32 accumulators kept in registers;
+//   * A tile [BM][BK] and B tile [BK][BN] staged in LDS with XOR-swizzled 16-byte slots;
+//     A fragments are read with ds_read_b128, B fragments (B is [K,N] row-major, so a lane
+//     needs 8 consecutive k of one column) with the transposing ds_read_b64_tr_b16;
+//   * 128-bit global loads into registers for tile t+1 while tile t is multiplied;
+//   * the accumulators go through LDS once in the epilogue so that every lane owns 8
+//     consecutive columns of a row: peer partials are read and outputs written 16 B (bf16)
+//     or 32 B (fp32) per lane, 128..512 B contiguous per row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "flux.h"
+
+namespace flux {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+// ---- workspace layout (bytes) -------------------------------------------------------------
+constexpr size_t WS_STATUS_OFF = 0;        // uint32 code, uint32 detail
+constexpr size_t WS_COUNTER_OFF = 256;     // uint32 per communication tile (copy kernel arrivals)
+constexpr int MAX_COMM_TILES = 1024;
+constexpr size_t WS_TILECNT_OFF = WS_COUNTER_OFF + 4 * MAX_COMM_TILES;   // split-K arrival counters
+constexpr int MAX_SPLITK_TILES = 4096;
+constexpr size_t WS_HEADER_BYTES = WS_TILECNT_OFF + 4 * MAX_SPLITK_TILES; // split-K partials follow
+
+// ---- TileCoord (paper Sec. 4.1) -----------------------------------------------------------
+// The host builds `m_order`: the order in which m-tiles are scheduled (slice by slice after
+// the local rank for ReduceScatter, chunk by chunk in arrival order for AllGather).  Ascending
+// workgroup ids walk that order in bands of `band_h` m-tiles times all n-tiles, m fastest.
+// Workgroups are dealt round-robin to the accelerator dies, so with n_xcd > 1 the in-band index
+// is regrouped to give every die a contiguous run of the band (shared panels stay in its L2).
+struct TileMap {
+  int32_t tiles_m, tiles_n, band_h, n_xcd;
+  uint16_t m_order[FLUX_MAX_M_TILES];
+};
+
+__host__ __device__ inline void tile_coord(const TileMap& tm, int block, int& mt, int& nt) {
+  const int band_sz = tm.band_h * tm.tiles_n;
+  const int band = block / band_sz;
+  int q = block - band * band_sz;
+  if (tm.n_xcd > 1 && band_sz % tm.n_xcd == 0) q = (q % tm.n_xcd) * (band_sz / tm.n_xcd) + q / tm.n_xcd;
+  const int i = band * tm.band_h + q % tm.band_h;
+  nt = q / tm.band_h;
+  mt = tm.m_order[i];
+}
+
+enum : int { EPI_PLAIN = 0, EPI_RS = 1 };
+
+struct GemmArgs {
+  const __bf16* A;           // [M,K]
+  const __bf16* B;           // [K,N]
+  int32_t M, N, K;
+  // plain epilogue
+  void* C;                   // [M,N] of out dtype
+  // reduce-scatter epilogue
+  const void* peers[FLUX_MAX_RANKS];
+  void* outs[FLUX_MAX_RANKS];
+  int32_t R, rank, S;        // S = M / R
+  int32_t partial_f32, out_f32;
+  // all-gather prologue
+  const uint32_t* signals;
+  int32_t rows_per_signal;
+  uint32_t* status;
+  unsigned long long timeout_ticks;
+  // split-K
+  int32_t split_k, k_per_split;   // k_per_split is a multiple of BK
+  float* sk_partials;             // [split_k][tiles][BM*BN] fp32
+  uint32_t* sk_counters;          // [tiles]
+  TileMap tm;
+};
+
+// ---- LDS swizzles ---------------------------------------------------------------------------
+// A tile: rows of BK bf16 = BK/8 slots of 16 B; slot s of row r is stored at slot s ^ fA(r).
+// With 128-byte rows, 8 (or 16) consecutive rows read the same logical slot in one
+// ds_read_b128 pass; fA spreads them over all banks for both a 128 B and a 256 B wide LDS.
+template <int SLOTS>
+__device__ __forceinline__ int swz_a(int row) {
+  return ((row & 7) ^ ((row >> 3) & 1)) & (SLOTS - 1);
+}
+// B tile: rows of BN bf16 (one k each); the transposing read touches 4 consecutive k rows at
+// the same columns, so rows k..k+3 are pushed to different 64-byte (and 32-byte) bank groups.
+template <int SLOTS>
+__device__ __forceinline__ int swz_b(int k) {
+  const int kk = k & 3;
+  return ((kk << 2) ^ (kk << 1)) & (SLOTS - 1);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 h = __builtin_convertvector(v, bf16x2);   // round-to-nearest-even
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int OCC_>
+struct TileCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int NSTAGE = NSTAGE_, OCC = OCC_;
+  static constexpr int NT = WAVES_M * WAVES_N * 64;
+  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  static constexpr int MI = WTM / 32, NI = WTN / 32;
+  static constexpr int A_SLOTS = BK / 8, B_SLOTS = BN / 8;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int A_VEC = BM * BK / 8 / NT, B_VEC = BK * BN / 8 / NT;
+  static constexpr int EP_STRIDE = WTN + 8;                       // floats; 4 rows apart = 128 B off
+  static constexpr int EP_BYTES = WAVES_M * WAVES_N * 32 * EP_STRIDE * 4;
+  static constexpr int MAIN_BYTES = NSTAGE * STAGE_BYTES > EP_BYTES ? NSTAGE * STAGE_BYTES : EP_BYTES;
+  static constexpr int MISC_OFF = MAIN_BYTES;              // 16 B: one int shared by the workgroup
+  static constexpr int PTRS_OFF = MAIN_BYTES + 16;         // FLUX_MAX_RANKS output slice pointers
+  static constexpr int LDS_BYTES = PTRS_OFF + 8 * FLUX_MAX_RANKS;
+  static_assert(BM % (WAVES_M * 32) == 0 && BN % (WAVES_N * 32) == 0 && BK % 16 == 0, "tile shape");
+  static_assert((BM * BK / 8) % NT == 0 && (BK * BN / 8) % NT == 0, "loader shape");
+  static_assert(B_SLOTS >= 8, "BN >= 64");
+};
+
+template <class C, bool EDGE>
+struct Loader {
+  // per-thread global pointers of the 16-byte vectors this thread stages, k offset 0
+  const __bf16* pa[C::A_VEC];
+  const __bf16* pb[C::B_VEC];
+  int lds_a[C::A_VEC], lds_b[C::B_VEC];
+  int ka[C::A_VEC];            // column (k) offset of each A vector inside the tile
+  int kb[C::B_VEC];            // row (k) offset of each B vector inside the tile
+  bool nb_ok[C::B_VEC];
+
+  __device__ __forceinline__ void init(const GemmArgs& a, int m0, int n0, int tid) {
+#pragma unroll
+    for (int p = 0; p < C::A_VEC; ++p) {
+      const int v = tid + C::NT * p;
+      const int row = v / C::A_SLOTS, slot = v % C::A_SLOTS;
+      int gr = m0 + row;
+      if (EDGE) gr = gr < a.M ? gr : a.M - 1;
+      pa[p] = a.A + (size_t)gr * a.K + slot * 8;
+      ka[p] = slot * 8;
+      lds_a[p] = row * (C::BK * 2) + ((slot ^ swz_a<C::A_SLOTS>(row)) << 4);
+    }
+#pragma unroll
+    for (int p = 0; p < C::B_VEC; ++p) {
+      const int v = tid + C::NT * p;
+      const int k = v / C::B_SLOTS, s = v % C::B_SLOTS;
+      int gn = n0 + s * 8;
+      nb_ok[p] = !EDGE || gn < a.N;
+      if (EDGE && gn >= a.N) gn = 0;
+      pb[p] = a.B + (size_t)k * a.N + gn;
+      kb[p] = k;
+      lds_b[p] = C::A_BYTES + k * (C::BN * 2) + ((s ^ swz_b<C::B_SLOTS>(k)) << 4);
+    }
+  }
+
+  __device__ __forceinline__ void load(const GemmArgs& a, int k0, int k_end, uint4 (&ra)[C::A_VEC], uint4 (&rb)[C::B_VEC]) const {
+#pragma unroll
+    for (int p = 0; p < C::A_VEC; ++p) {
+      if (!EDGE || k0 + ka[p] < k_end) ra[p] = *reinterpret_cast<const uint4*>(pa[p] + k0);
+      else ra[p] = make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int p = 0; p < C::B_VEC; ++p) {
+      if (!EDGE || (nb_ok[p] && k0 + kb[p] < k_end)) rb[p] = *reinterpret_cast<const uint4*>(pb[p] + (size_t)k0 * a.N);
+      else rb[p] = make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  __device__ __forceinline__ void store(unsigned char* stage, const uint4 (&ra)[C::A_VEC], const uint4 (&rb)[C::B_VEC]) const {
+#pragma unroll
+    for (int p = 0; p < C::A_VEC; ++p) *reinterpret_cast<uint4*>(stage + lds_a[p]) = ra[p];
+#pragma unroll
+    for (int p = 0; p < C::B_VEC; ++p) *reinterpret_cast<uint4*>(stage + lds_b[p]) = rb[p];
+  }
+};
+
+// One BK-deep slab of MFMAs out of the LDS stage.
+template <class C>
+__device__ __forceinline__ void mma_stage(const unsigned char* stage, int wm, int wn, int lane,
+                                          f32x16 (&acc)[C::MI][C::NI]) {
+  const int g = lane >> 4, i = lane & 15;
+#pragma unroll
+  for (int ks = 0; ks < C::BK / 16; ++ks) {
+    bf16x8 af[C::MI], bfr[C::NI];
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi) {
+      const int row = wm * C::WTM + mi * 32 + (lane & 31);
+      const int q = ks * 2 + (lane >> 5);
+      af[mi] = *reinterpret_cast<const bf16x8*>(stage + row * (C::BK * 2) + ((q ^ swz_a<C::A_SLOTS>(row)) << 4));
+    }
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni) {
+      const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
+      const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);
+      const int off = C::A_BYTES + k * (C::BN * 2) + ((((n >> 3) ^ swz_b<C::B_SLOTS>(k))) << 4) + ((n >> 2) & 1) * 8;
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off + 4 * C::BN * 2));
+      s16x8 w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      bfr[ni] = __builtin_bit_cast(bf16x8, w);
+    }
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+  }
+}
+
+// 8 consecutive output columns of one row: add the peer partials (ascending rank), convert
+// once, store into the owner's slice (GetOutput + Reduce of Alg. 1) or into C.
+template <int EPI>
+__device__ __forceinline__ void epilogue_row8(const GemmArgs& a, void* const* lds_outs, int gm, int gn, float (&v)[8]) {
+  if (EPI == EPI_RS) {
+    const size_t off = (size_t)gm * a.N + gn;
+    // constant indices only: a run-time index into the by-value argument block would force a
+    // private-memory copy of it
+    if (a.partial_f32) {
+#pragma unroll
+      for (int j = 0; j < FLUX_MAX_RANKS; ++j)
+        if (j < a.R && j != a.rank) {
+          const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.peers[j]) + off);
+          const float4 x = p[0], y = p[1];
+          v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
+          v[4] += y.x; v[5] += y.y; v[6] += y.z; v[7] += y.w;
+        }
+    } else {
+      uint4 w[FLUX_MAX_RANKS];
+#pragma unroll
+      for (int j = 0; j < FLUX_MAX_RANKS; ++j)
+        if (j < a.R && j != a.rank) w[j] = *reinterpret_cast<const uint4*>(static_cast<const __bf16*>(a.peers[j]) + off);
+#pragma unroll
+      for (int j = 0; j < FLUX_MAX_RANKS; ++j)
+        if (j < a.R && j != a.rank) {
+          v[0] += bf16_lo(w[j].x); v[1] += bf16_hi(w[j].x);
+          v[2] += bf16_lo(w[j].y); v[3] += bf16_hi(w[j].y);
+          v[4] += bf16_lo(w[j].z); v[5] += bf16_hi(w[j].z);
+          v[6] += bf16_lo(w[j].w); v[7] += bf16_hi(w[j].w);
+        }
+    }
+  }
+  void* base;
+  size_t o;
+  if (EPI == EPI_RS) {
+    const int r = gm / a.S;
+    base = lds_outs[r];
+    o = (size_t)(gm - r * a.S) * a.N + gn;
+  } else {
+    base = a.C;
+    o = (size_t)gm * a.N + gn;
+  }
+  if (a.out_f32) {
+    float4* q = reinterpret_cast<float4*>(static_cast<float*>(base) + o);
+    q[0] = make_float4(v[0], v[1], v[2], v[3]);
+    q[1] = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    uint4 w;
+    w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
+    w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4*>(static_cast<__bf16*>(base) + o) = w;
+  }
+}
+
+// WaitSignal (Alg. 2): one lane polls every signal covering rows [m0, m1) with coherent loads,
+// then an acquire fence makes the copied rows visible; the workgroup barrier hands that to the
+// other waves.  Bounded: past `timeout_ticks` the tile is given up and the status block says so.
+__device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, int* lds_ok) {
+  if (threadIdx.x == 0) {
+    const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
+    int ok = 1;
+    const unsigned long long t0 = wall_clock64();
+    for (int f = f0; f <= f1 && ok; ++f) {
+      while (__hip_atomic_load(a.signals + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u) {
+        __builtin_amdgcn_s_sleep(16);
+        if (wall_clock64() - t0 > a.timeout_ticks) {
+          if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)f;
+          ok = 0;
+          break;
+        }
+      }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);   // system scope: covers copy kernels and DMA writers
+    *lds_ok = ok;
+  }
+  __syncthreads();
+  return *lds_ok != 0;
+}
+
+template <class C, int EPI, bool WAIT, bool EDGE>
+__global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+
+  const int ntiles = a.tm.tiles_m * a.tm.tiles_n;
+  const int tile = (int)blockIdx.x % ntiles;
+  const int split = (int)blockIdx.x / ntiles;
+  int mt, nt;
+  tile_coord(a.tm, tile, mt, nt);
+  const int m0 = mt * C::BM, n0 = nt * C::BN;
+  const int m1 = m0 + C::BM < a.M ? m0 + C::BM : a.M;
+
+  void** lds_outs = reinterpret_cast<void**>(smem + C::PTRS_OFF);
+  if (EPI == EPI_RS) {
+#pragma unroll
+    for (int j = 0; j < FLUX_MAX_RANKS; ++j)
+      if (tid == j) lds_outs[j] = a.outs[j];     // made visible by the main loop's barriers
+  }
+
+  if (WAIT) {
+    if (!wait_signals(a, m0, m1, reinterpret_cast<int*>(smem + C::MISC_OFF))) return;
+  }
+
+  const int k_begin = split * a.k_per_split;
+  const int k_end = (k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
+  const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
+
+  f32x16 acc[C::MI][C::NI];
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
+
+  Loader<C, EDGE> ld;
+  ld.init(a, m0, n0, tid);
+  uint4 ra[C::A_VEC], rb[C::B_VEC];
+
+  if (KT > 0) {
+    ld.load(a, k_begin, k_end, ra, rb);
+    ld.store(smem, ra, rb);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+      unsigned char* cur = smem + (C::NSTAGE == 2 ? (kt & 1) * C::STAGE_BYTES : 0);
+      const bool more = kt + 1 < KT;
+      if (more) ld.load(a, k_begin + (kt + 1) * C::BK, k_end, ra, rb);
+      mma_stage<C>(cur, wm, wn, lane, acc);
+      if (C::NSTAGE == 1) __syncthreads();
+      if (more) ld.store(smem + (C::NSTAGE == 2 ? ((kt + 1) & 1) * C::STAGE_BYTES : 0), ra, rb);
+      __syncthreads();
+    }
+  }
+
+  // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
+  if (a.split_k > 1) {
+    float* mine = a.sk_partials + ((size_t)split * ntiles + tile) * (C::BM * C::BN);
+    // layout inside a tile's partial block: [mi][ni][e][thread] -> coalesced 4-byte columns
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          mine[((mi * C::NI + ni) * 16 + e) * C::NT + tid] = acc[mi][ni][e];
+    __threadfence();
+    __syncthreads();
+    int* lds_last = reinterpret_cast<int*>(smem + C::MISC_OFF);
+    if (tid == 0) {
+      const uint32_t prev = atomicAdd(a.sk_counters + tile, 1u);
+      const int last = prev == (uint32_t)(a.split_k - 1);
+      if (last) a.sk_counters[tile] = 0u;     // ready for the next launch
+      *lds_last = last;
+    }
+    __syncthreads();
+    if (!*lds_last) return;
+    __threadfence();
+    for (int s = 0; s < a.split_k; ++s) {
+      if (s == split) continue;
+      const float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            acc[mi][ni][e] += __builtin_nontemporal_load(other + ((mi * C::NI + ni) * 16 + e) * C::NT + tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: registers -> LDS (per wave, 32 rows at a time) -> 8 columns per lane ----
+  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * C::EP_STRIDE);
+  constexpr int CH = C::WTN / 8;          // 8-column chunks per row of the wave tile
+  constexpr int RPP = 64 / CH;            // rows per pass
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
+      }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 32 / RPP; ++it) {
+      const int r = it * RPP + lane / CH, cc = lane % CH;
+      const float4 x = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8);
+      const float4 y = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8 + 4);
+      float v[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+      const int gm = m0 + wm * C::WTM + mi * 32 + r;
+      const int gn = n0 + wn * C::WTN + cc * 8;
+      if (!EDGE || (gm < a.M && gn < a.N)) epilogue_row8<EPI>(a, lds_outs, gm, gn, v);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+}  // namespace flux

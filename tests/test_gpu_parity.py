@@ -1,0 +1,335 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Placement and exact-integer cases are bit-exact; floating-point cases use
+|gpu - ref64| <= tol * max(1, |ref64|) with tol = 1e-2 (bf16 out) or 1e-5 (fp32 variant)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import flux_oracle as fo
+from paper_2406_06858_amd import binding as fb
+from paper_2406_06858_amd import inputs as fi
+
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+
+W = fi.WORKLOADS
+ALL_CFGS = [1, 2, 3, 4, 5, 6]
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# c1: the small fp32 case, every rank, forced 64x64 tiles and every other configuration
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rank", [0, 1])
+@pytest.mark.parametrize("cfg", [4, 0, 1, 3])
+def test_c1_rs_fp32_variant(rank, cfg):
+    w = W["c1_rs"]
+    _say("c1_rs rank", rank, "cfg", cfg)
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg)
+    s64, _ = gh.oracle_rs(w, rank, A, B, peers)
+    for r in range(w.R):
+        gh.assert_close(outs[r], s64[r], "f32", f"slice {r}")
+
+
+# ---------------------------------------------------------------------------------------------
+# exact-integer inputs: every partial sum is an integer < 2^24, so fp32 and fp64 agree exactly
+# and the single bf16 rounding is unique -> whole outputs compared bitwise
+# ---------------------------------------------------------------------------------------------
+
+INT_RS = fi.Workload("int_rs", "rs", 640, 384, 320, 4, a_dist=("int", 2), b_dist=("int", 2),
+                     peer_dist=("int", 8), seed=77)
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS)
+@pytest.mark.parametrize("pd,od", [("bf16", "bf16"), ("f32", "f32"), ("bf16", "f32")])
+def test_rs_exact_integers_bitwise(cfg, pd, od):
+    w = fi.scaled(INT_RS, partial_dtype=pd, out_dtype=od)
+    for rank in (0, 3):
+        _say("int_rs cfg", cfg, pd, od, "rank", rank)
+        A, B, peers = fi.make_rs_inputs(w, rank)
+        outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg)
+        _, want = gh.oracle_rs(w, rank, A, B, peers)
+        for r in range(w.R):
+            gh.assert_bits_equal(outs[r], want[r], f"cfg {cfg} slice {r}")
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS)
+def test_rs_ragged_shapes_bitwise(cfg):
+    # M, N, K are multiples of neither tile size; slice height 125 straddles tiles
+    w = fi.Workload("int_rs_ragged", "rs", 1000, 520, 200, 8, a_dist=("int", 2), b_dist=("int", 2),
+                    peer_dist=("int", 8), seed=78)
+    rank = 5
+    _say("ragged rs cfg", cfg)
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg)
+    _, want = gh.oracle_rs(w, rank, A, B, peers)
+    for r in range(w.R):
+        gh.assert_bits_equal(outs[r], want[r], f"slice {r}")
+
+
+@pytest.mark.parametrize("cfg", ALL_CFGS)
+def test_ag_exact_integers_bitwise(cfg):
+    w = fi.Workload("int_ag", "ag", 768, 320, 448, 4, a_dist=("int", 2), b_dist=("int", 2), seed=79)
+    for rank in (0, 2):
+        _say("int_ag cfg", cfg, "rank", rank)
+        chunks, B, arrival = fi.make_ag_inputs(w, rank)
+        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=cfg)
+        assert status == (fb.FLUX_OK, 0)
+        _, want = gh.oracle_ag(w, chunks, B)
+        gh.assert_bits_equal(Cg, want, f"cfg {cfg}")
+        # A_agg is the row-wise concatenation of the chunks, bit for bit
+        gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+        # signals are left in the preset state: local 1, the others 0
+        assert signals.cpu().tolist() == [1 if c == rank else 0 for c in range(w.R)]
+
+
+def test_rs_placement_probe():
+    """A.B carries the global row index, peers are zero: every output element says which global
+    row it came from; all R slices, every row, bit-exact."""
+    M, N, K, R, rank = 512, 256, 256, 8, 6
+    w = fi.Workload("probe", "rs", M, N, K, R, partial_dtype="f32", out_dtype="f32")
+    A = torch.zeros(M, K)
+    A[torch.arange(M), torch.arange(M) % K] = torch.arange(M, dtype=torch.float32) % 251   # exact in bf16
+    B = torch.ones(K, N)
+    peers = [None if j == rank else torch.zeros(M, N) for j in range(R)]
+    outs = gh.run_rs(w, rank, A.bfloat16(), B.bfloat16(), peers)
+    for r in range(R):
+        want = ((torch.arange(w.S) + r * w.S) % 251).to(torch.float32)[:, None].expand(w.S, N)
+        assert torch.equal(outs[r].cpu(), want), f"slice {r}"
+
+
+# ---------------------------------------------------------------------------------------------
+# floating-point parity at reduced and full sizes
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,shrink", [("c3_rs", dict(M=1024, N=1024, K=768)), ("c4_rs", dict(M=2048, N=1536, K=512))])
+def test_rs_reduced_size_all_elements(name, shrink):
+    w = fi.scaled(W[name], **shrink)
+    for rank, cfg in ((0, 0), (5, 1), (7, 2), (2, 3)):
+        _say(name, "reduced rank", rank, "cfg", cfg)
+        A, B, peers = fi.make_rs_inputs(w, rank)
+        outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg)
+        s64, _ = gh.oracle_rs(w, rank, A, B, peers)
+        for r in range(w.R):
+            gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+
+
+@pytest.mark.parametrize("name,shrink", [("c2_ag", dict(M=1024, N=896, K=1024)), ("c4_ag", dict(M=2048, N=768, K=1536))])
+def test_ag_reduced_size_all_elements(name, shrink):
+    w = fi.scaled(W[name], **shrink)
+    for rank, cfg in ((0, 0), (3, 1), (7, 2), (4, 3)):
+        _say(name, "reduced rank", rank, "cfg", cfg)
+        chunks, B, arrival = fi.make_ag_inputs(w, rank)
+        Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=cfg)
+        assert status == (fb.FLUX_OK, 0)
+        C64, _ = gh.oracle_ag(w, chunks, B)
+        gh.assert_close(Cg, C64, w.out_dtype)
+
+
+def _sample_rows(M, S, n_per_slice, seed):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for r in range(M // S):
+        picks = set(rng.integers(0, S, n_per_slice).tolist()) | {0, S - 1}
+        rows += [r * S + i for i in sorted(picks)]
+    return rows
+
+
+@pytest.mark.parametrize("name", ["c3_rs", "c4_rs"])
+def test_rs_full_size_sampled_rows(name):
+    """Full benchmark shape in the launch configuration the benchmark uses; the oracle
+    evaluates a seeded sample of complete rows in every slice (first and last row included)."""
+    w = W[name]
+    rank = 3
+    _say(name, "full size: generating inputs")
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    _say(name, "running")
+    outs = gh.run_rs(w, rank, A, B, peers)
+    rows = _sample_rows(w.M, w.S, 6, 5)
+    _say(name, "oracle on", len(rows), "rows")
+    ref = fo.gemm_rs_rows(fi.to_numpy(A), fi.to_numpy(B), [None if t is None else fi.to_numpy(t) for t in peers],
+                          w.R, rank, w.partial_dtype, rows)
+    for owner, lr, vals in ref:
+        gh.assert_close(outs[owner][lr], vals, w.out_dtype, f"slice {owner} row {lr}")
+    # property that holds at any size: no element was left unwritten (outputs start as NaN)
+    for r in range(w.R):
+        assert not torch.isnan(outs[r]).any()
+
+
+@pytest.mark.parametrize("name", ["c2_ag", "c4_ag"])
+def test_ag_full_size_sampled_rows(name):
+    w = W[name]
+    rank = 2
+    _say(name, "full size: generating inputs")
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    _say(name, "running, arrival order", arrival)
+    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival)
+    assert status == (fb.FLUX_OK, 0)
+    rows = _sample_rows(w.M, w.S, 6, 6)
+    _say(name, "oracle on", len(rows), "rows")
+    ref = fo.ag_gemm_rows([fi.to_numpy(c) for c in chunks], fi.to_numpy(B), rows)
+    gh.assert_close(Cg[rows], ref, w.out_dtype)
+    assert not torch.isnan(Cg).any()
+    assert torch.equal(A_agg.view(torch.int16).cpu(), torch.cat(chunks).view(torch.int16))
+
+
+@pytest.mark.parametrize("M", [8, 64, 256])
+@pytest.mark.parametrize("op", ["ag", "rs"])
+def test_decode_shapes_all_elements(op, M):
+    w = W[f"c5_{op}_m{M}"]
+    rank = 1
+    _say(w.name)
+    if op == "rs":
+        A, B, peers = fi.make_rs_inputs(w, rank)
+        outs = gh.run_rs(w, rank, A, B, peers)
+        s64, _ = gh.oracle_rs(w, rank, A, B, peers)
+        for r in range(w.R):
+            gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+    else:
+        chunks, B, arrival = fi.make_ag_inputs(w, rank)
+        Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival)
+        assert status == (fb.FLUX_OK, 0)
+        C64, _ = gh.oracle_ag(w, chunks, B)
+        gh.assert_close(Cg, C64, w.out_dtype)
+
+
+@pytest.mark.parametrize("split", [2, 3, 7])
+def test_split_k_bitwise_on_integers(split):
+    w = fi.Workload("int_rs_split", "rs", 64, 512, 1024, 8, a_dist=("int", 2), b_dist=("int", 2),
+                    peer_dist=("int", 8), seed=80)
+    rank = 4
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    _, want = gh.oracle_rs(w, rank, A, B, peers)
+    for cfg in (5, 6, 4):
+        _say("split-k", split, "cfg", cfg)
+        for rep in range(2):        # second launch reuses the counters the first one reset
+            outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg, split_k=split)
+            for r in range(w.R):
+                gh.assert_bits_equal(outs[r], want[r], f"slice {r}")
+
+
+# ---------------------------------------------------------------------------------------------
+# AllGather protocol: orders, signals, copy engines, timing
+# ---------------------------------------------------------------------------------------------
+
+AG_SMALL = fi.scaled(W["c2_ag"], M=2048, N=512, K=512)
+
+
+@pytest.mark.parametrize("order", ["ring", "reversed", "random"])
+@pytest.mark.parametrize("flags", [0, fb.FLUX_FLAG_COPY_MEMCPY, fb.FLUX_FLAG_NO_SWIZZLE])
+def test_ag_arrival_orders_and_copy_engines(order, flags):
+    w = AG_SMALL
+    rank = 5
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    if order == "ring":
+        arrival = None
+    elif order == "reversed":
+        arrival = list(reversed(fo.default_order(rank, w.R)))
+    _say("ag order", order, "flags", flags)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    for ctpc in (0, 2, 4):
+        Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, flags=flags, comm_tiles_per_chunk=ctpc,
+                                           tile_config=3)
+        assert status == (fb.FLUX_OK, 0)
+        gh.assert_close(Cg, C64, w.out_dtype, f"ctpc {ctpc}")
+        n = max(1, ctpc)
+        assert signals.cpu().tolist() == [1 if i // n == rank else 0 for i in range(w.R * n)]
+
+
+def test_ag_delayed_copy_stream_still_correct():
+    """The copy driver starts ~10 ms late (host-forced); every remote tile has to spin."""
+    w = AG_SMALL
+    rank = 0
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival, delay_copy_cycles=20_000_000)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_close(Cg, C64, w.out_dtype)
+
+
+def test_ag_local_chunk_in_place():
+    w = AG_SMALL
+    rank = 6
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival, local_in_place=True)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_close(Cg, C64, w.out_dtype)
+
+
+def test_ag_r1_needs_no_copy():
+    w = fi.Workload("ag_r1", "ag", 256, 256, 256, 1, seed=81)
+    chunks, B, arrival = fi.make_ag_inputs(w, 0)
+    assert arrival == []
+    Cg, _, signals, status = gh.run_ag(w, 0, chunks, B, None)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    gh.assert_close(Cg, C64, w.out_dtype)
+    assert signals.cpu().tolist() == [1]
+
+
+def test_ag_signal_wait_times_out_cleanly():
+    """Failure handling, forced from the host: the copy stream is held back and the spin limit
+    is one tick, so waiting tiles give up, the kernel still exits, and the status block says
+    which signal was missing.  Tiles of the local chunk (preset signal) are still computed."""
+    w = AG_SMALL
+    rank = 2
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, delay_copy_cycles=20_000_000, timeout_ticks=1)
+    code, detail = status
+    assert code == fb.FLUX_ERR_TIMEOUT
+    assert 0 <= detail < w.R and detail != rank
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    lo, hi = rank * w.S, (rank + 1) * w.S
+    gh.assert_close(Cg[lo:hi], C64[lo:hi], w.out_dtype, "local chunk rows")
+    # and the library is usable afterwards
+    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_close(Cg, C64, w.out_dtype)
+
+
+def test_results_are_deterministic():
+    w = fi.scaled(W["c3_rs"], M=1024, N=1024, K=512)
+    A, B, peers = fi.make_rs_inputs(w, 1)
+    a = gh.run_rs(w, 1, A, B, peers)
+    b = gh.run_rs(w, 1, A, B, peers)
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+# ---------------------------------------------------------------------------------------------
+# non-overlapped baseline
+# ---------------------------------------------------------------------------------------------
+
+def test_unfused_baseline_matches_oracle():
+    w = fi.scaled(W["c3_rs"], M=1024, N=1024, K=768)
+    rank = 3
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype)
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
+    outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
+    tmp = torch.empty((w.M, w.N), dtype=torch.bfloat16, device=gh.DEV)
+    fb.flux_gemm_ref_unfused(fb.FLUX_OP_RS, fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM, p, A=dA, B=dB,
+                             peer_partials=dpeers, out_slices=outs, Cout=tmp)
+    torch.cuda.synchronize()
+    s64, _ = gh.oracle_rs(w, rank, A, B, peers)
+    for r in range(w.R):
+        # the baseline rounds the GEMM result to bf16 before adding: one extra half-ulp
+        gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+
+    wa = fi.scaled(W["c2_ag"], M=1024, N=896, K=1024)
+    chunks, B, _ = fi.make_ag_inputs(wa, 1)
+    pa = fb.problem(wa.M, wa.N, wa.K, wa.R, 1, "bf16", wa.out_dtype)
+    A_agg = torch.full((wa.M, wa.K), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    Cout = torch.full((wa.M, wa.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    fb.flux_gemm_ref_unfused(fb.FLUX_OP_AG, fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM, pa,
+                             A_chunks=[c.to(gh.DEV) for c in chunks], A_agg=A_agg, B=B.to(gh.DEV), Cout=Cout)
+    torch.cuda.synchronize()
+    C64, _ = gh.oracle_ag(wa, chunks, B)
+    gh.assert_close(Cout, C64, wa.out_dtype)

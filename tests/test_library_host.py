@@ -1,0 +1,146 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/flux.h declares, rejects
+bad arguments before enqueuing anything, and its TileCoord agrees with the oracle's."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import flux_oracle as fo
+from paper_2406_06858_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = fb.lib()
+    header = open(os.path.join(ROOT, "include", "flux.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(flux_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(fb.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert fb.flux_version() >= 1
+
+
+def test_problem_struct_layout_matches_header():
+    # 12 int32/uint32 fields + one uint64, naturally aligned
+    import ctypes
+    assert ctypes.sizeof(fb.flux_problem_t) == 56
+    assert fb.flux_problem_t.spin_timeout_ticks.offset == 48
+
+
+def test_status_strings():
+    L = fb.lib()
+    assert L.flux_status_string(0) == b"ok"
+    assert b"timed out" in L.flux_status_string(fb.FLUX_ERR_TIMEOUT)
+
+
+def test_default_order_matches_oracle():
+    for R in range(1, 9):
+        for rank in range(R):
+            assert fb.flux_default_order(rank, R) == fo.default_order(rank, R)
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(M=100, R=8), fb.FLUX_ERR_SHAPE),          # M % R != 0
+    (dict(N=100), fb.FLUX_ERR_SHAPE),               # N % 8 != 0
+    (dict(K=100), fb.FLUX_ERR_SHAPE),
+    (dict(M=0), fb.FLUX_ERR_SHAPE),
+    (dict(R=17), fb.FLUX_ERR_SHAPE),
+    (dict(rank=8), fb.FLUX_ERR_INVALID_ARG),
+    (dict(out_dtype=7), fb.FLUX_ERR_INVALID_ARG),
+    (dict(tile_config=99), fb.FLUX_ERR_INVALID_ARG),
+])
+def test_invalid_problems_are_rejected(bad, status):
+    kw = dict(M=128, N=256, K=256, R=8, rank=0)
+    kw.update(bad)
+    out_dtype = kw.pop("out_dtype", None)
+    p = fb.problem(**kw)
+    if out_dtype is not None:
+        p.out_dtype = out_dtype
+    with pytest.raises(fb.FluxError) as e:
+        fb.flux_tile_shape(fb.FLUX_OP_RS, p)
+    assert e.value.status == status
+    assert fb.flux_workspace_bytes(fb.FLUX_OP_RS, p) == 0
+
+
+def test_null_pointers_are_rejected_before_any_enqueue():
+    import ctypes as C
+    p = fb.problem(128, 256, 256, 2, 0)
+    L = fb.lib()
+    null_list = (C.c_void_p * 2)()
+    assert L.flux_gemm_rs(C.byref(p), None, None, null_list, null_list, None, 0, None) == fb.FLUX_ERR_INVALID_ARG
+    assert L.flux_ag_gemm(C.byref(p), null_list, None, None, None, None, None, None, 0, None, None) == fb.FLUX_ERR_INVALID_ARG
+    # misaligned base pointer
+    assert L.flux_gemm_rs(C.byref(p), 8, 16, null_list, null_list, None, 0, None) == fb.FLUX_ERR_INVALID_ARG
+
+
+def test_bad_arrival_order_is_rejected():
+    p = fb.problem(128, 256, 256, 4, 1)
+    for arr in ([0, 2, 2], [0, 1, 3], [0, 2, 5]):
+        with pytest.raises(fb.FluxError) as e:
+            fb.flux_tile_coord(fb.FLUX_OP_AG, p, arr, 0)
+        assert e.value.status == fb.FLUX_ERR_INVALID_ARG
+
+
+def test_comm_tiles_must_divide_chunk():
+    p = fb.problem(128, 256, 256, 4, 1, comm_tiles_per_chunk=5)
+    with pytest.raises(fb.FluxError) as e:
+        fb.flux_tile_shape(fb.FLUX_OP_AG, p)
+    assert e.value.status == fb.FLUX_ERR_SHAPE
+
+
+def _all_configs():
+    return [(i,) + fb.flux_tile_config_info(i) for i in range(1, fb.flux_tile_config_count() + 1)]
+
+
+SHAPES = [
+    # (M, N, R)
+    (128, 256, 2), (4096, 3584, 8), (4096, 8192, 8), (64, 3584, 8), (8, 8192, 8), (256, 3584, 8),
+    (1000, 520, 8), (96, 40, 3), (8192, 4608, 8),
+]
+
+
+@pytest.mark.parametrize("M,N,R", SHAPES)
+@pytest.mark.parametrize("op", ["rs", "ag"])
+def test_tile_coord_matches_oracle(M, N, R, op):
+    """The library's TileCoord and the oracle's are written independently; they must agree on
+    every workgroup id, for every tile configuration, rank and swizzle flag."""
+    opc = fb.FLUX_OP_RS if op == "rs" else fb.FLUX_OP_AG
+    for cfg, bm, bn, _ in _all_configs():
+        tiles = -(-M // bm) * -(-N // bn)
+        step = max(1, tiles // 97)
+        for rank in sorted({0, R // 2, R - 1}):
+            arr = None
+            if op == "ag":
+                rng = np.random.default_rng(1000 * rank + M)
+                remote = [c for c in range(R) if c != rank]
+                arr = [remote[i] for i in rng.permutation(len(remote))]
+            for flags, n_xcd in ((0, 8), (fb.FLUX_FLAG_NO_XCD_REMAP, 1)):
+                p = fb.problem(M, N, 256, R, rank, tile_config=cfg, flags=flags)
+                shape = fb.flux_tile_shape(opc, p)
+                assert (shape.tile_m, shape.tile_n, shape.n_xcd) == (bm, bn, n_xcd)
+                for b in list(range(0, tiles, step)) + [tiles - 1]:
+                    got = fb.flux_tile_coord(opc, p, arr, b)
+                    want = fo.tile_coord(op, b, M, N, R, rank, bm, bn, arr, n_xcd)
+                    assert got == want, (cfg, rank, flags, b)
+
+
+def test_no_swizzle_flag_gives_natural_order():
+    M, N, R, rank = 4096, 3584, 8, 3
+    p = fb.problem(M, N, 256, R, rank, tile_config=1, flags=fb.FLUX_FLAG_NO_SWIZZLE)
+    tiles_n = N // 256
+    for b in (0, 1, tiles_n, 5 * tiles_n + 3):
+        assert fb.flux_tile_coord(fb.FLUX_OP_RS, p, None, b) == (b // tiles_n, b % tiles_n)
+
+
+def test_workspace_bytes():
+    p = fb.problem(4096, 8192, 3584, 8, 0)
+    assert fb.flux_workspace_bytes(fb.FLUX_OP_RS, p) == 0          # no K split: nothing needed
+    assert fb.flux_workspace_bytes(fb.FLUX_OP_AG, p) > 0           # status + counters
+    d = fb.problem(64, 8192, 3584, 8, 0, split_k=4)
+    shape = fb.flux_tile_shape(fb.FLUX_OP_RS, d)
+    assert shape.split_k == 4
+    tiles = -(-64 // shape.tile_m) * (8192 // shape.tile_n)
+    assert fb.flux_workspace_bytes(fb.FLUX_OP_RS, d) >= 4 * tiles * shape.tile_m * shape.tile_n * 4

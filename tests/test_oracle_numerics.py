@@ -189,3 +189,19 @@ def test_peer_partial_shape_and_count_are_checked():
         fo.gemm_rs(A, B, [None, bf16(np.ones((2, 2)))], 2, 0, "bf16", "f32")
     with pytest.raises(ValueError):
         fo.gemm_rs(bf16(np.ones((3, 2))), B, [None, bf16(np.ones((3, 2)))], 2, 0, "bf16", "f32")
+
+
+def test_row_subset_variants_agree_with_full_definitions():
+    rng = np.random.default_rng(21)
+    M, N, K, R, rank = 12, 5, 6, 3, 1
+    A = rand_int(rng, (M, K), 3)
+    B = rand_int(rng, (K, N), 3)
+    peers = [None if j == rank else bf16(rand_int(rng, (M, N), 9)) for j in range(R)]
+    s64, _ = fo.gemm_rs(bf16(A), bf16(B), peers, R, rank, "bf16", "f32")
+    rows = [11, 0, 5, 4]
+    for (owner, lr, vals), i in zip(fo.gemm_rs_rows(bf16(A), bf16(B), peers, R, rank, "bf16", rows), rows):
+        assert owner * (M // R) + lr == i
+        assert np.array_equal(vals, s64[owner][lr])
+    chunks = [bf16(A[r * 4:(r + 1) * 4]) for r in range(R)]
+    C64, _ = fo.ag_gemm(chunks, bf16(B), "f32")
+    assert np.array_equal(fo.ag_gemm_rows(chunks, bf16(B), rows), C64[rows])
