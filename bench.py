@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused tensor-parallel GEMMs on one MI355X.
+
+A step is one pass of the whole hot path on one batch: the fused AllGather-GEMM of the
+Llama-2-70B-like MLP up-projection (4096 tokens, TP=8; chunks released by the copy driver in a
+seeded random order) followed by the fused GEMM-ReduceScatter of the matching down-projection
+(7 peer partials added in the epilogue, 8 row slices written).  Inputs are seeded synthetic
+tensors, already resident in HBM when the timed region starts.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0
+TIMEOUT_TICKS = 500_000_000        # 5 s: a lost signal ends the run with an error, not a hang
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-config / overlap-efficiency section")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (R virtual ranks inside one MI355X); --gpus must be 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2406_06858_amd import binding as fb
+    from paper_2406_06858_amd import inputs as fi
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    W = fi.WORKLOADS
+    compute = torch.cuda.current_stream()
+    copy = torch.cuda.Stream()
+
+    class AG:
+        def __init__(self, w, rank, **kw):
+            self.w, self.rank = w, rank
+            self.chunks_cpu, self.B_cpu, self.arrival = fi.make_ag_inputs(w, rank)
+            self.p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, spin_timeout_ticks=TIMEOUT_TICKS, **kw)
+            self.chunks = [c.to(dev) for c in self.chunks_cpu]
+            self.B = self.B_cpu.to(dev)
+            self.A_agg = torch.zeros((w.M, w.K), dtype=torch.bfloat16, device=dev)
+            self.C = torch.zeros((w.M, w.N), dtype=torch.bfloat16, device=dev)
+            self.signals = torch.zeros(w.R * max(1, kw.get("comm_tiles_per_chunk", 0)), dtype=torch.int32, device=dev)
+            self.ws = torch.zeros(fb.flux_workspace_bytes(fb.FLUX_OP_AG, self.p) // 4 + 1, dtype=torch.int32, device=dev)
+
+        def fused(self):
+            fb.flux_ag_gemm(self.p, self.chunks, self.A_agg, self.B, self.C, self.signals, self.arrival,
+                            self.ws, compute, copy)
+
+        def unfused(self, phases):
+            fb.flux_gemm_ref_unfused(fb.FLUX_OP_AG, phases, self.p, A_chunks=self.chunks, A_agg=self.A_agg,
+                                     B=self.B, Cout=self.C, workspace=self.ws, stream=compute)
+
+        def alg_bytes(self):     # fused kernel: A_agg + B read once, C written once
+            w = self.w
+            return 2.0 * (w.M * w.K + w.K * w.N + w.M * w.N)
+
+    class RS:
+        def __init__(self, w, rank, **kw):
+            self.w, self.rank = w, rank
+            self.A_cpu, self.B_cpu, self.peers_cpu = fi.make_rs_inputs(w, rank)
+            self.p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype, **kw)
+            self.A, self.B = self.A_cpu.to(dev), self.B_cpu.to(dev)
+            self.peers = [None if t is None else t.to(dev) for t in self.peers_cpu]
+            dt = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
+            self.outs = [torch.zeros((w.S, w.N), dtype=dt, device=dev) for _ in range(w.R)]
+            self.tmp = torch.zeros((w.M, w.N), dtype=dt, device=dev)
+            n = fb.flux_workspace_bytes(fb.FLUX_OP_RS, self.p)
+            self.ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev) if n else None
+
+        def fused(self):
+            fb.flux_gemm_rs(self.p, self.A, self.B, self.peers, self.outs, self.ws, compute)
+
+        def unfused(self, phases):
+            fb.flux_gemm_ref_unfused(fb.FLUX_OP_RS, phases, self.p, A=self.A, B=self.B, peer_partials=self.peers,
+                                     out_slices=self.outs, Cout=self.tmp, workspace=self.ws, stream=compute)
+
+        def alg_bytes(self):
+            w = self.w
+            ps = 2 if w.partial_dtype == "bf16" else 4
+            os_ = 2 if w.out_dtype == "bf16" else 4
+            return 2.0 * (w.M * w.K + w.K * w.N) + (w.R - 1) * w.M * w.N * ps + w.M * w.N * os_
+
+    def time_calls(fn, reps, warm):
+        """Median wall time (ms) of `fn` measured with events on the compute stream."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = fb.HipEvent(), fb.HipEvent()
+            e0.record(compute)
+            fn()
+            e1.record(compute)
+            e1.synchronize()
+            ts.append(e0.elapsed_ms(e1))
+        return statistics.median(ts)
+
+    def overlap_block(op, reps=20, warm=5):
+        """Eq. 1-2 with GEMM_non-split := the plain kernel of the same tile configuration."""
+        t_gemm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_GEMM), reps, warm)
+        t_comm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_COMM), reps, warm)
+        t_unf = time_calls(lambda: op.unfused(fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM), reps, warm)
+        t_fus = time_calls(op.fused, reps, warm)
+        ect_no, ect_ov = t_unf - t_gemm, t_fus - t_gemm
+        E = 1.0 - ect_ov / ect_no if ect_no > 0 else None
+        w = op.w
+        return {"ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
+                "ms_fused": round(t_fus, 4), "overlap_efficiency": None if E is None else round(E, 4),
+                "fused_tflops": round(w.flops / t_fus / 1e9, 1),
+                "fused_frac_mfma_peak": round(w.flops / t_fus / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "fused_alg_GBs": round(op.alg_bytes() / t_fus / 1e6, 1),
+                "fused_frac_hbm_peak": round(op.alg_bytes() / t_fus / 1e6 / HBM_PEAK_GBS, 4)}
+
+    # ---- the timed workload: MLP up-projection (AG-GEMM) + down-projection (GEMM-RS) ----
+    ag = AG(W["c2_ag"], rank=2)
+    rs = RS(W["c3_rs"], rank=2)
+    flops_step = ag.w.flops + rs.w.flops
+
+    def step(prof=None):
+        if prof is not None:
+            fb.flux_profile_next_gemm(prof[0], prof[1])
+        ag.fused()
+        if prof is not None:
+            fb.flux_profile_next_gemm(prof[2], prof[3])
+        rs.fused()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    profs = [[fb.HipEvent() for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(profs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+    ag_ms = statistics.mean(p[0].elapsed_ms(p[1]) for p in profs)
+    rs_ms = statistics.mean(p[2].elapsed_ms(p[3]) for p in profs)
+    status = fb.flux_query_status(ag.ws)
+    if status[0] != fb.FLUX_OK:
+        print(f"bench.py: AllGather-GEMM reported status {status}", file=sys.stderr)
+        return 1
+
+    # spot check against the oracle on a few rows (outside the timed region)
+    from oracle import flux_oracle as fo
+    rows = [0, 511, 512, 2047, 4095]
+    ref = fo.ag_gemm_rows([fi.to_numpy(c) for c in ag.chunks_cpu], fi.to_numpy(ag.B_cpu), rows)
+    got = ag.C[rows].float().cpu().double().numpy()
+    ok_ag = bool(np.all(np.abs(got - ref) <= 1e-2 * np.maximum(1.0, np.abs(ref))))
+    refr = fo.gemm_rs_rows(fi.to_numpy(rs.A_cpu), fi.to_numpy(rs.B_cpu),
+                           [None if t is None else fi.to_numpy(t) for t in rs.peers_cpu], rs.w.R, rs.rank,
+                           rs.w.partial_dtype, rows)
+    ok_rs = all(bool(np.all(np.abs(rs.outs[o][lr].float().cpu().double().numpy() - v) <= 1e-2 * np.maximum(1.0, np.abs(v))))
+                for o, lr, v in refr)
+    if not (ok_ag and ok_rs):
+        print("bench.py: result check against the CPU oracle FAILED", file=sys.stderr)
+        return 1
+
+    # roofline of the dominant kernel: the fused AllGather-GEMM kernel (bf16 MFMA bound)
+    ag_tflops = ag.w.flops / (ag_ms * 1e-3) / 1e12
+    roofline = {"kernel": "gemm_kernel<AllGather prologue> on c2_ag", "bound": "mfma",
+                "achieved": round(ag_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ag_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "avg_kernel_ms": round(ag_ms, 4),
+                "second_kernel": {"kernel": "gemm_kernel<ReduceScatter epilogue> on c3_rs",
+                                  "avg_kernel_ms": round(rs_ms, 4),
+                                  "tflops": round(rs.w.flops / (rs_ms * 1e-3) / 1e12, 1),
+                                  "frac_mfma": round(rs.w.flops / (rs_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                  "alg_GBs": round(rs.alg_bytes() / rs_ms / 1e6, 1),
+                                  "frac_hbm": round(rs.alg_bytes() / rs_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+
+    extra = {}
+    if not args.no_extra:
+        extra["c2_ag"] = overlap_block(ag)
+        extra["c3_rs"] = overlap_block(rs)
+        del ag, rs
+        torch.cuda.empty_cache()
+        for name in ("c4_ag", "c4_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):
+            op = AG(W[name], 2) if W[name].op == "ag" else RS(W[name], 2)
+            extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50)
+            del op
+            torch.cuda.empty_cache()
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on the host cores: full AllGather-GEMM of the timed shape
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        w = W["c2_ag"]
+        chunks, B, _ = fi.make_ag_inputs(w, 2)
+        sample_rows = 1024
+        cn = [fi.to_numpy(c) for c in chunks]
+        Bn = fi.to_numpy(B)
+        t0 = time.perf_counter()
+        fo.ag_gemm_rows(cn, Bn, list(range(sample_rows)))
+        dt = time.perf_counter() - t0
+        cpu_baseline = {"value": round(2.0 * sample_rows * w.N * w.K / dt / 1e12, 4), "unit": "TFLOP/s",
+                        "cores": cores, "kind": "oracle",
+                        "sample": f"oracle ag_gemm_rows on the first {sample_rows} of {w.M} rows of c2_ag (fp64 numpy), {dt:.2f} s"}
+
+    out = {
+        "metric": "fused GEMM-RS/AG-GEMM TFLOP/s (% MFMA peak) + % comm time hidden, 1 MI355X",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "c2_ag + c3_rs: Llama-2-70B-like MLP at TP=8, 4096 tokens - fused AllGather-GEMM "
+                               "[8x512,8192]x[8192,3584] then fused GEMM-ReduceScatter [4096,3584]x[3584,8192] + 7 peers",
+                   "virtual_ranks": 8, "rank": 2, "frac_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "extra": extra,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -165,6 +165,15 @@ int flux_tile_config_info(int32_t id, int32_t* tile_m, int32_t* tile_n, int32_t*
 /* Communication order of Sec. 4.3 (ring starting after the local rank): fills order[R-1]. */
 int flux_default_order(int32_t rank, int32_t R, int32_t* order);
 
+/*
+ * Measurement hook: the next flux_gemm_rs / flux_ag_gemm / flux_gemm_ref_unfused call made by
+ * this thread records `start` immediately before and `stop` immediately after its GEMM kernel
+ * launch, on the stream that kernel runs on (hipEvent_t handles passed as void*; the pair is
+ * consumed by that call).  Passing NULLs cancels a pending pair.  The elapsed time between
+ * the two is the kernel's duration including any in-kernel signal waits.
+ */
+int flux_profile_next_gemm(void* start_event, void* stop_event);
+
 const char* flux_status_string(int status);
 int flux_last_hip_error(void);       /* hipError_t of the most recent FLUX_ERR_HIP on this thread */
 int flux_version(void);

@@ -28,7 +28,7 @@ EXPORTS = [
     "flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_workspace_bytes",
     "flux_query_status", "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
     "flux_tile_config_info", "flux_default_order", "flux_status_string", "flux_last_hip_error",
-    "flux_version",
+    "flux_version", "flux_profile_next_gemm",
 ]
 
 
@@ -72,11 +72,13 @@ def lib():
         L.flux_tile_shape.argtypes = [C.c_int, pp, pi32, pi32, pi32, pi32, pi32]
         L.flux_tile_config_info.argtypes = [C.c_int32, pi32, pi32, pi32]
         L.flux_default_order.argtypes = [C.c_int32, C.c_int32, pi32]
+        L.flux_profile_next_gemm.argtypes = [vp, vp]
         L.flux_status_string.argtypes = [C.c_int]
         L.flux_status_string.restype = C.c_char_p
         for name in ("flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_query_status",
                      "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
-                     "flux_tile_config_info", "flux_default_order", "flux_last_hip_error", "flux_version"):
+                     "flux_tile_config_info", "flux_default_order", "flux_last_hip_error", "flux_version",
+                     "flux_profile_next_gemm"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -201,3 +203,53 @@ def tile_config_for(tile_m: int, tile_n: int) -> int:
         if (bm, bn) == (tile_m, tile_n):
             return i
     raise ValueError(f"no tile configuration {tile_m}x{tile_n}")
+
+
+# ---- HIP events created directly on the runtime, for timing a kernel on the library's stream ----
+_hip = None
+
+
+def _hiprt():
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        _hip.hipEventDestroy.argtypes = [C.c_void_p]
+        _hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        _hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+    return _hip
+
+
+class HipEvent:
+    """A timing-enabled hipEvent_t (plain handle; torch is not involved)."""
+
+    def __init__(self):
+        self.handle = C.c_void_p()
+        if _hiprt().hipEventCreate(C.byref(self.handle)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+
+    def record(self, stream=None):
+        if _hiprt().hipEventRecord(self.handle, _stream(stream)) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def synchronize(self):
+        if _hiprt().hipEventSynchronize(self.handle) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+
+    def elapsed_ms(self, later: "HipEvent") -> float:
+        ms = C.c_float(0)
+        if _hiprt().hipEventElapsedTime(C.byref(ms), self.handle, later.handle) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value
+
+    def __del__(self):
+        try:
+            _hiprt().hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
+def flux_profile_next_gemm(start: HipEvent | None, stop: HipEvent | None):
+    _check(lib().flux_profile_next_gemm(None if start is None else start.handle,
+                                        None if stop is None else stop.handle), "flux_profile_next_gemm")

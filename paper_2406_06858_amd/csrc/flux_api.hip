@@ -20,6 +20,7 @@ constexpr int N_XCD = 8;                       // accelerator dies of an MI355X,
 constexpr unsigned long long DEFAULT_TIMEOUT_TICKS = 1000000000ull;   // 10 s at 100 MHz
 
 static thread_local int g_last_hip_error = 0;
+static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 
 #define FLUX_HIP(expr)                                  \
   do {                                                  \
@@ -317,7 +318,11 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
 
 static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hipStream_t s) {
   const int grid = pl.tiles_m * pl.tiles_n * pl.split_k;
+  hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
+  if (e0) FLUX_HIP(hipEventRecord(e0, s));
   FLUX_HIP(g_cfgs[pl.cfg].launch(epi, wait, pl.edge, a, grid, s));
+  if (e1) FLUX_HIP(hipEventRecord(e1, s));
   return FLUX_OK;
 }
 
@@ -379,6 +384,13 @@ extern "C" {
 int flux_version(void) { return 1; }
 
 int flux_last_hip_error(void) { return g_last_hip_error; }
+
+int flux_profile_next_gemm(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return FLUX_ERR_INVALID_ARG;
+  g_prof_start = static_cast<hipEvent_t>(start_event);
+  g_prof_stop = static_cast<hipEvent_t>(stop_event);
+  return FLUX_OK;
+}
 
 const char* flux_status_string(int status) {
   switch (status) {
