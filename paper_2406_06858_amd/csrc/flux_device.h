@@ -296,6 +296,79 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   return *lds_ok != 0;
 }
 
+// Everything after the main loop: the split-K hand-over (all but the last-arriving workgroup of
+// a tile park their partial sums, the last one adds them up) and the epilogue, in which the
+// accumulators pass through LDS once (per wave, 32 rows at a time) so that every lane ends up
+// with 8 consecutive columns of one row.  `smem` must hold C::EP_BYTES and is free to reuse.
+template <class C, int EPI, bool EDGE>
+__device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem, int* lds_misc, void* const* lds_outs,
+                                          f32x16 (&acc)[C::MI][C::NI], int tile, int split, int ntiles,
+                                          int m0, int n0, int tid, int lane, int wave, int wm, int wn) {
+  // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
+  if (a.split_k > 1) {
+    float* mine = a.sk_partials + ((size_t)split * ntiles + tile) * (C::BM * C::BN);
+    // layout inside a tile's partial block: [mi][ni][e][thread] -> coalesced 4-byte columns
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          mine[((mi * C::NI + ni) * 16 + e) * C::NT + tid] = acc[mi][ni][e];
+    __threadfence();
+    __syncthreads();
+    int* lds_last = lds_misc;
+    if (tid == 0) {
+      const uint32_t prev = atomicAdd(a.sk_counters + tile, 1u);
+      const int last = prev == (uint32_t)(a.split_k - 1);
+      if (last) a.sk_counters[tile] = 0u;     // ready for the next launch
+      *lds_last = last;
+    }
+    __syncthreads();
+    if (!*lds_last) return;
+    __threadfence();
+    for (int s = 0; s < a.split_k; ++s) {
+      if (s == split) continue;
+      const float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            acc[mi][ni][e] += __builtin_nontemporal_load(other + ((mi * C::NI + ni) * 16 + e) * C::NT + tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: registers -> LDS (per wave, 32 rows at a time) -> 8 columns per lane ----
+  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * C::EP_STRIDE);
+  constexpr int CH = C::WTN / 8;          // 8-column chunks per row of the wave tile
+  constexpr int RPP = 64 / CH;            // rows per pass
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
+      }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 32 / RPP; ++it) {
+      const int r = it * RPP + lane / CH, cc = lane % CH;
+      const float4 x = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8);
+      const float4 y = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8 + 4);
+      float v[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+      const int gm = m0 + wm * C::WTM + mi * 32 + r;
+      const int gn = n0 + wn * C::WTN + cc * 8;
+      if (!EDGE || (gm < a.M && gn < a.N)) epilogue_row8<EPI>(a, lds_outs, gm, gn, v);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 template <class C, int EPI, bool WAIT, bool EDGE>
 __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -352,69 +425,128 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
     }
   }
 
-  // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
-  if (a.split_k > 1) {
-    float* mine = a.sk_partials + ((size_t)split * ntiles + tile) * (C::BM * C::BN);
-    // layout inside a tile's partial block: [mi][ni][e][thread] -> coalesced 4-byte columns
-#pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          mine[((mi * C::NI + ni) * 16 + e) * C::NT + tid] = acc[mi][ni][e];
-    __threadfence();
-    __syncthreads();
-    int* lds_last = reinterpret_cast<int*>(smem + C::MISC_OFF);
-    if (tid == 0) {
-      const uint32_t prev = atomicAdd(a.sk_counters + tile, 1u);
-      const int last = prev == (uint32_t)(a.split_k - 1);
-      if (last) a.sk_counters[tile] = 0u;     // ready for the next launch
-      *lds_last = last;
-    }
-    __syncthreads();
-    if (!*lds_last) return;
-    __threadfence();
-    for (int s = 0; s < a.split_k; ++s) {
-      if (s == split) continue;
-      const float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
-#pragma unroll
-      for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            acc[mi][ni][e] += __builtin_nontemporal_load(other + ((mi * C::NI + ni) * 16 + e) * C::NT + tid);
-    }
-    __syncthreads();
+  gemm_tail<C, EPI, EDGE>(a, smem, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs, acc, tile, split, ntiles,
+                          m0, n0, tid, lane, wave, wm, wn);
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Fast path for shapes that the tile divides: global -> LDS without passing through registers.
+//
+// buffer_load_dwordx4 ... lds writes the 64 x 16 B a wave fetches to 1 KiB of consecutive LDS,
+// so the swizzled layouts above are produced by permuting which 16 B each lane FETCHES:
+//   A: one instruction = 8 rows x 128 B; lane i fills physical slot i%8 of row i/8 and fetches
+//      logical slot (i%8) ^ swz_a(row);
+//   B: one instruction = 1 KiB / (2*BN) k-rows; lane i fills physical slot i%B_SLOTS and
+//      fetches logical slot (i%B_SLOTS) ^ swz_b(k).
+// Per K-slab only scalar offsets change (soffset), so the address arithmetic costs no vector
+// instructions.  The two LDS stages are separate arrays: the compiler's wait-count insertion can
+// then tell the stage being filled from the stage being read and does not serialise them.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+template <class C>
+struct DmaLoader {
+  static constexpr int NW = C::NT / 64;
+  static constexpr int A_INSTR = C::BM / 8 / NW;               // per wave
+  static constexpr int RPI = 512 / C::BN;                      // B k-rows per instruction
+  static constexpr int B_INSTR = C::BK / RPI / NW;             // per wave
+  static_assert(C::BK == 64, "A rows must be 128 B");
+  static_assert(NW % 2 == 0 && (RPI * NW) % 4 == 0, "swizzle must not depend on the instruction index");
+  static_assert(C::BM % (8 * NW) == 0 && C::BK % (RPI * NW) == 0 && 512 % C::BN == 0, "loader shape");
+
+  __amdgpu_buffer_rsrc_t ra, rb;
+  int voff_a, voff_b;
+
+  __device__ __forceinline__ void init(const GemmArgs& a, int m0, int n0, int wave, int lane) {
+    ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.A), 0, (int)((unsigned)a.M * (unsigned)a.K * 2u), 0x00027000);
+    rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0, (int)((unsigned)a.K * (unsigned)a.N * 2u), 0x00027000);
+    const int r_in = lane >> 3, sp = lane & 7;
+    const int row = 8 * wave + r_in;
+    voff_a = ((m0 + row) * a.K + ((sp ^ swz_a<C::A_SLOTS>(row)) << 3)) * 2;
+    const int k_in = lane / C::B_SLOTS, spb = lane % C::B_SLOTS;
+    const int k = RPI * wave + k_in;
+    voff_b = (k * a.N + n0 + ((spb ^ swz_b<C::B_SLOTS>(k)) << 3)) * 2;
   }
 
-  // ---- epilogue: registers -> LDS (per wave, 32 rows at a time) -> 8 columns per lane ----
-  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * C::EP_STRIDE);
-  constexpr int CH = C::WTN / 8;          // 8-column chunks per row of the wave tile
-  constexpr int RPP = 64 / CH;            // rows per pass
+  // all loads of one K-slab for this wave; `stage` is the base of the LDS stage being filled
+  __device__ __forceinline__ void issue(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
 #pragma unroll
-  for (int mi = 0; mi < C::MI; ++mi) {
+    for (int p = 0; p < A_INSTR; ++p)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (p * NW + wave) * 1024), 16, voff_a,
+                                               (k0 + p * 8 * NW * a.K) * 2, 0, 0);
+#pragma unroll
+    for (int p = 0; p < B_INSTR; ++p)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
+                                               (k0 + p * RPI * NW) * a.N * 2, 0, 0);
+    // keep the loads where they are written: scheduled late they would be issued just before
+    // the wait for them, and nothing would overlap
+    __builtin_amdgcn_sched_barrier(0);
+  }
+};
+
+__device__ __forceinline__ void wait_vm0_and_barrier() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-bound loads have landed
+  __syncthreads();
+}
+
+template <class C, int EPI, bool WAIT>
+__global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs a) {
+  constexpr int S0_BYTES = C::STAGE_BYTES > C::EP_BYTES ? C::STAGE_BYTES : C::EP_BYTES;
+  __shared__ __attribute__((aligned(1024))) unsigned char stage0[S0_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char stage1[C::STAGE_BYTES];
+  __shared__ int lds_misc[4];
+  __shared__ void* lds_outs[FLUX_MAX_RANKS];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+
+  const int ntiles = a.tm.tiles_m * a.tm.tiles_n;
+  const int tile = (int)blockIdx.x % ntiles;
+  const int split = (int)blockIdx.x / ntiles;
+  int mt, nt;
+  tile_coord(a.tm, tile, mt, nt);
+  const int m0 = mt * C::BM, n0 = nt * C::BN;
+
+  if (EPI == EPI_RS) {
+#pragma unroll
+    for (int j = 0; j < FLUX_MAX_RANKS; ++j)
+      if (tid == j) lds_outs[j] = a.outs[j];
+  }
+  if (WAIT) {
+    if (!wait_signals(a, m0, m0 + C::BM, lds_misc)) return;
+  }
+
+  const int k_begin = split * a.k_per_split;
+  const int k_end = (k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
+  const int KT = (k_end - k_begin) / C::BK;
+
+  f32x16 acc[C::MI][C::NI];
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
-      }
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int it = 0; it < 32 / RPP; ++it) {
-      const int r = it * RPP + lane / CH, cc = lane % CH;
-      const float4 x = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8);
-      const float4 y = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8 + 4);
-      float v[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-      const int gm = m0 + wm * C::WTM + mi * 32 + r;
-      const int gn = n0 + wn * C::WTN + cc * 8;
-      if (!EDGE || (gm < a.M && gn < a.N)) epilogue_row8<EPI>(a, lds_outs, gm, gn, v);
-    }
-    __builtin_amdgcn_wave_barrier();
+      for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
+
+  DmaLoader<C> ld;
+  ld.init(a, m0, n0, wave, lane);
+  ld.issue(a, stage0, k_begin, wave);
+  wait_vm0_and_barrier();
+  int kt = 0;
+  for (; kt + 2 <= KT; kt += 2) {
+    ld.issue(a, stage1, k_begin + (kt + 1) * C::BK, wave);
+    mma_stage<C>(stage0, wm, wn, lane, acc);
+    wait_vm0_and_barrier();
+    if (kt + 2 < KT) ld.issue(a, stage0, k_begin + (kt + 2) * C::BK, wave);
+    mma_stage<C>(stage1, wm, wn, lane, acc);
+    wait_vm0_and_barrier();
   }
+  if (kt < KT) {
+    mma_stage<C>(stage0, wm, wn, lane, acc);
+    __syncthreads();
+  }
+  gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, ntiles, m0, n0, tid, lane, wave, wm, wn);
 }
 
 }  // namespace flux

@@ -20,18 +20,25 @@ typedef TileCfg<32, 128, 64, 1, 4, 2, 2> Cfg;    // decode, M <= 32
 #error "FLUX_CFG_ID must be 1..6"
 #endif
 
+// Shapes the tile divides take the direct-to-LDS kernel; ragged shapes the register-staged one,
+// which masks rows, columns and the K tail.
 template <int EPI, bool WAIT, bool EDGE>
 static hipError_t launch_one(const GemmArgs& a, int grid, hipStream_t s) {
-  auto k = gemm_kernel<Cfg, EPI, WAIT, EDGE>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+  if constexpr (!EDGE && Cfg::NSTAGE == 2) {
+    hipLaunchKernelGGL((gemm_kernel_dma<Cfg, EPI, WAIT>), dim3(grid), dim3(Cfg::NT), 0, s, a);
+    return hipGetLastError();
+  } else {
+    auto k = gemm_kernel<Cfg, EPI, WAIT, EDGE>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(k, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, s, a);
+    return hipGetLastError();
   }
-  hipLaunchKernelGGL(k, dim3(grid), dim3(Cfg::NT), Cfg::LDS_BYTES, s, a);
-  return hipGetLastError();
 }
 
 #define FLUX_CAT2(a, b) a##b
