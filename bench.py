@@ -60,9 +60,14 @@ def main() -> int:
             self.chunks = [c.to(dev) for c in self.chunks_cpu]
             self.B = self.B_cpu.to(dev)
             self.A_agg = torch.zeros((w.M, w.K), dtype=torch.bfloat16, device=dev)
+            # the local chunk lives in place inside A_agg (its signal is preset), as a rank's own
+            # activations would; only the R-1 remote chunks are transferred
+            self.A_agg[rank * w.S:(rank + 1) * w.S].copy_(self.chunks[rank])
+            self.chunks[rank] = self.A_agg[rank * w.S:(rank + 1) * w.S]
             self.C = torch.zeros((w.M, w.N), dtype=torch.bfloat16, device=dev)
             self.signals = torch.zeros(w.R * max(1, kw.get("comm_tiles_per_chunk", 0)), dtype=torch.int32, device=dev)
             self.ws = torch.zeros(fb.flux_workspace_bytes(fb.FLUX_OP_AG, self.p) // 4 + 1, dtype=torch.int32, device=dev)
+            fb.flux_init_buffers(fb.FLUX_OP_AG, self.p, self.ws, self.signals)
 
         def fused(self):
             fb.flux_ag_gemm(self.p, self.chunks, self.A_agg, self.B, self.C, self.signals, self.arrival,
@@ -88,6 +93,8 @@ def main() -> int:
             self.tmp = torch.zeros((w.M, w.N), dtype=dt, device=dev)
             n = fb.flux_workspace_bytes(fb.FLUX_OP_RS, self.p)
             self.ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev) if n else None
+            if self.ws is not None:
+                fb.flux_init_buffers(fb.FLUX_OP_RS, self.p, self.ws)
 
         def fused(self):
             fb.flux_gemm_rs(self.p, self.A, self.B, self.peers, self.outs, self.ws, compute)

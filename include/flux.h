@@ -34,6 +34,7 @@
  *   - Errors are returned as flux_status_t values; nothing throws or aborts.  A signal wait
  *     that exceeds `spin_timeout_ticks` is reported through flux_query_status after the
  *     stream has been synchronised (the kernel then leaves the affected tiles unwritten).
+ *   - The status block keeps the first timeout until flux_init_buffers clears it.
  *   - Calls that share a workspace, an A_agg buffer or a signal array must not overlap in time.
  */
 #ifndef FLUX_MI355_H_
@@ -94,7 +95,8 @@ typedef struct flux_problem {
  *                   entry [rank] is ignored (may be NULL).
  *   out_slices      host array [R] of device pointers to [M/R,N] matrices of out_dtype, all
  *                   written (every element exactly once).
- *   workspace       device, >= flux_workspace_bytes(FLUX_OP_RS, p) bytes (may be NULL if 0).
+ *   workspace       device, >= flux_workspace_bytes(FLUX_OP_RS, p) bytes (may be NULL if 0),
+ *                   initialised once with flux_init_buffers.
  */
 int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
                  const void* const* peer_partials, void* const* out_slices,
@@ -106,12 +108,16 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.
  *   B, C            device, [K,N] bf16 and [M,N] out_dtype.
- *   signals         device uint32[R * comm_tiles_per_chunk] ("signal_list"); contents on entry
- *                   are ignored; on completion local ones hold 1, the others 0 (reset after
- *                   the GEMM, ordered by stream + event as in Sec. 4.3 "Signals").
+ *   signals         device uint32[R * comm_tiles_per_chunk] ("signal_list").  Must be in the preset
+ *                   state on entry (local communication tiles 1, the others 0): preset once
+ *                   with flux_init_buffers, as the paper presets at operator initialisation;
+ *                   a call that completes without timeout leaves them preset again (the reset
+ *                   after the GEMM of Sec. 4.3 "Signals", done by the last workgroup that has
+ *                   passed its wait).  After a timeout call flux_init_buffers again.
  *   arrival_order   host int32[R-1]: the remote ranks in the order the copy driver transfers
  *                   them; NULL = ring order starting after `rank` (Sec. 4.3).
- *   workspace       device, >= flux_workspace_bytes(FLUX_OP_AG, p).
+ *   workspace       device, >= flux_workspace_bytes(FLUX_OP_AG, p), initialised once with
+ *                   flux_init_buffers (counters and status block).
  *   compute_stream  the GEMM kernel's stream; on return of the call it is ordered after the
  *                   GEMM, the copy driver and the signal reset.
  *   copy_stream     the copy driver's stream; must differ from compute_stream.
@@ -139,6 +145,15 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p,
 
 /* Bytes of device workspace the given problem needs (0 on invalid problems). */
 size_t flux_workspace_bytes(int op, const flux_problem_t* p);
+
+/*
+ * One-time initialisation of caller-owned buffers (the paper's operator-initialisation step,
+ * Sec. 4.3 "Signals"): clears the workspace header (arrival counters, status block) and, for
+ * FLUX_OP_AG, presets `signals` (local communication tiles 1, the others 0).  `workspace` or
+ * `signals` may be NULL to skip that part.  Enqueued on `stream`.
+ */
+int flux_init_buffers(int op, const flux_problem_t* p, void* workspace, size_t workspace_bytes,
+                      uint32_t* signals, void* stream);
 
 /*
  * Reads the status block a finished flux_ag_gemm left in `workspace` (blocking device-to-host

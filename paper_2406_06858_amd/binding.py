@@ -28,7 +28,7 @@ EXPORTS = [
     "flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_workspace_bytes",
     "flux_query_status", "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
     "flux_tile_config_info", "flux_default_order", "flux_status_string", "flux_last_hip_error",
-    "flux_version", "flux_profile_next_gemm",
+    "flux_version", "flux_profile_next_gemm", "flux_init_buffers",
 ]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.flux_gemm_ref_unfused.argtypes = [C.c_int, C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, vp, C.c_size_t, vp]
         L.flux_workspace_bytes.argtypes = [C.c_int, pp]
         L.flux_workspace_bytes.restype = C.c_size_t
+        L.flux_init_buffers.argtypes = [C.c_int, pp, vp, C.c_size_t, vp, vp]
         L.flux_query_status.argtypes = [vp, pi32, pi32]
         L.flux_tile_coord.argtypes = [C.c_int, pp, pi32, C.c_int32, pi32, pi32]
         L.flux_tile_shape.argtypes = [C.c_int, pp, pi32, pi32, pi32, pi32, pi32]
@@ -78,7 +79,7 @@ def lib():
         for name in ("flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_query_status",
                      "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
                      "flux_tile_config_info", "flux_default_order", "flux_last_hip_error", "flux_version",
-                     "flux_profile_next_gemm"):
+                     "flux_profile_next_gemm", "flux_init_buffers"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -123,6 +124,12 @@ def _check(status: int, where: str):
 
 def flux_workspace_bytes(op: int, p: flux_problem_t) -> int:
     return int(lib().flux_workspace_bytes(op, C.byref(p)))
+
+
+def flux_init_buffers(op, p, workspace=None, signals=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().flux_init_buffers(op, C.byref(p), _ptr(workspace), ws_bytes, _ptr(signals), _stream(stream)),
+           "flux_init_buffers")
 
 
 def flux_gemm_rs(p, A, B, peer_partials, out_slices, workspace=None, stream=None):

@@ -194,10 +194,10 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     cfg = 4;
   } else if ((long long)p->M * p->N <= 256ll * 1024) {
     cfg = 3;
-  } else if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 2 * 256) {
-    cfg = 0;
+  } else if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 128) {
+    cfg = 0;          // 256x256: the least operand traffic per flop
   } else {
-    cfg = 1;
+    cfg = 2;          // 128x128: enough tiles to fill the chip on mid-sized problems
   }
   pl->cfg = cfg;
   pl->bm = g_cfgs[cfg].bm; pl->bn = g_cfgs[cfg].bn; pl->bk = g_cfgs[cfg].bk;
@@ -311,6 +311,7 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
   if (ws != nullptr) {
     unsigned char* w = static_cast<unsigned char*>(ws);
     a->status = reinterpret_cast<uint32_t*>(w + WS_STATUS_OFF);
+    a->done_counter = reinterpret_cast<uint32_t*>(w + WS_DONE_OFF);
     a->sk_counters = reinterpret_cast<uint32_t*>(w + WS_TILECNT_OFF);
     a->sk_partials = reinterpret_cast<float*>(w + WS_HEADER_BYTES);
   }
@@ -323,14 +324,6 @@ static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hip
   if (e0) FLUX_HIP(hipEventRecord(e0, s));
   FLUX_HIP(g_cfgs[pl.cfg].launch(epi, wait, pl.edge, a, grid, s));
   if (e1) FLUX_HIP(hipEventRecord(e1, s));
-  return FLUX_OK;
-}
-
-static int clear_header(void* ws, hipStream_t s) {
-  const int words = (int)(WS_HEADER_BYTES / 4);
-  hipLaunchKernelGGL(preset_kernel, dim3((words + 255) / 256), dim3(256), 0, s,
-                     (uint32_t*)nullptr, 0, 0, 0, static_cast<uint32_t*>(ws), words);
-  FLUX_HIP(hipGetLastError());
   return FLUX_OK;
 }
 
@@ -426,6 +419,23 @@ size_t flux_workspace_bytes(int op, const flux_problem_t* p) {
   return workspace_need(pl);
 }
 
+int flux_init_buffers(int op, const flux_problem_t* p, void* workspace, size_t workspace_bytes,
+                      uint32_t* signals, void* stream) {
+  Plan pl;
+  int st = make_plan(op, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (workspace != nullptr && (workspace_bytes < WS_HEADER_BYTES || !aligned16(workspace))) return FLUX_ERR_WORKSPACE;
+  if (workspace == nullptr && signals == nullptr) return FLUX_OK;
+  const int n_sig = (op == FLUX_OP_AG && signals) ? p->R * pl.ctpc : 0;
+  const int words = workspace ? (int)(WS_HEADER_BYTES / 4) : 0;
+  if (std::max(words, n_sig) == 0) return FLUX_OK;
+  hipLaunchKernelGGL(preset_kernel, dim3((std::max(words, n_sig) + 255) / 256), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), n_sig ? signals : (uint32_t*)nullptr, n_sig,
+                     p->rank * pl.ctpc, (p->rank + 1) * pl.ctpc, static_cast<uint32_t*>(workspace), words);
+  FLUX_HIP(hipGetLastError());
+  return FLUX_OK;
+}
+
 int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* tile_n, int32_t* tile_k,
                     int32_t* split_k, int32_t* n_xcd) {
   Plan pl;
@@ -486,7 +496,6 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   a.B = static_cast<const __bf16*>(B);
   for (int r = 0; r < p->R; ++r) { a.peers[r] = peer_partials[r]; a.outs[r] = out_slices[r]; }
   build_tile_map(FLUX_OP_RS, p, pl, nullptr, &a.tm);
-  if (pl.split_k > 1) { st = clear_header(workspace, s); if (st != FLUX_OK) return st; }
   return launch_gemm(pl, EPI_RS, 0, a, s);
 }
 
@@ -519,15 +528,11 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   a.B = static_cast<const __bf16*>(B);
   a.C = C;
   a.signals = signals;
+  a.n_signals = p->R * pl.ctpc;
+  a.sig_local_lo = p->rank * pl.ctpc;
+  a.sig_local_hi = (p->rank + 1) * pl.ctpc;
   build_tile_map(FLUX_OP_AG, p, pl, order, &a.tm);
 
-  // preset: local signals 1, the rest 0; counters and status cleared
-  const int n_sig = p->R * pl.ctpc;
-  const int words = (int)(WS_HEADER_BYTES / 4);
-  hipLaunchKernelGGL(preset_kernel, dim3((std::max(words, n_sig) + 255) / 256), dim3(256), 0, cs,
-                     signals, n_sig, p->rank * pl.ctpc, (p->rank + 1) * pl.ctpc,
-                     static_cast<uint32_t*>(workspace), words);
-  FLUX_HIP(hipGetLastError());
   // local chunk (its signal is preset, so it must be in place before the kernel starts)
   const __bf16* local_dst = static_cast<const __bf16*>(A_agg) + (size_t)p->rank * chunk_elems;
   if (A_chunks[p->rank] != static_cast<const void*>(local_dst)) {
@@ -555,12 +560,10 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   }
   st = launch_gemm(pl, EPI_PLAIN, 1, a, cs);
   if (st != FLUX_OK) return st;
-  // join + reset of the signals, ordered after both the GEMM and the copy driver
+  // join: compute_stream continues only after the copy driver has finished too (the signals
+  // were already put back by the last workgroup past its wait)
   FLUX_HIP(hipEventRecord(ev_join, xs));
   FLUX_HIP(hipStreamWaitEvent(cs, ev_join, 0));
-  hipLaunchKernelGGL(preset_kernel, dim3((n_sig + 255) / 256), dim3(256), 0, cs,
-                     signals, n_sig, p->rank * pl.ctpc, (p->rank + 1) * pl.ctpc, (uint32_t*)nullptr, 0);
-  FLUX_HIP(hipGetLastError());
   return FLUX_OK;
 }
 
@@ -596,7 +599,6 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
     if (do_gemm) {
       if (!A || !aligned16(A)) return FLUX_ERR_INVALID_ARG;
       a.A = static_cast<const __bf16*>(A);
-      if (pl.split_k > 1) { st = clear_header(workspace, s); if (st != FLUX_OK) return st; }
       st = launch_gemm(pl, EPI_PLAIN, 0, a, s);
       if (st != FLUX_OK) return st;
     }
@@ -638,7 +640,6 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
   }
   if (do_gemm) {
     a.A = static_cast<const __bf16*>(A_agg);
-    if (pl.split_k > 1) { st = clear_header(workspace, s); if (st != FLUX_OK) return st; }
     st = launch_gemm(pl, EPI_PLAIN, 0, a, s);
     if (st != FLUX_OK) return st;
   }

@@ -30,6 +30,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 // ---- workspace layout (bytes) -------------------------------------------------------------
 constexpr size_t WS_STATUS_OFF = 0;        // uint32 code, uint32 detail
+constexpr size_t WS_DONE_OFF = 16;         // uint32: workgroups that are past their signal wait
 constexpr size_t WS_COUNTER_OFF = 256;     // uint32 per communication tile (copy kernel arrivals)
 constexpr int MAX_COMM_TILES = 1024;
 constexpr size_t WS_TILECNT_OFF = WS_COUNTER_OFF + 4 * MAX_COMM_TILES;   // split-K arrival counters
@@ -71,8 +72,10 @@ struct GemmArgs {
   int32_t R, rank, S;        // S = M / R
   int32_t partial_f32, out_f32;
   // all-gather prologue
-  const uint32_t* signals;
+  uint32_t* signals;
   int32_t rows_per_signal;
+  int32_t n_signals, sig_local_lo, sig_local_hi;   // local communication tiles: [lo, hi)
+  uint32_t* done_counter;
   uint32_t* status;
   unsigned long long timeout_ticks;
   // split-K
@@ -274,6 +277,9 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& a, void* const* ld
 // WaitSignal (Alg. 2): one lane polls every signal covering rows [m0, m1) with coherent loads,
 // then an acquire fence makes the copied rows visible; the workgroup barrier hands that to the
 // other waves.  Bounded: past `timeout_ticks` the tile is given up and the status block says so.
+// A workgroup never looks at the signals again after this, so the last workgroup of the grid
+// to get here puts the signal array back into its preset state for the next call (the reset
+// "after the GEMM" of Sec. 4.3, without a separate launch).
 __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, int* lds_ok) {
   if (threadIdx.x == 0) {
     const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
@@ -291,6 +297,13 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
     }
     __atomic_thread_fence(__ATOMIC_ACQUIRE);   // system scope: covers copy kernels and DMA writers
     *lds_ok = ok;
+    const uint32_t prev = atomicAdd(a.done_counter, 1u);
+    if (prev == gridDim.x - 1) {
+      for (int i = 0; i < a.n_signals; ++i)
+        __hip_atomic_store(a.signals + i, (i >= a.sig_local_lo && i < a.sig_local_hi) ? 1u : 0u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(a.done_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
   __syncthreads();
   return *lds_ok != 0;
@@ -469,6 +482,20 @@ struct DmaLoader {
     voff_b = (k * a.N + n0 + ((spb ^ swz_b<C::B_SLOTS>(k)) << 3)) * 2;
   }
 
+  static constexpr int N_INSTR = A_INSTR + B_INSTR;
+
+  // same with an index that is constant after loop unrolling
+  __device__ __forceinline__ void issue_dyn(int idx, const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
+    if (idx < A_INSTR) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (idx * NW + wave) * 1024), 16, voff_a,
+                                               (k0 + idx * 8 * NW * a.K) * 2, 0, 0);
+    } else {
+      const int p = idx - A_INSTR;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
+                                               (k0 + p * RPI * NW) * a.N * 2, 0, 0);
+    }
+  }
+
   // all loads of one K-slab for this wave; `stage` is the base of the LDS stage being filled
   __device__ __forceinline__ void issue(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
 #pragma unroll
@@ -484,6 +511,73 @@ struct DmaLoader {
     __builtin_amdgcn_sched_barrier(0);
   }
 };
+
+template <class C>
+__device__ __forceinline__ bf16x8 frag_a(const unsigned char* stage, int ks, int mi, int wm, int lane) {
+  const int row = wm * C::WTM + mi * 32 + (lane & 31);
+  const int q = ks * 2 + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(stage + row * (C::BK * 2) + ((q ^ swz_a<C::A_SLOTS>(row)) << 4));
+}
+
+template <class C>
+__device__ __forceinline__ bf16x8 frag_b(const unsigned char* stage, int ks, int ni, int wn, int lane) {
+  const int g = lane >> 4, i = lane & 15;
+  const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
+  const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);
+  const int off = C::A_BYTES + k * (C::BN * 2) + ((((n >> 3) ^ swz_b<C::B_SLOTS>(k))) << 4) + ((n >> 2) & 1) * 8;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off + 4 * C::BN * 2));
+  s16x8 w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+// One K-slab out of LDS stage `cur`, software-pipelined by hand:
+//   * the MFMAs run in (ks, mi) groups of NI; the fragments of k-step ks+1 are fetched while the
+//     MFMAs of ks run (two register sets);
+//   * the wave's DMA loads for the NEXT slab (into `nxt`) are dealt out one group at a time.  A
+//     wave issues in order, and a burst of loads would hold it in the memory pipeline's queue
+//     for about as long as the slab's MFMAs take; spread out, the loads drain behind the MFMAs.
+// Loads are only placed in the first SPREAD_NUM/SPREAD_DEN of the groups so the last one has
+// time to land before the end-of-slab wait.
+template <class C, bool ISSUE>
+__device__ __forceinline__ void mma_stage_dma(const unsigned char* cur, unsigned char* nxt, const DmaLoader<C>& ld,
+                                              const GemmArgs& a, int k_next, int wave, int wm, int wn, int lane,
+                                              f32x16 (&acc)[C::MI][C::NI]) {
+  constexpr int KS = C::BK / 16;
+  constexpr int G = KS * C::MI;                       // MFMA groups in the slab
+  constexpr int L = DmaLoader<C>::N_INSTR;            // loads to place
+  constexpr int GS = (G * 3 + 3) / 4;                 // groups that carry loads
+  bf16x8 af[2][C::MI], bfr[2][C::NI];
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi) af[0][mi] = frag_a<C>(cur, 0, mi, wm, lane);
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) bfr[0][ni] = frag_b<C>(cur, 0, ni, wn, lane);
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi) {
+      const int g = ks * C::MI + mi;
+      // loads [g*L/GS, (g+1)*L/GS) go with group g (compile-time after unrolling)
+      if (ISSUE && g < GS) {
+        const int lo = g * L / GS, hi = (g + 1) * L / GS;
+#pragma unroll
+        for (int idx = 0; idx < L; ++idx)
+          if (idx >= lo && idx < hi) ld.issue_dyn(idx, a, nxt, k_next, wave);
+      }
+      if (mi == 0 && ks + 1 < KS) {
+#pragma unroll
+        for (int m2 = 0; m2 < C::MI; ++m2) af[(ks + 1) & 1][m2] = frag_a<C>(cur, ks + 1, m2, wm, lane);
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni) bfr[(ks + 1) & 1][ni] = frag_b<C>(cur, ks + 1, ni, wn, lane);
+      }
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][mi], bfr[ks & 1][ni], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
 
 __device__ __forceinline__ void wait_vm0_and_barrier() {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-bound loads have landed
@@ -534,18 +628,20 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   ld.issue(a, stage0, k_begin, wave);
   wait_vm0_and_barrier();
   int kt = 0;
-  for (; kt + 2 <= KT; kt += 2) {
-    ld.issue(a, stage1, k_begin + (kt + 1) * C::BK, wave);
-    mma_stage<C>(stage0, wm, wn, lane, acc);
+  for (; kt + 2 < KT; kt += 2) {       // both halves have a next slab to fetch
+    mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
-    if (kt + 2 < KT) ld.issue(a, stage0, k_begin + (kt + 2) * C::BK, wave);
-    mma_stage<C>(stage1, wm, wn, lane, acc);
+    mma_stage_dma<C, true>(stage1, stage0, ld, a, k_begin + (kt + 2) * C::BK, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
   }
-  if (kt < KT) {
-    mma_stage<C>(stage0, wm, wn, lane, acc);
-    __syncthreads();
+  if (kt + 2 == KT) {
+    mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
+    wait_vm0_and_barrier();
+    mma_stage_dma<C, false>(stage1, stage0, ld, a, 0, wave, wm, wn, lane, acc);
+  } else if (kt + 1 == KT) {
+    mma_stage_dma<C, false>(stage0, stage1, ld, a, 0, wave, wm, wn, lane, acc);
   }
+  __syncthreads();
   gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, ntiles, m0, n0, tid, lane, wave, wm, wn);
 }
 

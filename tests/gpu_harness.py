@@ -57,6 +57,9 @@ def run_rs(w: fi.Workload, rank: int, A, B, peers, tile_config=0, split_k=0, fla
     fill = float("nan") if poison else 0.0
     outs = [torch.full((w.S, w.N), fill, dtype=_TORCH[w.out_dtype], device=DEV) for _ in range(w.R)]
     ws = workspace_for(fb.FLUX_OP_RS, p)
+    if ws is not None:
+        ws.fill_(-1)                                  # garbage until initialised
+        fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
     fb.flux_gemm_rs(p, dA, dB, dpeers, outs, ws)
     torch.cuda.synchronize()
     return outs
@@ -64,7 +67,7 @@ def run_rs(w: fi.Workload, rank: int, A, B, peers, tile_config=0, split_k=0, fla
 
 def run_ag(w: fi.Workload, rank: int, chunks, B, arrival, tile_config=0, split_k=0, flags=0,
            comm_tiles_per_chunk=0, copy_workgroups=0, local_in_place=False, delay_copy_cycles=0,
-           timeout_ticks=TEST_TIMEOUT_TICKS):
+           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1):
     """Fused AllGather-GEMM through the C ABI.  A_agg starts NaN-poisoned so a tile that reads
     rows before their signal shows up in C.  Returns (C, A_agg, signals, status)."""
     p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, tile_config, split_k, flags,
@@ -77,17 +80,26 @@ def run_ag(w: fi.Workload, rank: int, chunks, B, arrival, tile_config=0, split_k
         dchunks[rank] = A_agg[rank * w.S:(rank + 1) * w.S]
     Cout = torch.full((w.M, w.N), float("nan"), dtype=_TORCH[w.out_dtype], device=DEV)
     nsig = w.R * max(1, comm_tiles_per_chunk)
-    signals = torch.full((nsig,), 12345, dtype=torch.int32, device=DEV)     # garbage on entry
+    signals = torch.full((nsig,), 12345, dtype=torch.int32, device=DEV)     # garbage until initialised
     ws = workspace_for(fb.FLUX_OP_AG, p)
+    ws.fill_(-1)
+    fb.flux_init_buffers(fb.FLUX_OP_AG, p, ws, signals)
     compute = torch.cuda.current_stream()
     copy = torch.cuda.Stream()
     torch.cuda.synchronize()
     if delay_copy_cycles:
         with torch.cuda.stream(copy):
             torch.cuda._sleep(int(delay_copy_cycles))
-    fb.flux_ag_gemm(p, dchunks, A_agg, dB, Cout, signals, arrival, ws, compute, copy)
-    torch.cuda.synchronize()
-    status = fb.flux_query_status(ws)
+    results = []
+    for _ in range(repeat):      # later calls rely on the state the previous call left behind
+        if results:
+            A_agg[:rank * w.S].fill_(float("nan"))
+            A_agg[(rank + 1) * w.S:].fill_(float("nan"))
+            Cout.fill_(float("nan"))
+        fb.flux_ag_gemm(p, dchunks, A_agg, dB, Cout, signals, arrival, ws, compute, copy)
+        torch.cuda.synchronize()
+        results.append(fb.flux_query_status(ws))
+    status = results[-1] if all(r == results[0] for r in results) else results
     return Cout, A_agg, signals, status
 
 

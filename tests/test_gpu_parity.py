@@ -79,7 +79,8 @@ def test_ag_exact_integers_bitwise(cfg):
     for rank in (0, 2):
         _say("int_ag cfg", cfg, "rank", rank)
         chunks, B, arrival = fi.make_ag_inputs(w, rank)
-        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=cfg)
+        # three calls in a row on the same buffers: each must leave signals and counters ready
+        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=cfg, repeat=3)
         assert status == (fb.FLUX_OK, 0)
         _, want = gh.oracle_ag(w, chunks, B)
         gh.assert_bits_equal(Cg, want, f"cfg {cfg}")
@@ -206,12 +207,20 @@ def test_split_k_bitwise_on_integers(split):
     rank = 4
     A, B, peers = fi.make_rs_inputs(w, rank)
     _, want = gh.oracle_rs(w, rank, A, B, peers)
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
     for cfg in (5, 6, 4):
         _say("split-k", split, "cfg", cfg)
-        for rep in range(2):        # second launch reuses the counters the first one reset
-            outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg, split_k=split)
+        p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype, cfg, split)
+        ws = gh.workspace_for(fb.FLUX_OP_RS, p)
+        ws.fill_(-1)
+        fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+        for rep in range(3):        # later launches reuse the counters the earlier ones put back
+            outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
+            fb.flux_gemm_rs(p, dA, dB, dpeers, outs, ws)
+            torch.cuda.synchronize()
             for r in range(w.R):
-                gh.assert_bits_equal(outs[r], want[r], f"slice {r}")
+                gh.assert_bits_equal(outs[r], want[r], f"rep {rep} slice {r}")
 
 
 # ---------------------------------------------------------------------------------------------
