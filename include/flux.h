@@ -69,6 +69,10 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
 #define FLUX_FLAG_COPY_MEMCPY  0x4u  /* AG copy driver = hipMemcpyAsync + stream write-value per
                                         communication tile instead of the copy kernel */
 
+#define FLUX_FLAG_COPY_FIRST    0x8u  /* AG: hold the GEMM grid back (stream wait-value) until every
+                                        copy workgroup is running; off by default, the wait costs
+                                        more than it saves when the copy kernel is launched first */
+
 /* flux_gemm_ref_unfused phases */
 #define FLUX_PHASE_GEMM 0x1
 #define FLUX_PHASE_COMM 0x2

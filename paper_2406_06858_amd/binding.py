@@ -20,7 +20,7 @@ FLUX_OK, FLUX_ERR_INVALID_ARG, FLUX_ERR_SHAPE, FLUX_ERR_UNSUPPORTED = 0, 1, 2, 3
 FLUX_ERR_WORKSPACE, FLUX_ERR_HIP, FLUX_ERR_TIMEOUT = 4, 5, 6
 FLUX_BF16, FLUX_F32 = 0, 1
 FLUX_OP_RS, FLUX_OP_AG = 0, 1
-FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY = 0x1, 0x2, 0x4
+FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY, FLUX_FLAG_COPY_FIRST = 0x1, 0x2, 0x4, 0x8
 FLUX_PHASE_GEMM, FLUX_PHASE_COMM = 0x1, 0x2
 FLUX_MAX_RANKS = 16
 

@@ -55,36 +55,54 @@ struct CopyArgs {
   unsigned long long tile_vec;        // 16-byte vectors per communication tile
   uint32_t* signals;                  // may be null (baseline copy)
   uint32_t* counters;
+  uint32_t* started;                  // may be null
 };
+
+// 16-byte store at device scope: written through this die's L2, so that a reader on another
+// accelerator die needs no write-back of the whole L2 to see it.
+__device__ __forceinline__ void store_through(uint4* p, const u32x4& d) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+}
+
+// streaming 16-byte load (the source is read once)
+__device__ __forceinline__ u32x4 load_stream(const uint4* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
 
 // Copy driver as one kernel: all workgroups move communication tile after communication tile
 // in transfer order (DataTransfer of Alg. 3); the workgroup that finishes a tile last sets its
-// signal (SetSignal) after every workgroup's stores have been released to device scope.
+// signal (SetSignal).  The data is stored write-through and each wave waits for its stores to
+// be acknowledged before the workgroup counts itself in, so no cache write-back fence (which
+// would sweep the whole L2 of the die, per tile) is needed to publish a tile.
 __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
   const unsigned long long stride = (unsigned long long)gridDim.x * blockDim.x;
   const unsigned long long t0 = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x;
   const int n_tiles = c.n_order * c.tiles_per_chunk;
+  if (c.started != nullptr && threadIdx.x == 0)
+    __hip_atomic_fetch_add(c.started, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   for (int idx = 0; idx < n_tiles; ++idx) {
     const int chunk = c.order[idx / c.tiles_per_chunk];
     const int t = idx % c.tiles_per_chunk;
     const uint4* __restrict__ src = c.src[chunk] + (unsigned long long)t * c.tile_vec;
     uint4* __restrict__ dst = c.dst + (unsigned long long)chunk * c.chunk_vec + (unsigned long long)t * c.tile_vec;
     unsigned long long i = t0;
-    for (; i + 3 * stride < c.tile_vec; i += 4 * stride) {
-      const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-      dst[i] = v0; dst[i + stride] = v1; dst[i + 2 * stride] = v2; dst[i + 3 * stride] = v3;
+    for (; i + 7 * stride < c.tile_vec; i += 8 * stride) {
+      u32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = load_stream(src + i + u * stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) store_through(dst + i + u * stride, v[u]);
     }
-    for (; i < c.tile_vec; i += stride) dst[i] = src[i];
+    for (; i < c.tile_vec; i += stride) store_through(dst + i, load_stream(src + i));
     if (c.signals != nullptr) {
       const int flag = chunk * c.tiles_per_chunk + t;
-      __threadfence();
+      __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
       __syncthreads();
       if (threadIdx.x == 0) {
-        const uint32_t prev = atomicAdd(c.counters + flag, 1u);
+        const uint32_t prev = __hip_atomic_fetch_add(c.counters + flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (prev == gridDim.x - 1) {
-          c.counters[flag] = 0u;
-          __threadfence();
-          __hip_atomic_store(c.signals + flag, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+          __hip_atomic_store(c.counters + flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(c.signals + flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
       }
     }
@@ -108,22 +126,24 @@ __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
     const size_t off = (size_t)gm * a.N + gn;
     float x[8];
     if (a.out_f32) {
-      const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.C) + off);
-      const float4 u = p[0], w = p[1];
-      x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w; x[4] = w.x; x[5] = w.y; x[6] = w.z; x[7] = w.w;
+      const float* p = static_cast<const float*>(a.C) + off;
+      const uint4 u = ld_stream16(p), w = ld_stream16(p + 4);
+      x[0] = __uint_as_float(u.x); x[1] = __uint_as_float(u.y); x[2] = __uint_as_float(u.z); x[3] = __uint_as_float(u.w);
+      x[4] = __uint_as_float(w.x); x[5] = __uint_as_float(w.y); x[6] = __uint_as_float(w.z); x[7] = __uint_as_float(w.w);
     } else {
-      const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const __bf16*>(a.C) + off);
+      const uint4 w = ld_stream16(static_cast<const __bf16*>(a.C) + off);
       x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
       x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
     }
     for (int j = 0; j < a.R; ++j) {
       if (j == a.rank) continue;
       if (a.partial_f32) {
-        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.peers[j]) + off);
-        const float4 u = p[0], w = p[1];
-        x[0] += u.x; x[1] += u.y; x[2] += u.z; x[3] += u.w; x[4] += w.x; x[5] += w.y; x[6] += w.z; x[7] += w.w;
+        const float* p = static_cast<const float*>(a.peers[j]) + off;
+        const uint4 u = ld_stream16(p), w = ld_stream16(p + 4);
+        x[0] += __uint_as_float(u.x); x[1] += __uint_as_float(u.y); x[2] += __uint_as_float(u.z); x[3] += __uint_as_float(u.w);
+        x[4] += __uint_as_float(w.x); x[5] += __uint_as_float(w.y); x[6] += __uint_as_float(w.z); x[7] += __uint_as_float(w.w);
       } else {
-        const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const __bf16*>(a.peers[j]) + off);
+        const uint4 w = ld_stream16(static_cast<const __bf16*>(a.peers[j]) + off);
         x[0] += bf16_lo(w.x); x[1] += bf16_hi(w.x); x[2] += bf16_lo(w.y); x[3] += bf16_hi(w.y);
         x[4] += bf16_lo(w.z); x[5] += bf16_hi(w.z); x[6] += bf16_lo(w.w); x[7] += bf16_hi(w.w);
       }
@@ -131,14 +151,14 @@ __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
     const int r = gm / a.S;
     const size_t o = (size_t)(gm - r * a.S) * a.N + gn;
     if (a.out_f32) {
-      float4* q = reinterpret_cast<float4*>(static_cast<float*>(a.outs[r]) + o);
-      q[0] = make_float4(x[0], x[1], x[2], x[3]);
-      q[1] = make_float4(x[4], x[5], x[6], x[7]);
+      float* q = static_cast<float*>(a.outs[r]) + o;
+      st_stream16(q, make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])));
+      st_stream16(q + 4, make_uint4(__float_as_uint(x[4]), __float_as_uint(x[5]), __float_as_uint(x[6]), __float_as_uint(x[7])));
     } else {
       uint4 w;
       w.x = pack_bf16x2(x[0], x[1]); w.y = pack_bf16x2(x[2], x[3]);
       w.z = pack_bf16x2(x[4], x[5]); w.w = pack_bf16x2(x[6], x[7]);
-      *reinterpret_cast<uint4*>(static_cast<__bf16*>(a.outs[r]) + o) = w;
+      st_stream16(static_cast<__bf16*>(a.outs[r]) + o, w);
     }
   }
 }
@@ -312,6 +332,7 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
     unsigned char* w = static_cast<unsigned char*>(ws);
     a->status = reinterpret_cast<uint32_t*>(w + WS_STATUS_OFF);
     a->done_counter = reinterpret_cast<uint32_t*>(w + WS_DONE_OFF);
+    a->started_counter = reinterpret_cast<uint32_t*>(w + WS_STARTED_OFF);
     a->sk_counters = reinterpret_cast<uint32_t*>(w + WS_TILECNT_OFF);
     a->sk_partials = reinterpret_cast<float*>(w + WS_HEADER_BYTES);
   }
@@ -328,7 +349,9 @@ static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hip
 }
 
 static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* const* chunks, void* A_agg,
-                       const int* order, int n_order, uint32_t* signals, void* ws, hipStream_t s) {
+                       const int* order, int n_order, uint32_t* signals, void* ws, hipStream_t s,
+                       int* wgs_out = nullptr) {
+  if (wgs_out) *wgs_out = 0;
   if (n_order == 0) return FLUX_OK;
   CopyArgs c;
   std::memset(&c, 0, sizeof(c));
@@ -343,9 +366,11 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
   c.signals = signals;
   c.counters = ws ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_COUNTER_OFF) : nullptr;
   int wgs = p->copy_workgroups;
-  if (wgs <= 0) wgs = signals ? 64 : 1024;
+  if (wgs <= 0) wgs = signals ? 256 : 1024;   // fused: one per CU, the transfer is over before most tiles need it
   const unsigned long long max_useful = (c.tile_vec + 255) / 256;
   if ((unsigned long long)wgs > max_useful) wgs = (int)std::max<unsigned long long>(1, max_useful);
+  c.started = (signals && ws) ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_STARTED_OFF) : nullptr;
+  if (wgs_out) *wgs_out = wgs;
   hipLaunchKernelGGL(ag_copy_kernel, dim3(wgs), dim3(256), 0, s, c);
   FLUX_HIP(hipGetLastError());
   return FLUX_OK;
@@ -555,8 +580,14 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
       }
     }
   } else {
-    st = launch_copy(p, pl, A_chunks, A_agg, order, p->R - 1, signals, workspace, xs);
+    int copy_wgs = 0;
+    st = launch_copy(p, pl, A_chunks, A_agg, order, p->R - 1, signals, workspace, xs, &copy_wgs);
     if (st != FLUX_OK) return st;
+    // Optionally the GEMM grid is not dispatched before every copy workgroup is running: waiting
+    // tiles hold their CU, so a copy driver that came second finds no room until tiles finish.
+    if (copy_wgs > 0 && (p->flags & FLUX_FLAG_COPY_FIRST))
+      FLUX_HIP(hipStreamWaitValue32(cs, static_cast<unsigned char*>(workspace) + WS_STARTED_OFF, (uint32_t)copy_wgs,
+                                    hipStreamWaitValueGte, 0xffffffffu));
   }
   st = launch_gemm(pl, EPI_PLAIN, 1, a, cs);
   if (st != FLUX_OK) return st;

@@ -31,6 +31,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 // ---- workspace layout (bytes) -------------------------------------------------------------
 constexpr size_t WS_STATUS_OFF = 0;        // uint32 code, uint32 detail
 constexpr size_t WS_DONE_OFF = 16;         // uint32: workgroups that are past their signal wait
+constexpr size_t WS_STARTED_OFF = 32;      // uint32: copy-driver workgroups that have started
 constexpr size_t WS_COUNTER_OFF = 256;     // uint32 per communication tile (copy kernel arrivals)
 constexpr int MAX_COMM_TILES = 1024;
 constexpr size_t WS_TILECNT_OFF = WS_COUNTER_OFF + 4 * MAX_COMM_TILES;   // split-K arrival counters
@@ -76,6 +77,7 @@ struct GemmArgs {
   int32_t rows_per_signal;
   int32_t n_signals, sig_local_lo, sig_local_hi;   // local communication tiles: [lo, hi)
   uint32_t* done_counter;
+  uint32_t* started_counter;
   uint32_t* status;
   unsigned long long timeout_ticks;
   // split-K
@@ -105,6 +107,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2 v = {lo, hi};
   bf16x2 h = __builtin_convertvector(v, bf16x2);   // round-to-nearest-even
   return __builtin_bit_cast(uint32_t, h);
+}
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// Streaming (non-temporal) 16-byte accesses for data touched exactly once: peer partials and
+// outputs must not push the A/B panels, which are re-read many times, out of the L2.
+__device__ __forceinline__ uint4 ld_stream16(const void* p) {
+  const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void st_stream16(void* p, const uint4& v) {
+  const u32x4 d = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(d, static_cast<u32x4*>(p));
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -232,16 +247,16 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& a, void* const* ld
 #pragma unroll
       for (int j = 0; j < FLUX_MAX_RANKS; ++j)
         if (j < a.R && j != a.rank) {
-          const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.peers[j]) + off);
-          const float4 x = p[0], y = p[1];
-          v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w;
-          v[4] += y.x; v[5] += y.y; v[6] += y.z; v[7] += y.w;
+          const float* p = static_cast<const float*>(a.peers[j]) + off;
+          const uint4 x = ld_stream16(p), y = ld_stream16(p + 4);
+          v[0] += __uint_as_float(x.x); v[1] += __uint_as_float(x.y); v[2] += __uint_as_float(x.z); v[3] += __uint_as_float(x.w);
+          v[4] += __uint_as_float(y.x); v[5] += __uint_as_float(y.y); v[6] += __uint_as_float(y.z); v[7] += __uint_as_float(y.w);
         }
     } else {
       uint4 w[FLUX_MAX_RANKS];
 #pragma unroll
       for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-        if (j < a.R && j != a.rank) w[j] = *reinterpret_cast<const uint4*>(static_cast<const __bf16*>(a.peers[j]) + off);
+        if (j < a.R && j != a.rank) w[j] = ld_stream16(static_cast<const __bf16*>(a.peers[j]) + off);
 #pragma unroll
       for (int j = 0; j < FLUX_MAX_RANKS; ++j)
         if (j < a.R && j != a.rank) {
@@ -263,14 +278,14 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& a, void* const* ld
     o = (size_t)gm * a.N + gn;
   }
   if (a.out_f32) {
-    float4* q = reinterpret_cast<float4*>(static_cast<float*>(base) + o);
-    q[0] = make_float4(v[0], v[1], v[2], v[3]);
-    q[1] = make_float4(v[4], v[5], v[6], v[7]);
+    float* q = static_cast<float*>(base) + o;
+    st_stream16(q, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+    st_stream16(q + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
   } else {
     uint4 w;
     w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
     w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
-    *reinterpret_cast<uint4*>(static_cast<__bf16*>(base) + o) = w;
+    st_stream16(static_cast<__bf16*>(base) + o, w);
   }
 }
 
@@ -302,6 +317,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
       for (int i = 0; i < a.n_signals; ++i)
         __hip_atomic_store(a.signals + i, (i >= a.sig_local_lo && i < a.sig_local_hi) ? 1u : 0u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(a.started_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       __hip_atomic_store(a.done_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
