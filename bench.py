@@ -33,6 +33,13 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--ramp-seconds", type=float, default=2.0, help="untimed load before the warm-up steps")
+    ap.add_argument("--ag-flags", type=int, default=0,
+                    help="FLUX_FLAG_* bits for the AllGather-GEMM (8 = copy-first: needed under rocprofv3 --pmc, "
+                         "which runs kernels one at a time, so the copy driver must be dispatched before the GEMM)")
+    ap.add_argument("--serial-kernels", type=int, default=0, metavar="N",
+                    help="counter-collection mode: run N rounds of [chunk copy, AllGather-GEMM kernel on the gathered "
+                         "matrix, fused GEMM-ReduceScatter] one kernel at a time and exit (rocprofv3 --pmc serialises "
+                         "kernels, so the concurrent copy driver of the fused call cannot make progress under it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-config / overlap-efficiency section")
     args = ap.parse_args()
@@ -146,9 +153,19 @@ def main() -> int:
                 "fused_frac_hbm_peak": round(op.alg_bytes() / t_fus / 1e6 / HBM_PEAK_GBS, 4)}
 
     # ---- the timed workload: MLP up-projection (AG-GEMM) + down-projection (GEMM-RS) ----
-    ag = AG(W["c2_ag"], rank=2)
+    ag = AG(W["c2_ag"], rank=2, flags=args.ag_flags)
     rs = RS(W["c3_rs"], rank=2)
     flops_step = ag.w.flops + rs.w.flops
+
+    if args.serial_kernels > 0:
+        for _ in range(args.serial_kernels):
+            ag.unfused(fb.FLUX_PHASE_COMM)      # plain copy of 7 chunks: 58.7 MB read + 58.7 MB written
+            ag.unfused(fb.FLUX_PHASE_GEMM)      # same tile configuration as the fused kernel, no signal wait
+            rs.fused()
+            torch.cuda.synchronize()
+        print(json.dumps({"mode": "serial-kernels", "rounds": args.serial_kernels,
+                          "copy_bytes_read": 7 * ag.w.S * ag.w.K * 2, "copy_bytes_written": 7 * ag.w.S * ag.w.K * 2}))
+        return 0
 
     def step(prof=None):
         if prof is not None:
@@ -199,11 +216,17 @@ def main() -> int:
         print("bench.py: result check against the CPU oracle FAILED", file=sys.stderr)
         return 1
 
+    # Traffic behind the L2 per launch of the AllGather-GEMM kernel, from two rocprofv3 --pmc runs
+    # (FETCH_SIZE, WRITE_SIZE) of `bench.py --serial-kernels 10`, each scaled by what the same
+    # counter reads for the 58.7 MB chunk copy (1.9984 and 1.0000 KiB per count):
+    # 776.6 MB fetched + 32.4 MB written (profiles/bench_c2ag_c3rs_pmc_traffic.txt).
+    traffic_bytes = 776.6e6 + 32.4e6
     # roofline of the dominant kernel: the fused AllGather-GEMM kernel (bf16 MFMA bound)
     ag_tflops = ag.w.flops / (ag_ms * 1e-3) / 1e12
     roofline = {"kernel": "gemm_kernel<AllGather prologue> on c2_ag", "bound": "mfma",
                 "achieved": round(ag_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ag_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(ag_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic_bytes,
+                "traffic_note": "bytes per launch requested by the L2s from Infinity Cache/HBM; algorithmic 155.2e6",
                 "avg_kernel_ms": round(ag_ms, 4),
                 "second_kernel": {"kernel": "gemm_kernel<ReduceScatter epilogue> on c3_rs",
                                   "avg_kernel_ms": round(rs_ms, 4),

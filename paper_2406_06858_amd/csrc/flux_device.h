@@ -643,21 +643,22 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   ld.init(a, m0, n0, wave, lane);
   ld.issue(a, stage0, k_begin, wave);
   wait_vm0_and_barrier();
+  // Every slab prefetches its successor; the last one fetches itself again (into the stage that
+  // is not being read), which keeps a single code shape for the loop instead of a prefetch-free
+  // copy of it that the register allocator handles badly.
+  const int k_last = k_begin + (KT - 1) * C::BK;
   int kt = 0;
-  for (; kt + 2 < KT; kt += 2) {       // both halves have a next slab to fetch
+  for (; kt + 2 <= KT; kt += 2) {
     mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
-    mma_stage_dma<C, true>(stage1, stage0, ld, a, k_begin + (kt + 2) * C::BK, wave, wm, wn, lane, acc);
+    const int k2 = k_begin + (kt + 2) * C::BK;
+    mma_stage_dma<C, true>(stage1, stage0, ld, a, k2 < k_last ? k2 : k_last, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
   }
-  if (kt + 2 == KT) {
-    mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
+  if (kt < KT) {
+    mma_stage_dma<C, true>(stage0, stage1, ld, a, k_last, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
-    mma_stage_dma<C, false>(stage1, stage0, ld, a, 0, wave, wm, wn, lane, acc);
-  } else if (kt + 1 == KT) {
-    mma_stage_dma<C, false>(stage0, stage1, ld, a, 0, wave, wm, wn, lane, acc);
   }
-  __syncthreads();
   gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, ntiles, m0, n0, tid, lane, wave, wm, wn);
 }
 
