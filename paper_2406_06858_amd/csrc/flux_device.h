@@ -335,37 +335,54 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
                                           int m0, int n0, int tid, int lane, int wave, int wm, int wn) {
   // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
   if (a.split_k > 1) {
+    // Partials are stored and re-read with device-scope (sc1) accesses, which go through the
+    // die's L2 to memory: the hand-over between workgroups on different dies then needs neither
+    // an L2 write-back nor an L2 invalidate, only "my stores are acknowledged" before counting in.
+    constexpr int SC1 = 16;                               // cache-policy bit: device scope
+    constexpr int BLOCK_BYTES = C::BM * C::BN * 4;
+    constexpr int NV = C::MI * C::NI * 4;                 // 16-byte vectors per thread
     float* mine = a.sk_partials + ((size_t)split * ntiles + tile) * (C::BM * C::BN);
-    // layout inside a tile's partial block: [mi][ni][e][thread] -> coalesced 4-byte columns
+    __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(mine, 0, BLOCK_BYTES, 0x00027000);
+    // layout inside a tile's partial block: [vector index][thread] -> coalesced 16-byte columns
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          mine[((mi * C::NI + ni) * 16 + e) * C::NT + tid] = acc[mi][ni][e];
-    __threadfence();
+        for (int q = 0; q < 4; ++q) {
+          const u32x4 v = {__float_as_uint(acc[mi][ni][4 * q]), __float_as_uint(acc[mi][ni][4 * q + 1]),
+                           __float_as_uint(acc[mi][ni][4 * q + 2]), __float_as_uint(acc[mi][ni][4 * q + 3])};
+          __builtin_amdgcn_raw_buffer_store_b128(v, rm, (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
+        }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0): stores acknowledged
     __syncthreads();
     int* lds_last = lds_misc;
     if (tid == 0) {
-      const uint32_t prev = atomicAdd(a.sk_counters + tile, 1u);
+      const uint32_t prev = __hip_atomic_fetch_add(a.sk_counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const int last = prev == (uint32_t)(a.split_k - 1);
-      if (last) a.sk_counters[tile] = 0u;     // ready for the next launch
+      if (last) __hip_atomic_store(a.sk_counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
       *lds_last = last;
     }
     __syncthreads();
     if (!*lds_last) return;
-    __threadfence();
+    (void)NV;
+#pragma unroll 4
     for (int s = 0; s < a.split_k; ++s) {
       if (s == split) continue;
-      const float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
+      float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
+      __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(other, 0, BLOCK_BYTES, 0x00027000);
 #pragma unroll
       for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            acc[mi][ni][e] += __builtin_nontemporal_load(other + ((mi * C::NI + ni) * 16 + e) * C::NT + tid);
+          for (int q = 0; q < 4; ++q) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ro, (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
+            acc[mi][ni][4 * q] += __uint_as_float(v[0]);
+            acc[mi][ni][4 * q + 1] += __uint_as_float(v[1]);
+            acc[mi][ni][4 * q + 2] += __uint_as_float(v[2]);
+            acc[mi][ni][4 * q + 3] += __uint_as_float(v[3]);
+          }
     }
     __syncthreads();
   }
