@@ -246,7 +246,18 @@ def main() -> int:
             extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50)
             del op
             torch.cuda.empty_cache()
-
+        # Secondary, labelled: the copy driver paced to an inbound link of 7 x 153 GB/s (what one
+        # rank of an 8-GPU xGMI mesh receives), so that communication is a paper-like fraction
+        # of the GEMM time; communication tile = chunk / ctpc (Sec. 4.3), swizzle on and off.
+        link = {}
+        for name, variants in (("c4_ag", ((1, 0), (2, 0), (4, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE))), ("c2_ag", ((1, 0), (2, 0)))):
+            for ctpc, flags in variants:
+                op = AG(W[name], 2, link_gbps=1071, copy_workgroups=64, comm_tiles_per_chunk=ctpc, flags=flags)
+                key = f"{name}_ctpc{ctpc}" + ("_noswizzle" if flags else "")
+                link[key] = overlap_block(op)
+                del op
+                torch.cuda.empty_cache()
+        extra["link_paced_1071GBps"] = link
     cpu_baseline = None
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host cores: full AllGather-GEMM of the timed shape

@@ -88,6 +88,10 @@ typedef struct flux_problem {
   int32_t comm_tiles_per_chunk; /* AG: signals per chunk (Sec. 4.3 "communication tile size");
                                    0 or 1 = one per chunk; must divide M/R                        */
   int32_t copy_workgroups;  /* AG copy kernel grid size; 0 = library picks                        */
+  int32_t link_gbps;        /* AG copy kernel: 0 = copy at memory speed; else emulate an inbound
+                               link of that many GB/s: communication tile i is not signalled
+                               before (i+1)*tile_bytes/link_gbps after the driver started       */
+  int32_t reserved;         /* must be 0                                                          */
   uint64_t spin_timeout_ticks;  /* AG: bound on one signal wait, in 100 MHz wall-clock ticks;
                                    0 = library default (10 s).  The paper spins without bound.   */
 } flux_problem_t;
@@ -138,7 +142,8 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
  *   op = FLUX_OP_AG:  FLUX_PHASE_COMM  copy all chunks into A_agg (no signals);
  *                     FLUX_PHASE_GEMM  C = A_agg.B.
  *   `phases` selects which of the two to enqueue (both: communication and GEMM in dependency
- *   order).  Arguments not used by `op` may be NULL.  The GEMM kernel is the same tile
+ *   order).  Arguments not used by `op` may be NULL; `workspace` as for the fused call when
+ *   flux_workspace_bytes is non-zero for the problem (FLUX_OP_RS: only when K is split).  The GEMM kernel is the same tile
  *   configuration the fused call would use, without prologue wait or reduce epilogue.
  */
 int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p,

@@ -56,6 +56,7 @@ struct CopyArgs {
   uint32_t* signals;                  // may be null (baseline copy)
   uint32_t* counters;
   uint32_t* started;                  // may be null
+  unsigned long long pace_ticks;      // 100 MHz ticks per communication tile, 0 = unpaced
 };
 
 // 16-byte store at device scope: written through this die's L2, so that a reader on another
@@ -80,6 +81,7 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
   const int n_tiles = c.n_order * c.tiles_per_chunk;
   if (c.started != nullptr && threadIdx.x == 0)
     __hip_atomic_fetch_add(c.started, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  const unsigned long long t_start = wall_clock64();
   for (int idx = 0; idx < n_tiles; ++idx) {
     const int chunk = c.order[idx / c.tiles_per_chunk];
     const int t = idx % c.tiles_per_chunk;
@@ -94,6 +96,9 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
       for (int u = 0; u < 8; ++u) store_through(dst + i + u * stride, v[u]);
     }
     for (; i < c.tile_vec; i += stride) store_through(dst + i, load_stream(src + i));
+    // link emulation: the tile "arrives" no earlier than a link of the given rate allows
+    if (c.pace_ticks != 0 && threadIdx.x == 0)
+      while (wall_clock64() - t_start < (unsigned long long)(idx + 1) * c.pace_ticks) __builtin_amdgcn_s_sleep(8);
     if (c.signals != nullptr) {
       const int flag = chunk * c.tiles_per_chunk + t;
       __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
@@ -193,6 +198,7 @@ static int validate_problem(int op, const flux_problem_t* p) {
   if (p->tile_config < 0 || p->tile_config > NUM_CFGS) return FLUX_ERR_INVALID_ARG;
   if (p->split_k < 0 || p->split_k > 64) return FLUX_ERR_INVALID_ARG;
   if (p->copy_workgroups < 0 || p->copy_workgroups > 4096) return FLUX_ERR_INVALID_ARG;
+  if (p->link_gbps < 0 || p->reserved != 0) return FLUX_ERR_INVALID_ARG;
   if (op == FLUX_OP_AG) {
     const int ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
     const int S = p->M / p->R;
@@ -230,9 +236,13 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   int split = p->split_k;
   if (split <= 0) {
     split = 1;
-    if (p->M <= 64 && tiles < 512) {            // decode: put enough workgroups on B's stream
+    if (tiles < 256) {                          // too few tiles to fill the chip: cut K as well
       split = (int)std::min<long long>((512 + tiles - 1) / tiles, 16);
       split = std::max(1, std::min(split, kt / 4));
+      // parked fp32 partials (written and re-read) should not outweigh the operands themselves
+      const long long operands = (long long)p->M * p->K + (long long)p->K * p->N;
+      const long long cap = operands / (4ll * p->M * p->N);
+      split = (int)std::max<long long>(1, std::min<long long>(split, cap));
     }
   }
   split = std::max(1, std::min(split, kt));
@@ -365,8 +375,10 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
   c.tile_vec = chunk_vec / c.tiles_per_chunk;
   c.signals = signals;
   c.counters = ws ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_COUNTER_OFF) : nullptr;
+  // bytes / (GB/s) = ns; 10 ns per tick
+  c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
   int wgs = p->copy_workgroups;
-  if (wgs <= 0) wgs = signals ? 256 : 1024;   // fused: one per CU, the transfer is over before most tiles need it
+  if (wgs <= 0) wgs = p->link_gbps > 0 ? 32 : (signals ? 256 : 1024);   // unpaced: one per CU, over before most tiles need it
   const unsigned long long max_useful = (c.tile_vec + 255) / 256;
   if ((unsigned long long)wgs > max_useful) wgs = (int)std::max<unsigned long long>(1, max_useful);
   c.started = (signals && ws) ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_STARTED_OFF) : nullptr;

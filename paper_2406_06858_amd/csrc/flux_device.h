@@ -366,9 +366,16 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
     __syncthreads();
     if (!*lds_last) return;
     (void)NV;
+    // the sum always runs over the parked partials in split order, whichever workgroup happens
+    // to be last, so results do not depend on arrival timing
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
 #pragma unroll 4
     for (int s = 0; s < a.split_k; ++s) {
-      if (s == split) continue;
       float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
       __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(other, 0, BLOCK_BYTES, 0x00027000);
 #pragma unroll

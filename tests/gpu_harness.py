@@ -67,11 +67,11 @@ def run_rs(w: fi.Workload, rank: int, A, B, peers, tile_config=0, split_k=0, fla
 
 def run_ag(w: fi.Workload, rank: int, chunks, B, arrival, tile_config=0, split_k=0, flags=0,
            comm_tiles_per_chunk=0, copy_workgroups=0, local_in_place=False, delay_copy_cycles=0,
-           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1):
+           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1, link_gbps=0):
     """Fused AllGather-GEMM through the C ABI.  A_agg starts NaN-poisoned so a tile that reads
     rows before their signal shows up in C.  Returns (C, A_agg, signals, status)."""
     p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, tile_config, split_k, flags,
-                   comm_tiles_per_chunk, copy_workgroups, timeout_ticks)
+                   comm_tiles_per_chunk, copy_workgroups, timeout_ticks, link_gbps)
     dB = B.to(DEV)
     A_agg = torch.full((w.M, w.K), float("nan"), dtype=torch.bfloat16, device=DEV)
     dchunks = [c.to(DEV) for c in chunks]

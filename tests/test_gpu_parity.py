@@ -262,6 +262,21 @@ def test_ag_delayed_copy_stream_still_correct():
     gh.assert_close(Cg, C64, w.out_dtype)
 
 
+def test_ag_link_paced_copy_driver():
+    """Emulated slow link (20 GB/s: each 256 KB chunk is released ~13 us after the previous one):
+    tiles really wait for their chunk; results and the signal reset are unaffected."""
+    w = AG_SMALL
+    rank = 4
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    for ctpc, flags in ((1, 0), (4, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE), (1, fb.FLUX_FLAG_COPY_FIRST)):
+        Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, comm_tiles_per_chunk=ctpc, flags=flags,
+                                           link_gbps=20, repeat=2)
+        assert status == (fb.FLUX_OK, 0)
+        gh.assert_close(Cg, C64, w.out_dtype, f"ctpc {ctpc} flags {flags}")
+        assert signals.cpu().tolist() == [1 if i // ctpc == rank else 0 for i in range(w.R * ctpc)]
+
+
 def test_ag_local_chunk_in_place():
     w = AG_SMALL
     rank = 6
@@ -305,10 +320,12 @@ def test_ag_signal_wait_times_out_cleanly():
 def test_results_are_deterministic():
     w = fi.scaled(W["c3_rs"], M=1024, N=1024, K=512)
     A, B, peers = fi.make_rs_inputs(w, 1)
-    a = gh.run_rs(w, 1, A, B, peers)
-    b = gh.run_rs(w, 1, A, B, peers)
-    for x, y in zip(a, b):
-        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+    for split in (0, 1, 4):          # the K-split sum runs in split order whoever arrives last
+        a = gh.run_rs(w, 1, A, B, peers, split_k=split)
+        for _ in range(3):
+            b = gh.run_rs(w, 1, A, B, peers, split_k=split)
+            for x, y in zip(a, b):
+                assert torch.equal(x.view(torch.int16), y.view(torch.int16))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -324,8 +341,11 @@ def test_unfused_baseline_matches_oracle():
     dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
     outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
     tmp = torch.empty((w.M, w.N), dtype=torch.bfloat16, device=gh.DEV)
+    ws = gh.workspace_for(fb.FLUX_OP_RS, p)
+    if ws is not None:
+        fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
     fb.flux_gemm_ref_unfused(fb.FLUX_OP_RS, fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM, p, A=dA, B=dB,
-                             peer_partials=dpeers, out_slices=outs, Cout=tmp)
+                             peer_partials=dpeers, out_slices=outs, Cout=tmp, workspace=ws)
     torch.cuda.synchronize()
     s64, _ = gh.oracle_rs(w, rank, A, B, peers)
     for r in range(w.R):
@@ -337,8 +357,11 @@ def test_unfused_baseline_matches_oracle():
     pa = fb.problem(wa.M, wa.N, wa.K, wa.R, 1, "bf16", wa.out_dtype)
     A_agg = torch.full((wa.M, wa.K), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
     Cout = torch.full((wa.M, wa.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    wsa = gh.workspace_for(fb.FLUX_OP_AG, pa)
+    fb.flux_init_buffers(fb.FLUX_OP_AG, pa, wsa)
     fb.flux_gemm_ref_unfused(fb.FLUX_OP_AG, fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM, pa,
-                             A_chunks=[c.to(gh.DEV) for c in chunks], A_agg=A_agg, B=B.to(gh.DEV), Cout=Cout)
+                             A_chunks=[c.to(gh.DEV) for c in chunks], A_agg=A_agg, B=B.to(gh.DEV), Cout=Cout,
+                             workspace=wsa)
     torch.cuda.synchronize()
     C64, _ = gh.oracle_ag(wa, chunks, B)
     gh.assert_close(Cout, C64, wa.out_dtype)

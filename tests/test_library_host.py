@@ -24,10 +24,10 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 
 def test_problem_struct_layout_matches_header():
-    # 12 int32/uint32 fields + one uint64, naturally aligned
+    # 14 int32/uint32 fields + one uint64, naturally aligned
     import ctypes
-    assert ctypes.sizeof(fb.flux_problem_t) == 56
-    assert fb.flux_problem_t.spin_timeout_ticks.offset == 48
+    assert ctypes.sizeof(fb.flux_problem_t) == 64
+    assert fb.flux_problem_t.spin_timeout_ticks.offset == 56
 
 
 def test_status_strings():
