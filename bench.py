@@ -34,8 +34,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--ramp-seconds", type=float, default=2.0, help="untimed load before the warm-up steps")
     ap.add_argument("--ag-flags", type=int, default=0,
-                    help="FLUX_FLAG_* bits for the AllGather-GEMM (8 = copy-first: needed under rocprofv3 --pmc, "
-                         "which runs kernels one at a time, so the copy driver must be dispatched before the GEMM)")
+                    help="FLUX_FLAG_* bits for the AllGather-GEMM of the timed step")
     ap.add_argument("--serial-kernels", type=int, default=0, metavar="N",
                     help="counter-collection mode: run N rounds of [chunk copy, AllGather-GEMM kernel on the gathered "
                          "matrix, fused GEMM-ReduceScatter] one kernel at a time and exit (rocprofv3 --pmc serialises "

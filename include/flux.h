@@ -53,7 +53,7 @@ extern "C" {
 typedef enum {
   FLUX_OK = 0,
   FLUX_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, misaligned base */
-  FLUX_ERR_SHAPE = 2,         /* M % R != 0, N or K not a multiple of 8, sizes <= 0 or too large */
+  FLUX_ERR_SHAPE = 2,         /* M % R != 0, N or K not a multiple of 8, sizes <= 0, or a matrix of 2^31 elements or more */
   FLUX_ERR_UNSUPPORTED = 3,   /* valid request the library has no kernel for */
   FLUX_ERR_WORKSPACE = 4,     /* workspace missing or smaller than flux_workspace_bytes */
   FLUX_ERR_HIP = 5,           /* a HIP runtime call failed (flux_last_hip_error has the code) */
@@ -69,9 +69,8 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
 #define FLUX_FLAG_COPY_MEMCPY  0x4u  /* AG copy driver = hipMemcpyAsync + stream write-value per
                                         communication tile instead of the copy kernel */
 
-#define FLUX_FLAG_COPY_FIRST    0x8u  /* AG: hold the GEMM grid back (stream wait-value) until every
-                                        copy workgroup is running; off by default, the wait costs
-                                        more than it saves when the copy kernel is launched first */
+#define FLUX_FLAG_NO_TAIL_SPLIT 0x10u /* with split_k = 0: do not cut the tiles of a partly filled last
+                                        round of the grid along K (see flux_split_plan) */
 
 /* flux_gemm_ref_unfused phases */
 #define FLUX_PHASE_GEMM 0x1
@@ -87,7 +86,8 @@ typedef struct flux_problem {
   uint32_t flags;           /* FLUX_FLAG_*                                                        */
   int32_t comm_tiles_per_chunk; /* AG: signals per chunk (Sec. 4.3 "communication tile size");
                                    0 or 1 = one per chunk; must divide M/R                        */
-  int32_t copy_workgroups;  /* AG copy kernel grid size; 0 = library picks                        */
+  int32_t copy_workgroups;  /* AG copy kernel grid size; 0 = library picks.  The fused call uses at
+                               most 256: a communication tile moves in one piece per workgroup.    */
   int32_t link_gbps;        /* AG copy kernel: 0 = copy at memory speed; else emulate an inbound
                                link of that many GB/s: communication tile i is not signalled
                                before (i+1)*tile_bytes/link_gbps after the driver started       */
@@ -112,6 +112,12 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
 
 /*
  * AllGather-GEMM, fused (Alg. 2 kernel + Alg. 3 host driver, pull form).
+ * The copy driver is a kernel on copy_stream that moves the remote chunks communication tile by
+ * communication tile in `arrival_order`.  While some of the driver's workgroups have not been
+ * given a compute unit yet, a GEMM workgroup that has to wait for a tile moves pieces of it that
+ * no one has started on, so the call completes even when the GEMM grid occupies every compute
+ * unit first (its waiting workgroups do not leave).  With FLUX_FLAG_COPY_MEMCPY the driver is
+ * hipMemcpyAsync plus a stream write per tile and the GEMM only waits.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.
@@ -125,7 +131,7 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  *   arrival_order   host int32[R-1]: the remote ranks in the order the copy driver transfers
  *                   them; NULL = ring order starting after `rank` (Sec. 4.3).
  *   workspace       device, >= flux_workspace_bytes(FLUX_OP_AG, p), initialised once with
- *                   flux_init_buffers (counters and status block).
+ *                   flux_init_buffers (status block, counters, piece claims).
  *   compute_stream  the GEMM kernel's stream; on return of the call it is ordered after the
  *                   GEMM, the copy driver and the signal reset.
  *   copy_stream     the copy driver's stream; must differ from compute_stream.
@@ -177,6 +183,15 @@ int flux_query_status(const void* workspace, int32_t* code, int32_t* detail);
  */
 int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_order,
                     int32_t block, int32_t* m_tile, int32_t* n_tile);
+
+/*
+ * How a call would cut K: the first *full_tiles tiles in TileCoord order are computed by one
+ * workgroup each, the remaining *split_tiles tiles by *split_k workgroups each (a uniform split has
+ * full_tiles = 0; no split has split_k = 1 and split_tiles = all tiles).  The grid has
+ * full_tiles + split_tiles * split_k workgroups.  Host function; any pointer may be NULL.
+ */
+int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_t* split_tiles,
+                    int32_t* split_k);
 
 /* Tile configuration a call would use: tile sizes, K split and die count used for the remap. */
 int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* tile_n,

@@ -20,7 +20,8 @@ FLUX_OK, FLUX_ERR_INVALID_ARG, FLUX_ERR_SHAPE, FLUX_ERR_UNSUPPORTED = 0, 1, 2, 3
 FLUX_ERR_WORKSPACE, FLUX_ERR_HIP, FLUX_ERR_TIMEOUT = 4, 5, 6
 FLUX_BF16, FLUX_F32 = 0, 1
 FLUX_OP_RS, FLUX_OP_AG = 0, 1
-FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY, FLUX_FLAG_COPY_FIRST = 0x1, 0x2, 0x4, 0x8
+FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY = 0x1, 0x2, 0x4
+FLUX_FLAG_NO_TAIL_SPLIT = 0x10
 FLUX_PHASE_GEMM, FLUX_PHASE_COMM = 0x1, 0x2
 FLUX_MAX_RANKS = 16
 
@@ -28,7 +29,7 @@ EXPORTS = [
     "flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_workspace_bytes",
     "flux_query_status", "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
     "flux_tile_config_info", "flux_default_order", "flux_status_string", "flux_last_hip_error",
-    "flux_version", "flux_profile_next_gemm", "flux_init_buffers",
+    "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan",
 ]
 
 
@@ -72,6 +73,7 @@ def lib():
         L.flux_query_status.argtypes = [vp, pi32, pi32]
         L.flux_tile_coord.argtypes = [C.c_int, pp, pi32, C.c_int32, pi32, pi32]
         L.flux_tile_shape.argtypes = [C.c_int, pp, pi32, pi32, pi32, pi32, pi32]
+        L.flux_split_plan.argtypes = [C.c_int, pp, pi32, pi32, pi32]
         L.flux_tile_config_info.argtypes = [C.c_int32, pi32, pi32, pi32]
         L.flux_default_order.argtypes = [C.c_int32, C.c_int32, pi32]
         L.flux_profile_next_gemm.argtypes = [vp, vp]
@@ -80,7 +82,7 @@ def lib():
         for name in ("flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_query_status",
                      "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
                      "flux_tile_config_info", "flux_default_order", "flux_last_hip_error", "flux_version",
-                     "flux_profile_next_gemm", "flux_init_buffers"):
+                     "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -182,6 +184,13 @@ def flux_tile_shape(op, p) -> TileShape:
     v = [C.c_int32(0) for _ in range(5)]
     _check(lib().flux_tile_shape(op, C.byref(p), *[C.byref(x) for x in v]), "flux_tile_shape")
     return TileShape(*[x.value for x in v])
+
+
+def flux_split_plan(op, p):
+    """(full_tiles, split_tiles, split_k) a call would use."""
+    v = [C.c_int32(0) for _ in range(3)]
+    _check(lib().flux_split_plan(op, C.byref(p), *[C.byref(x) for x in v]), "flux_split_plan")
+    return tuple(x.value for x in v)
 
 
 def flux_tile_config_count() -> int:

@@ -1,6 +1,7 @@
 // Host side of the library: argument validation, TileCoord tables, the AllGather copy driver
 // (paper Alg. 3, pull form), the non-overlapped baseline and the C ABI declared in flux.h.
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -12,10 +13,11 @@ namespace flux {
 
 // (not const: a const table of host function pointers would also be emitted for the device)
 CfgInfo g_cfgs[NUM_CFGS] = {
-    {256, 256, 64, launch_cfg1}, {256, 128, 64, launch_cfg2}, {128, 128, 64, launch_cfg3},
-    {64, 64, 64, launch_cfg4},   {64, 128, 64, launch_cfg5},  {32, 128, 64, launch_cfg6},
+    {256, 256, 64, 1, launch_cfg1}, {256, 128, 64, 1, launch_cfg2}, {128, 128, 64, 2, launch_cfg3},
+    {64, 64, 64, 2, launch_cfg4},   {64, 128, 64, 2, launch_cfg5},  {32, 128, 64, 2, launch_cfg6},
 };
 
+constexpr int N_CU = 256;                      // compute units of an MI355X
 constexpr int N_XCD = 8;                       // accelerator dies of an MI355X, one L2 each
 constexpr unsigned long long DEFAULT_TIMEOUT_TICKS = 1000000000ull;   // 10 s at 100 MHz
 
@@ -53,64 +55,48 @@ struct CopyArgs {
   int32_t tiles_per_chunk;            // communication tiles per chunk
   unsigned long long chunk_vec;       // 16-byte vectors per chunk
   unsigned long long tile_vec;        // 16-byte vectors per communication tile
-  uint32_t* signals;                  // may be null (baseline copy)
+  uint32_t* signals;                  // may be null (baseline copy: nothing to claim, count or signal)
   uint32_t* counters;
+  uint32_t* claims;                   // [signals][gridDim.x]
+  uint32_t call_id;
   uint32_t* started;                  // may be null
   unsigned long long pace_ticks;      // 100 MHz ticks per communication tile, 0 = unpaced
 };
 
-// 16-byte store at device scope: written through this die's L2, so that a reader on another
-// accelerator die needs no write-back of the whole L2 to see it.
-__device__ __forceinline__ void store_through(uint4* p, const u32x4& d) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
-}
-
-// streaming 16-byte load (the source is read once)
-__device__ __forceinline__ u32x4 load_stream(const uint4* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-}
-
 // Copy driver as one kernel: all workgroups move communication tile after communication tile
-// in transfer order (DataTransfer of Alg. 3); the workgroup that finishes a tile last sets its
-// signal (SetSignal).  The data is stored write-through and each wave waits for its stores to
-// be acknowledged before the workgroup counts itself in, so no cache write-back fence (which
-// would sweep the whole L2 of the die, per tile) is needed to publish a tile.
+// in transfer order (DataTransfer of Alg. 3), workgroup w taking piece w of each unless a waiting
+// GEMM workgroup got to that piece first; whoever finishes a tile's last piece sets its signal
+// (SetSignal).  The data is stored write-through and each wave waits for its stores to be
+// acknowledged before the workgroup counts itself in, so no cache write-back fence (which would
+// sweep the whole L2 of the die, per tile) is needed to publish a tile.
 __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
-  const unsigned long long stride = (unsigned long long)gridDim.x * blockDim.x;
-  const unsigned long long t0 = (unsigned long long)blockIdx.x * blockDim.x + threadIdx.x;
+  __shared__ int mine;
+  // The driver's waves share compute units with GEMM waves whose MFMAs are always ready to issue;
+  // at equal priority the few memory instructions here would wait behind them.
+  __builtin_amdgcn_s_setprio(3);
   const int n_tiles = c.n_order * c.tiles_per_chunk;
   if (c.started != nullptr && threadIdx.x == 0)
-    __hip_atomic_fetch_add(c.started, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_fetch_add(c.started, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   const unsigned long long t_start = wall_clock64();
   for (int idx = 0; idx < n_tiles; ++idx) {
     const int chunk = c.order[idx / c.tiles_per_chunk];
     const int t = idx % c.tiles_per_chunk;
-    const uint4* __restrict__ src = c.src[chunk] + (unsigned long long)t * c.tile_vec;
-    uint4* __restrict__ dst = c.dst + (unsigned long long)chunk * c.chunk_vec + (unsigned long long)t * c.tile_vec;
-    unsigned long long i = t0;
-    for (; i + 7 * stride < c.tile_vec; i += 8 * stride) {
-      u32x4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = load_stream(src + i + u * stride);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) store_through(dst + i + u * stride, v[u]);
-    }
-    for (; i < c.tile_vec; i += stride) store_through(dst + i, load_stream(src + i));
+    const int flag = chunk * c.tiles_per_chunk + t;
     // link emulation: the tile "arrives" no earlier than a link of the given rate allows
+    // (its data may move while the link is still busy with the tile before)
+    if (c.signals != nullptr) {
+      if (threadIdx.x == 0) mine = claim_piece(c.claims + (size_t)flag * gridDim.x + blockIdx.x, c.call_id) ? 1 : 0;
+      __syncthreads();
+      const bool take = mine != 0;
+      __syncthreads();
+      if (!take) continue;
+    }
+    const uint4* src = c.src[chunk] + (unsigned long long)t * c.tile_vec;
+    uint4* dst = c.dst + (unsigned long long)chunk * c.chunk_vec + (unsigned long long)t * c.tile_vec;
+    copy_piece(src, dst, c.tile_vec, (int)blockIdx.x, (int)gridDim.x, (int)threadIdx.x);
     if (c.pace_ticks != 0 && threadIdx.x == 0)
       while (wall_clock64() - t_start < (unsigned long long)(idx + 1) * c.pace_ticks) __builtin_amdgcn_s_sleep(8);
-    if (c.signals != nullptr) {
-      const int flag = chunk * c.tiles_per_chunk + t;
-      __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        const uint32_t prev = __hip_atomic_fetch_add(c.counters + flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev == gridDim.x - 1) {
-          __hip_atomic_store(c.counters + flag, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(c.signals + flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        }
-      }
-    }
+    if (c.signals != nullptr) finish_piece(c.counters + flag, c.signals + flag, (int)gridDim.x);
   }
 }
 
@@ -177,9 +163,14 @@ struct Plan {
   int bm, bn, bk;
   int tiles_m, tiles_n;
   int split_k, k_per_split;
+  int full_tiles, split_tiles;   // tiles computed whole / tiles cut along K (the last ones in TileCoord order)
   int edge;
   int n_xcd;
   int ctpc;         // communication tiles per chunk
+  // AllGather copy driver
+  int copy_wgs;             // workgroups of the copy kernel = pieces per communication tile
+  int copy_help;            // waiting GEMM workgroups may take pieces
+  size_t claim_bytes;       // claim words in the workspace, after the header
 };
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -191,8 +182,9 @@ static int validate_problem(int op, const flux_problem_t* p) {
   if (p->R < 1 || p->R > FLUX_MAX_RANKS) return FLUX_ERR_SHAPE;
   if (p->rank < 0 || p->rank >= p->R) return FLUX_ERR_INVALID_ARG;
   if (p->M % p->R != 0 || p->N % 8 != 0 || p->K % 8 != 0) return FLUX_ERR_SHAPE;
-  if ((long long)p->M * p->N >= (1ll << 31) * 8ll || (long long)p->M * p->K >= (1ll << 31) * 8ll ||
-      (long long)p->K * p->N >= (1ll << 31) * 8ll) return FLUX_ERR_SHAPE;
+  // every matrix stays below 2^31 elements: the kernels address operands through 32-bit buffer offsets
+  if ((long long)p->M * p->N >= (1ll << 31) || (long long)p->M * p->K >= (1ll << 31) ||
+      (long long)p->K * p->N >= (1ll << 31)) return FLUX_ERR_SHAPE;
   if (p->out_dtype != FLUX_BF16 && p->out_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
   if (op == FLUX_OP_RS && p->partial_dtype != FLUX_BF16 && p->partial_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
   if (p->tile_config < 0 || p->tile_config > NUM_CFGS) return FLUX_ERR_INVALID_ARG;
@@ -245,15 +237,39 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
       split = (int)std::max<long long>(1, std::min<long long>(split, cap));
     }
   }
+  long long split_tiles = tiles;
+  if (p->split_k <= 0 && split == 1 && !(p->flags & FLUX_FLAG_NO_TAIL_SPLIT)) {
+    // A grid of a few rounds whose last round fills at most half of the chip: cut only that
+    // round's tiles along K so that it too occupies every CU, for a fraction of a round's time.
+    const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
+    const long long rem = tiles % slots;
+    if (tiles > slots && tiles < 8 * slots && rem > 0 && 2 * rem <= slots) {
+      const int ts = (int)std::min<long long>(std::min<long long>(slots / rem, 8), kt / 4);
+      if (ts > 1) { split = ts; split_tiles = rem; }
+    }
+  }
   split = std::max(1, std::min(split, kt));
   const int kt_per = (kt + split - 1) / split;
   split = (kt + kt_per - 1) / kt_per;             // no empty splits
-  if (split > 1 && tiles > MAX_SPLITK_TILES) return FLUX_ERR_UNSUPPORTED;
+  if (split > 1 && split_tiles > MAX_SPLITK_TILES) return FLUX_ERR_UNSUPPORTED;
   pl->split_k = split;
   pl->k_per_split = kt_per * pl->bk;
+  pl->split_tiles = split > 1 ? (int)split_tiles : (int)tiles;
+  pl->full_tiles = (int)tiles - pl->split_tiles;
   pl->edge = (p->M % pl->bm != 0) || (p->N % pl->bn != 0) || (p->K % pl->bk != 0);
   pl->n_xcd = (p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_NO_XCD_REMAP)) ? 1 : N_XCD;
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
+  pl->copy_wgs = 0; pl->copy_help = 0; pl->claim_bytes = 0;
+  if (op == FLUX_OP_AG) {
+    // unpaced: one workgroup per CU, over before most tiles need their rows; paced: a few are enough
+    int wgs = p->copy_workgroups > 0 ? p->copy_workgroups : (p->link_gbps > 0 ? 32 : 256);
+    wgs = std::min(wgs, MAX_COPY_PIECES);
+    const unsigned long long tile_vec = (unsigned long long)(p->M / p->R) * p->K / 8 / pl->ctpc;
+    wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (tile_vec + 255) / 256));
+    pl->copy_wgs = wgs;
+    pl->copy_help = !(p->flags & FLUX_FLAG_COPY_MEMCPY);
+    pl->claim_bytes = (((size_t)p->R * pl->ctpc * wgs * 4) + 255) / 256 * 256;
+  }
   return FLUX_OK;
 }
 
@@ -314,9 +330,9 @@ static void build_tile_map(int op, const flux_problem_t* p, const Plan& pl, cons
 }
 
 static size_t workspace_need(const Plan& pl) {
-  size_t need = WS_HEADER_BYTES;
+  size_t need = WS_HEADER_BYTES + pl.claim_bytes;
   if (pl.split_k > 1)
-    need += (size_t)pl.split_k * pl.tiles_m * pl.tiles_n * pl.bm * pl.bn * sizeof(float);
+    need += (size_t)pl.split_k * pl.split_tiles * pl.bm * pl.bn * sizeof(float);
   return need;
 }
 
@@ -336,6 +352,8 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
   a->out_f32 = p->out_dtype == FLUX_F32;
   a->split_k = pl.split_k;
   a->k_per_split = pl.k_per_split;
+  a->full_tiles = pl.full_tiles;
+  a->split_tiles = pl.split_tiles;
   a->rows_per_signal = std::max(1, (p->M / p->R) / pl.ctpc);
   a->timeout_ticks = p->spin_timeout_ticks ? p->spin_timeout_ticks : DEFAULT_TIMEOUT_TICKS;
   if (ws != nullptr) {
@@ -344,12 +362,14 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
     a->done_counter = reinterpret_cast<uint32_t*>(w + WS_DONE_OFF);
     a->started_counter = reinterpret_cast<uint32_t*>(w + WS_STARTED_OFF);
     a->sk_counters = reinterpret_cast<uint32_t*>(w + WS_TILECNT_OFF);
-    a->sk_partials = reinterpret_cast<float*>(w + WS_HEADER_BYTES);
+    a->copy_claims = reinterpret_cast<uint32_t*>(w + WS_HEADER_BYTES);
+    a->copy_counters = reinterpret_cast<uint32_t*>(w + WS_COUNTER_OFF);
+    a->sk_partials = reinterpret_cast<float*>(w + WS_HEADER_BYTES + pl.claim_bytes);
   }
 }
 
 static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hipStream_t s) {
-  const int grid = pl.tiles_m * pl.tiles_n * pl.split_k;
+  const int grid = pl.full_tiles + pl.split_tiles * pl.split_k;
   hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (e0) FLUX_HIP(hipEventRecord(e0, s));
@@ -358,10 +378,11 @@ static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hip
   return FLUX_OK;
 }
 
+// `fused`: the copy driver of a fused call (claims, counters, signals, pacing); otherwise a plain
+// copy of the listed chunks.
 static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* const* chunks, void* A_agg,
-                       const int* order, int n_order, uint32_t* signals, void* ws, hipStream_t s,
-                       int* wgs_out = nullptr) {
-  if (wgs_out) *wgs_out = 0;
+                       const int* order, int n_order, bool fused, uint32_t* signals, void* ws, uint32_t call_id,
+                       hipStream_t s) {
   if (n_order == 0) return FLUX_OK;
   CopyArgs c;
   std::memset(&c, 0, sizeof(c));
@@ -370,22 +391,34 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
   c.dst = static_cast<uint4*>(A_agg);
   for (int i = 0; i < n_order; ++i) c.order[i] = order[i];
   c.n_order = n_order;
-  c.tiles_per_chunk = signals ? pl.ctpc : 1;
+  c.tiles_per_chunk = fused ? pl.ctpc : 1;
   c.chunk_vec = chunk_vec;
   c.tile_vec = chunk_vec / c.tiles_per_chunk;
-  c.signals = signals;
-  c.counters = ws ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_COUNTER_OFF) : nullptr;
-  // bytes / (GB/s) = ns; 10 ns per tick
-  c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
-  int wgs = p->copy_workgroups;
-  if (wgs <= 0) wgs = p->link_gbps > 0 ? 32 : (signals ? 256 : 1024);   // unpaced: one per CU, over before most tiles need it
-  const unsigned long long max_useful = (c.tile_vec + 255) / 256;
-  if ((unsigned long long)wgs > max_useful) wgs = (int)std::max<unsigned long long>(1, max_useful);
-  c.started = (signals && ws) ? reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(ws) + WS_STARTED_OFF) : nullptr;
-  if (wgs_out) *wgs_out = wgs;
+  int wgs;
+  if (fused) {
+    unsigned char* w = static_cast<unsigned char*>(ws);
+    c.signals = signals;
+    c.counters = reinterpret_cast<uint32_t*>(w + WS_COUNTER_OFF);
+    c.claims = reinterpret_cast<uint32_t*>(w + WS_HEADER_BYTES);
+    c.call_id = call_id;
+    c.started = reinterpret_cast<uint32_t*>(w + WS_STARTED_OFF);
+    // bytes / (GB/s) = ns; 10 ns per tick
+    c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
+    wgs = pl.copy_wgs;
+  } else {
+    wgs = p->copy_workgroups > 0 ? p->copy_workgroups : 1024;
+    wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (c.tile_vec + 255) / 256));
+  }
   hipLaunchKernelGGL(ag_copy_kernel, dim3(wgs), dim3(256), 0, s, c);
   FLUX_HIP(hipGetLastError());
   return FLUX_OK;
+}
+
+static std::atomic<uint32_t> g_call_id{1};
+static uint32_t next_call_id() {
+  uint32_t id;
+  do { id = g_call_id.fetch_add(1, std::memory_order_relaxed); } while (id == 0);   // 0 = "never claimed"
+  return id;
 }
 
 static std::mutex g_event_mu;
@@ -461,10 +494,10 @@ int flux_init_buffers(int op, const flux_problem_t* p, void* workspace, size_t w
   Plan pl;
   int st = make_plan(op, p, &pl);
   if (st != FLUX_OK) return st;
-  if (workspace != nullptr && (workspace_bytes < WS_HEADER_BYTES || !aligned16(workspace))) return FLUX_ERR_WORKSPACE;
+  if (workspace != nullptr && (workspace_bytes < WS_HEADER_BYTES + pl.claim_bytes || !aligned16(workspace))) return FLUX_ERR_WORKSPACE;
   if (workspace == nullptr && signals == nullptr) return FLUX_OK;
   const int n_sig = (op == FLUX_OP_AG && signals) ? p->R * pl.ctpc : 0;
-  const int words = workspace ? (int)(WS_HEADER_BYTES / 4) : 0;
+  const int words = workspace ? (int)((WS_HEADER_BYTES + pl.claim_bytes) / 4) : 0;   // header and piece claims
   if (std::max(words, n_sig) == 0) return FLUX_OK;
   hipLaunchKernelGGL(preset_kernel, dim3((std::max(words, n_sig) + 255) / 256), dim3(256), 0,
                      static_cast<hipStream_t>(stream), n_sig ? signals : (uint32_t*)nullptr, n_sig,
@@ -483,6 +516,16 @@ int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* t
   if (tile_k) *tile_k = pl.bk;
   if (split_k) *split_k = pl.split_k;
   if (n_xcd) *n_xcd = pl.n_xcd;
+  return FLUX_OK;
+}
+
+int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_t* split_tiles, int32_t* split_k) {
+  Plan pl;
+  int st = make_plan(op, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (full_tiles) *full_tiles = pl.full_tiles;
+  if (split_tiles) *split_tiles = pl.split_tiles;
+  if (split_k) *split_k = pl.split_k;
   return FLUX_OK;
 }
 
@@ -531,7 +574,11 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   fill_common(&a, p, pl, pl.split_k > 1 ? workspace : nullptr);
   a.A = static_cast<const __bf16*>(A);
   a.B = static_cast<const __bf16*>(B);
-  for (int r = 0; r < p->R; ++r) { a.peers[r] = peer_partials[r]; a.outs[r] = out_slices[r]; }
+  // the kernel wants the R-1 peers packed, ascending rank
+  for (int r = 0, j = 0; r < p->R; ++r) {
+    a.outs[r] = out_slices[r];
+    if (r != p->rank) a.peers[j++] = peer_partials[r];
+  }
   build_tile_map(FLUX_OP_RS, p, pl, nullptr, &a.tm);
   return launch_gemm(pl, EPI_RS, 0, a, s);
 }
@@ -568,13 +615,20 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   a.n_signals = p->R * pl.ctpc;
   a.sig_local_lo = p->rank * pl.ctpc;
   a.sig_local_hi = (p->rank + 1) * pl.ctpc;
+  const uint32_t call_id = next_call_id();
+  if (pl.copy_help && p->R > 1) {
+    a.copy_pieces = pl.copy_wgs;
+    a.copy_call_id = call_id;
+    a.copy_tile_vec = (unsigned long long)chunk_elems / 8 / pl.ctpc;
+    for (int r = 0; r < p->R; ++r) a.outs[r] = const_cast<void*>(A_chunks[r]);   // chunk sources by rank
+  }
   build_tile_map(FLUX_OP_AG, p, pl, order, &a.tm);
 
   // local chunk (its signal is preset, so it must be in place before the kernel starts)
   const __bf16* local_dst = static_cast<const __bf16*>(A_agg) + (size_t)p->rank * chunk_elems;
   if (A_chunks[p->rank] != static_cast<const void*>(local_dst)) {
     int self = p->rank;
-    st = launch_copy(p, pl, A_chunks, A_agg, &self, 1, nullptr, nullptr, cs);
+    st = launch_copy(p, pl, A_chunks, A_agg, &self, 1, false, nullptr, nullptr, 0, cs);
     if (st != FLUX_OK) return st;
   }
   // fork: the copy driver may start once everything queued so far on compute_stream is done
@@ -592,14 +646,8 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
       }
     }
   } else {
-    int copy_wgs = 0;
-    st = launch_copy(p, pl, A_chunks, A_agg, order, p->R - 1, signals, workspace, xs, &copy_wgs);
+    st = launch_copy(p, pl, A_chunks, A_agg, order, p->R - 1, true, signals, workspace, call_id, xs);
     if (st != FLUX_OK) return st;
-    // Optionally the GEMM grid is not dispatched before every copy workgroup is running: waiting
-    // tiles hold their CU, so a copy driver that came second finds no room until tiles finish.
-    if (copy_wgs > 0 && (p->flags & FLUX_FLAG_COPY_FIRST))
-      FLUX_HIP(hipStreamWaitValue32(cs, static_cast<unsigned char*>(workspace) + WS_STARTED_OFF, (uint32_t)copy_wgs,
-                                    hipStreamWaitValueGte, 0xffffffffu));
   }
   st = launch_gemm(pl, EPI_PLAIN, 1, a, cs);
   if (st != FLUX_OK) return st;
@@ -678,7 +726,7 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
       const void* dst = static_cast<const __bf16*>(A_agg) + (size_t)r * chunk_elems;
       if (A_chunks[r] != dst) order[n++] = r;
     }
-    st = launch_copy(p, pl, A_chunks, A_agg, order, n, nullptr, nullptr, s);
+    st = launch_copy(p, pl, A_chunks, A_agg, order, n, false, nullptr, nullptr, 0, s);
     if (st != FLUX_OK) return st;
   }
   if (do_gemm) {

@@ -36,7 +36,10 @@ constexpr size_t WS_COUNTER_OFF = 256;     // uint32 per communication tile (cop
 constexpr int MAX_COMM_TILES = 1024;
 constexpr size_t WS_TILECNT_OFF = WS_COUNTER_OFF + 4 * MAX_COMM_TILES;   // split-K arrival counters
 constexpr int MAX_SPLITK_TILES = 4096;
-constexpr size_t WS_HEADER_BYTES = WS_TILECNT_OFF + 4 * MAX_SPLITK_TILES; // split-K partials follow
+constexpr size_t WS_HEADER_BYTES = WS_TILECNT_OFF + 4 * MAX_SPLITK_TILES;
+// After the header: AllGather piece claims (uint32 per communication tile and piece), then the
+// split-K partials.
+constexpr int MAX_COPY_PIECES = 256;       // pieces per communication tile = copy-driver workgroups
 
 // ---- TileCoord (paper Sec. 4.1) -----------------------------------------------------------
 // The host builds `m_order`: the order in which m-tiles are scheduled (slice by slice after
@@ -68,7 +71,7 @@ struct GemmArgs {
   // plain epilogue
   void* C;                   // [M,N] of out dtype
   // reduce-scatter epilogue
-  const void* peers[FLUX_MAX_RANKS];
+  const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
   void* outs[FLUX_MAX_RANKS];
   int32_t R, rank, S;        // S = M / R
   int32_t partial_f32, out_f32;
@@ -78,14 +81,38 @@ struct GemmArgs {
   int32_t n_signals, sig_local_lo, sig_local_hi;   // local communication tiles: [lo, hi)
   uint32_t* done_counter;
   uint32_t* started_counter;
+  // cooperative copy: a workgroup that has to wait moves unclaimed pieces of the tile it waits for
+  // (outs[] then holds the chunk sources, A is the gathered matrix); copy_pieces = 0: no copy kernel
+  uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
+  uint32_t* copy_counters;   // [n_signals] pieces finished
+  uint32_t copy_call_id;
+  int32_t copy_pieces;
+  unsigned long long copy_tile_vec;   // 16-byte vectors per communication tile
   uint32_t* status;
   unsigned long long timeout_ticks;
   // split-K
+  // K split: the first `full_tiles` tiles (in TileCoord order) are computed by one workgroup
+  // each; every one of the remaining `split_tiles` tiles by `split_k` workgroups that each take
+  // `k_per_split` of K.  A uniform split has full_tiles = 0; splitting only the tiles of the last,
+  // partly filled round of the grid keeps all CUs busy to the end.
+  int32_t full_tiles, split_tiles;
   int32_t split_k, k_per_split;   // k_per_split is a multiple of BK
-  float* sk_partials;             // [split_k][tiles][BM*BN] fp32
+  float* sk_partials;             // [split_k][split_tiles][BM*BN] fp32
   uint32_t* sk_counters;          // [tiles]
   TileMap tm;
 };
+
+// workgroup id -> (tile in TileCoord order, K split index, is this tile split)
+__device__ __forceinline__ void map_block(const GemmArgs& a, int b, int& tile, int& split, bool& is_split) {
+  if (b < a.full_tiles) {
+    tile = b; split = 0; is_split = false;
+  } else {
+    const int r = b - a.full_tiles;
+    tile = a.full_tiles + r % a.split_tiles;
+    split = r / a.split_tiles;
+    is_split = a.split_k > 1;
+  }
+}
 
 // ---- LDS swizzles ---------------------------------------------------------------------------
 // A tile: rows of BK bf16 = BK/8 slots of 16 B; slot s of row r is stored at slot s ^ fA(r).
@@ -235,38 +262,10 @@ __device__ __forceinline__ void mma_stage(const unsigned char* stage, int wm, in
   }
 }
 
-// 8 consecutive output columns of one row: add the peer partials (ascending rank), convert
-// once, store into the owner's slice (GetOutput + Reduce of Alg. 1) or into C.
+// Store 8 consecutive output columns of one row into the owner's slice (GetOutput of Alg. 1) or
+// into C, converting once.
 template <int EPI>
-__device__ __forceinline__ void epilogue_row8(const GemmArgs& a, void* const* lds_outs, int gm, int gn, float (&v)[8]) {
-  if (EPI == EPI_RS) {
-    const size_t off = (size_t)gm * a.N + gn;
-    // constant indices only: a run-time index into the by-value argument block would force a
-    // private-memory copy of it
-    if (a.partial_f32) {
-#pragma unroll
-      for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-        if (j < a.R && j != a.rank) {
-          const float* p = static_cast<const float*>(a.peers[j]) + off;
-          const uint4 x = ld_stream16(p), y = ld_stream16(p + 4);
-          v[0] += __uint_as_float(x.x); v[1] += __uint_as_float(x.y); v[2] += __uint_as_float(x.z); v[3] += __uint_as_float(x.w);
-          v[4] += __uint_as_float(y.x); v[5] += __uint_as_float(y.y); v[6] += __uint_as_float(y.z); v[7] += __uint_as_float(y.w);
-        }
-    } else {
-      uint4 w[FLUX_MAX_RANKS];
-#pragma unroll
-      for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-        if (j < a.R && j != a.rank) w[j] = ld_stream16(static_cast<const __bf16*>(a.peers[j]) + off);
-#pragma unroll
-      for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-        if (j < a.R && j != a.rank) {
-          v[0] += bf16_lo(w[j].x); v[1] += bf16_hi(w[j].x);
-          v[2] += bf16_lo(w[j].y); v[3] += bf16_hi(w[j].y);
-          v[4] += bf16_lo(w[j].z); v[5] += bf16_hi(w[j].z);
-          v[6] += bf16_lo(w[j].w); v[7] += bf16_hi(w[j].w);
-        }
-    }
-  }
+__device__ __forceinline__ void store_row8(const GemmArgs& a, void* const* lds_outs, int gm, int gn, const float (&v)[8]) {
   void* base;
   size_t o;
   if (EPI == EPI_RS) {
@@ -289,40 +288,240 @@ __device__ __forceinline__ void epilogue_row8(const GemmArgs& a, void* const* ld
   }
 }
 
-// WaitSignal (Alg. 2): one lane polls every signal covering rows [m0, m1) with coherent loads,
-// then an acquire fence makes the copied rows visible; the workgroup barrier hands that to the
-// other waves.  Bounded: past `timeout_ticks` the tile is given up and the status block says so.
-// A workgroup never looks at the signals again after this, so the last workgroup of the grid
-// to get here puts the signal array back into its preset state for the next call (the reset
-// "after the GEMM" of Sec. 4.3, without a separate launch).
-__device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, int* lds_ok) {
-  if (threadIdx.x == 0) {
-    const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
-    int ok = 1;
-    const unsigned long long t0 = wall_clock64();
-    for (int f = f0; f <= f1 && ok; ++f) {
-      while (__hip_atomic_load(a.signals + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u) {
-        __builtin_amdgcn_s_sleep(16);
-        if (wall_clock64() - t0 > a.timeout_ticks) {
-          if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)f;
-          ok = 0;
-          break;
-        }
+// The peer partials of one tile as buffer resources based at the tile's origin (Reduce of Alg. 1
+// reads them).  `a.peers` holds the R-1 peers in ascending rank order; a resource past that has no
+// records, so its loads return zeros and every lane runs the same straight-line code: seven loads
+// per 8-column piece, no branch and no pointer fetch between them.
+struct PeerBufs {
+  __amdgpu_buffer_rsrc_t r[FLUX_MAX_RANKS - 1];
+};
+
+__device__ __forceinline__ void make_peer_bufs(const GemmArgs& a, int m0, int n0, PeerBufs& pb) {
+  const size_t tile_off = ((size_t)m0 * a.N + n0) * (a.partial_f32 ? 4 : 2);
+#pragma unroll
+  for (int j = 0; j < FLUX_MAX_RANKS - 1; ++j) {
+    // (the address is the same in every lane; saying so keeps the resource in scalar registers)
+    const uint64_t addr = reinterpret_cast<uint64_t>(a.peers[j]) + tile_off;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr), hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
+    unsigned char* base = reinterpret_cast<unsigned char*>(((uint64_t)hi << 32) | lo);
+    pb.r[j] = __builtin_amdgcn_make_buffer_rsrc(base, 0, j < a.R - 1 ? 0x7fffffff : 0, 0x00027000);
+  }
+}
+
+// One 32-row block of a wave's tile, already transposed into `ep`: every lane takes 8 consecutive
+// columns of a row per pass.  With the reduce-scatter epilogue the peer loads of BATCH passes are
+// issued together before any of them is used (PF32: fp32 partials, two 16-byte loads per peer);
+// the peers are added in ascending rank order.
+template <class C, int EPI, bool EDGE, bool PF32, int BATCH>
+__device__ __forceinline__ void epilogue_block(const GemmArgs& a, void* const* lds_outs, const float* ep, const PeerBufs& pb,
+                                               int row_base, int col_base, int m0, int n0, int lane) {
+  constexpr int CH = C::WTN / 8;          // 8-column pieces per row of the wave tile
+  constexpr int RPP = 64 / CH;            // rows per pass
+  constexpr int NIT = 32 / RPP;
+  constexpr int B = BATCH < NIT ? BATCH : NIT;
+  constexpr int LPP = PF32 ? 2 : 1;
+  constexpr int NP = FLUX_MAX_RANKS - 1;
+  constexpr int NT_HINT = 2;              // cache policy: streamed once, do not keep
+  static_assert(NIT % B == 0, "batch must divide the passes");
+  const int cc = lane % CH, rl = lane / CH;
+#pragma unroll
+  for (int it0 = 0; it0 < NIT; it0 += B) {
+    u32x4 w[B][NP][LPP];
+    bool ok[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int row = row_base + (it0 + b) * RPP + rl, col = col_base + cc * 8;
+      ok[b] = !EDGE || (m0 + row < a.M && n0 + col < a.N);
+      if (EPI == EPI_RS) {
+        // a lane outside the matrix gets an offset past the records: zeros, no memory access
+        const int voff = ok[b] ? (row * a.N + col) * (PF32 ? 4 : 2) : (int)0x80000000;
+#pragma unroll
+        for (int j = 0; j < NP; ++j)
+#pragma unroll
+          for (int l = 0; l < LPP; ++l) w[b][j][l] = __builtin_amdgcn_raw_buffer_load_b128(pb.r[j], voff + 16 * l, 0, NT_HINT);
       }
     }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      const int r = (it0 + b) * RPP + rl;
+      const float4 x = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8);
+      const float4 y = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8 + 4);
+      float v[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+      if (EPI == EPI_RS) {
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+          if (PF32) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] += __uint_as_float(w[b][j][0][e]); v[4 + e] += __uint_as_float(w[b][j][LPP - 1][e]); }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[2 * e] += bf16_lo(w[b][j][0][e]); v[2 * e + 1] += bf16_hi(w[b][j][0][e]); }
+          }
+        }
+      }
+      if (ok[b]) store_row8<EPI>(a, lds_outs, m0 + row_base + r, n0 + col_base + cc * 8, v);
+    }
+  }
+}
+
+// The whole epilogue of one wave: its accumulators pass through LDS 32 rows at a time.
+template <class C, int EPI, bool EDGE, bool PF32, int BATCH>
+__device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds_outs, float* ep, f32x16 (&acc)[C::MI][C::NI],
+                                             int m0, int n0, int lane, int wm, int wn) {
+  PeerBufs pb;
+  if (EPI == EPI_RS) make_peer_bufs(a, m0, n0, pb);
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
+      }
+    __builtin_amdgcn_wave_barrier();
+    epilogue_block<C, EPI, EDGE, PF32, BATCH>(a, lds_outs, ep, pb, wm * C::WTM + mi * 32, wn * C::WTN, m0, n0, lane);
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// ---- AllGather copy pieces --------------------------------------------------------------------
+// A communication tile is moved in `pieces` pieces; piece w is what workgroup w of a grid of
+// `pieces` workgroups of 256 threads touches in a grid-stride loop over 16-byte vectors.  The copy
+// driver's workgroup w normally moves piece w of every tile; a GEMM workgroup that would otherwise
+// only wait may take pieces nobody has claimed yet.  Either way the piece is claimed first (a
+// compare-and-swap of the call's id into the piece's claim word), moved, and counted in; whoever
+// counts in last sets the tile's signal (SetSignal of Alg. 3).
+
+// 16-byte store at device scope: written through this die's L2, so that a reader on another
+// accelerator die needs no write-back of the whole L2 to see it.
+__device__ __forceinline__ void store_through(uint4* p, const u32x4& d) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+}
+
+__device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
+                                           int piece, int pieces, int tid) {
+  const unsigned long long stride = (unsigned long long)pieces * 256;
+  unsigned long long i = (unsigned long long)piece * 256 + tid;
+  for (; i + 7 * stride < tile_vec; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i + u * stride));
+#pragma unroll
+    for (int u = 0; u < 8; ++u) store_through(dst + i + u * stride, v[u]);
+  }
+  for (; i < tile_vec; i += stride) store_through(dst + i, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i)));
+}
+
+// true if this workgroup now owns the piece (call from one thread)
+__device__ __forceinline__ bool claim_piece(uint32_t* claim, uint32_t call_id) {
+  uint32_t old = __hip_atomic_load(claim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (old == call_id) return false;
+  return __hip_atomic_compare_exchange_strong(claim, &old, call_id, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// After the piece's stores: wait until they are acknowledged, count the piece in, set the signal
+// if it was the tile's last.  All threads of the workgroup call this.
+__device__ __forceinline__ void finish_piece(uint32_t* counter, uint32_t* signal, int pieces) {
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev == (uint32_t)pieces - 1) {
+      __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+      __hip_atomic_store(signal, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
+}
+
+// The copy driver's workgroups count themselves in when they start: word 0 of `started` only ever
+// grows.  Word 1 is what word 0 read before the current call's driver was launched; the last GEMM
+// workgroup past its wait advances it by the driver's size for the next call (by then every driver
+// workgroup of this call has been or will be counted, and the next call starts after the driver
+// has finished).  Nothing is ever reset, so a workgroup that starts late cannot spoil a count.
+__device__ __forceinline__ bool driver_fully_started(const uint32_t* started, int workgroups) {
+  const uint32_t total = __hip_atomic_load(started, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint32_t base = __hip_atomic_load(started + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return total - base >= (uint32_t)workgroups;
+}
+
+// WaitSignal (Alg. 2): one lane polls every signal covering rows [m0, m1) with coherent loads,
+// then an acquire fence makes the copied rows visible; the workgroup barrier hands that to the
+// other waves.  As long as every workgroup of the copy driver is running, that is all.  If some
+// of them have not been given a compute unit yet (the GEMM grid may have taken them all, and its
+// waiting workgroups do not leave), waiting would not end: the workgroup then claims and moves
+// pieces of the communication tile it waits for itself.  Bounded: past `timeout_ticks` the tile is
+// given up and the status block says so.  A workgroup never looks at the signals again after
+// this, so the last workgroup of the grid to get here puts the signal array back into its preset
+// state for the next call (the reset "after the GEMM" of Sec. 4.3, without a separate launch).
+// `lds` is 4 ints shared by the workgroup; `lds_srcs` holds the chunk sources by rank.
+__device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, int* lds, void* const* lds_srcs) {
+  const int tid = threadIdx.x;
+  const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
+  const unsigned long long t0 = wall_clock64();
+  enum : int { ARRIVED = 1, GIVE_UP = 2, HELP = 3 };
+  bool ok = true;
+  for (int f = f0; f <= f1 && ok; ++f) {
+    const bool can_help = a.copy_pieces > 0 && !(f >= a.sig_local_lo && f < a.sig_local_hi);
+    for (;;) {
+      if (tid == 0) {
+        int st;
+        for (int polls = 0;; ++polls) {
+          if (__hip_atomic_load(a.signals + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) { st = ARRIVED; break; }
+          if (wall_clock64() - t0 > a.timeout_ticks) {
+            if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)f;
+            st = GIVE_UP;
+            break;
+          }
+          if (can_help && polls >= 8 && !driver_fully_started(a.started_counter, a.copy_pieces)) { st = HELP; break; }
+          __builtin_amdgcn_s_sleep(16);
+        }
+        lds[0] = st;
+        lds[1] = 0x7fffffff;
+      }
+      __syncthreads();
+      const int st = lds[0];
+      __syncthreads();                    // everyone has read it before thread 0 can write again
+      if (st == ARRIVED) break;
+      if (st == GIVE_UP) { ok = false; break; }
+      // lowest piece of this tile that nobody has claimed
+      uint32_t* claims = a.copy_claims + (size_t)f * a.copy_pieces;
+      if (tid < a.copy_pieces &&
+          __hip_atomic_load(claims + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.copy_call_id)
+        atomicMin(&lds[1], tid);
+      __syncthreads();
+      const int piece = lds[1];
+      if (piece != 0x7fffffff) {
+        if (tid == 0) lds[2] = claim_piece(claims + piece, a.copy_call_id) ? 1 : 0;
+        __syncthreads();
+        if (lds[2]) {
+          const int ctpc = a.n_signals / a.R;
+          const uint4* src = static_cast<const uint4*>(lds_srcs[f / ctpc]) + (unsigned long long)(f % ctpc) * a.copy_tile_vec;
+          uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
+          copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
+          finish_piece(a.copy_counters + f, a.signals + f, a.copy_pieces);
+        }
+      } else {
+        // every piece is in the hands of a workgroup that is running: only waiting is left
+        __builtin_amdgcn_s_sleep(32);
+      }
+      __syncthreads();                    // lds[1], lds[2] are rewritten in the next round
+    }
+  }
+  if (tid == 0) {
     __atomic_thread_fence(__ATOMIC_ACQUIRE);   // system scope: covers copy kernels and DMA writers
-    *lds_ok = ok;
     const uint32_t prev = atomicAdd(a.done_counter, 1u);
     if (prev == gridDim.x - 1) {
       for (int i = 0; i < a.n_signals; ++i)
         __hip_atomic_store(a.signals + i, (i >= a.sig_local_lo && i < a.sig_local_hi) ? 1u : 0u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
-      __hip_atomic_store(a.started_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (a.copy_pieces > 0)
+        __hip_atomic_fetch_add(a.started_counter + 1, (uint32_t)a.copy_pieces, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.done_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   __syncthreads();
-  return *lds_ok != 0;
+  return ok;
 }
 
 // Everything after the main loop: the split-K hand-over (all but the last-arriving workgroup of
@@ -331,17 +530,18 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
 // with 8 consecutive columns of one row.  `smem` must hold C::EP_BYTES and is free to reuse.
 template <class C, int EPI, bool EDGE>
 __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem, int* lds_misc, void* const* lds_outs,
-                                          f32x16 (&acc)[C::MI][C::NI], int tile, int split, int ntiles,
+                                          f32x16 (&acc)[C::MI][C::NI], int tile, int split, bool is_split,
                                           int m0, int n0, int tid, int lane, int wave, int wm, int wn) {
   // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
-  if (a.split_k > 1) {
+  if (is_split) {
+    const int st = tile - a.full_tiles;            // index among the split tiles
     // Partials are stored and re-read with device-scope (sc1) accesses, which go through the
     // die's L2 to memory: the hand-over between workgroups on different dies then needs neither
     // an L2 write-back nor an L2 invalidate, only "my stores are acknowledged" before counting in.
     constexpr int SC1 = 16;                               // cache-policy bit: device scope
     constexpr int BLOCK_BYTES = C::BM * C::BN * 4;
     constexpr int NV = C::MI * C::NI * 4;                 // 16-byte vectors per thread
-    float* mine = a.sk_partials + ((size_t)split * ntiles + tile) * (C::BM * C::BN);
+    float* mine = a.sk_partials + ((size_t)split * a.split_tiles + st) * (C::BM * C::BN);
     __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(mine, 0, BLOCK_BYTES, 0x00027000);
     // layout inside a tile's partial block: [vector index][thread] -> coalesced 16-byte columns
 #pragma unroll
@@ -358,9 +558,9 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
     __syncthreads();
     int* lds_last = lds_misc;
     if (tid == 0) {
-      const uint32_t prev = __hip_atomic_fetch_add(a.sk_counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t prev = __hip_atomic_fetch_add(a.sk_counters + st, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const int last = prev == (uint32_t)(a.split_k - 1);
-      if (last) __hip_atomic_store(a.sk_counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+      if (last) __hip_atomic_store(a.sk_counters + st, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
       *lds_last = last;
     }
     __syncthreads();
@@ -376,7 +576,7 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
         for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
 #pragma unroll 4
     for (int s = 0; s < a.split_k; ++s) {
-      float* other = a.sk_partials + ((size_t)s * ntiles + tile) * (C::BM * C::BN);
+      float* other = a.sk_partials + ((size_t)s * a.split_tiles + st) * (C::BM * C::BN);
       __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(other, 0, BLOCK_BYTES, 0x00027000);
 #pragma unroll
       for (int mi = 0; mi < C::MI; ++mi)
@@ -396,30 +596,12 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
 
   // ---- epilogue: registers -> LDS (per wave, 32 rows at a time) -> 8 columns per lane ----
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * C::EP_STRIDE);
-  constexpr int CH = C::WTN / 8;          // 8-column chunks per row of the wave tile
-  constexpr int RPP = 64 / CH;            // rows per pass
-#pragma unroll
-  for (int mi = 0; mi < C::MI; ++mi) {
-#pragma unroll
-    for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
-      }
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int it = 0; it < 32 / RPP; ++it) {
-      const int r = it * RPP + lane / CH, cc = lane % CH;
-      const float4 x = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8);
-      const float4 y = *reinterpret_cast<const float4*>(ep + r * C::EP_STRIDE + cc * 8 + 4);
-      float v[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-      const int gm = m0 + wm * C::WTM + mi * 32 + r;
-      const int gn = n0 + wn * C::WTN + cc * 8;
-      if (!EDGE || (gm < a.M && gn < a.N)) epilogue_row8<EPI>(a, lds_outs, gm, gn, v);
-    }
-    __builtin_amdgcn_wave_barrier();
-  }
+  // (the dtype test stays outside the loop over blocks: inside it, the accumulators would no
+  // longer be kept in registers)
+  if (EPI == EPI_RS && a.partial_f32)
+    epilogue_all<C, EPI, EDGE, true, 2>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  else
+    epilogue_all<C, EPI, EDGE, false, 4>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
 }
 
 template <class C, int EPI, bool WAIT, bool EDGE>
@@ -428,27 +610,28 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
 
-  const int ntiles = a.tm.tiles_m * a.tm.tiles_n;
-  const int tile = (int)blockIdx.x % ntiles;
-  const int split = (int)blockIdx.x / ntiles;
+  int tile, split;
+  bool is_split;
+  map_block(a, (int)blockIdx.x, tile, split, is_split);
   int mt, nt;
   tile_coord(a.tm, tile, mt, nt);
   const int m0 = mt * C::BM, n0 = nt * C::BN;
   const int m1 = m0 + C::BM < a.M ? m0 + C::BM : a.M;
 
+  // output slices by rank (reduce-scatter) or chunk sources by rank (all-gather)
   void** lds_outs = reinterpret_cast<void**>(smem + C::PTRS_OFF);
-  if (EPI == EPI_RS) {
+  if (EPI == EPI_RS || WAIT) {
 #pragma unroll
     for (int j = 0; j < FLUX_MAX_RANKS; ++j)
       if (tid == j) lds_outs[j] = a.outs[j];     // made visible by the main loop's barriers
   }
 
   if (WAIT) {
-    if (!wait_signals(a, m0, m1, reinterpret_cast<int*>(smem + C::MISC_OFF))) return;
+    if (!wait_signals(a, m0, m1, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs)) return;
   }
 
-  const int k_begin = split * a.k_per_split;
-  const int k_end = (k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
+  const int k_begin = is_split ? split * a.k_per_split : 0;
+  const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
   const int KT = (k_end - k_begin + C::BK - 1) / C::BK;
 
   f32x16 acc[C::MI][C::NI];
@@ -478,7 +661,7 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
     }
   }
 
-  gemm_tail<C, EPI, EDGE>(a, smem, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs, acc, tile, split, ntiles,
+  gemm_tail<C, EPI, EDGE>(a, smem, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs, acc, tile, split, is_split,
                           m0, n0, tid, lane, wave, wm, wn);
 }
 
@@ -635,24 +818,24 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
 
-  const int ntiles = a.tm.tiles_m * a.tm.tiles_n;
-  const int tile = (int)blockIdx.x % ntiles;
-  const int split = (int)blockIdx.x / ntiles;
+  int tile, split;
+  bool is_split;
+  map_block(a, (int)blockIdx.x, tile, split, is_split);
   int mt, nt;
   tile_coord(a.tm, tile, mt, nt);
   const int m0 = mt * C::BM, n0 = nt * C::BN;
 
-  if (EPI == EPI_RS) {
+  if (EPI == EPI_RS || WAIT) {      // output slices (reduce-scatter) or chunk sources (all-gather), by rank
 #pragma unroll
     for (int j = 0; j < FLUX_MAX_RANKS; ++j)
       if (tid == j) lds_outs[j] = a.outs[j];
   }
   if (WAIT) {
-    if (!wait_signals(a, m0, m0 + C::BM, lds_misc)) return;
+    if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) return;
   }
 
-  const int k_begin = split * a.k_per_split;
-  const int k_end = (k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
+  const int k_begin = is_split ? split * a.k_per_split : 0;
+  const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
   const int KT = (k_end - k_begin) / C::BK;
 
   f32x16 acc[C::MI][C::NI];
@@ -683,7 +866,7 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
     mma_stage_dma<C, true>(stage0, stage1, ld, a, k_last, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
   }
-  gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, ntiles, m0, n0, tid, lane, wave, wm, wn);
+  gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, is_split, m0, n0, tid, lane, wave, wm, wn);
 }
 
 }  // namespace flux

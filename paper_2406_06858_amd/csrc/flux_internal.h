@@ -9,6 +9,7 @@ namespace flux {
 // One entry per compiled tile configuration (index = public id - 1).
 struct CfgInfo {
   int bm, bn, bk;
+  int occupancy;   // workgroups per CU the kernel is built for
   hipError_t (*launch)(int epi, int wait, int edge, const GemmArgs& a, int grid, hipStream_t s);
 };
 

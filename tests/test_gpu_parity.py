@@ -223,6 +223,43 @@ def test_split_k_bitwise_on_integers(split):
                 gh.assert_bits_equal(outs[r], want[r], f"rep {rep} slice {r}")
 
 
+@pytest.mark.parametrize("cfg,M,N,K", [(4, 1536, 1536, 1024), (1, 8192, 4608, 512), (3, 4608, 2048, 576)])
+def test_tail_split_bitwise_on_integers(cfg, M, N, K):
+    """Only the tiles of the partly filled last round are cut along K; the rest are computed whole."""
+    R = 8
+    wr = fi.Workload("int_rs_tail", "rs", M, N, K, R, a_dist=("int", 2), b_dist=("int", 2), peer_dist=("int", 8), seed=81)
+    wa = fi.Workload("int_ag_tail", "ag", M, N, K, R, a_dist=("int", 2), b_dist=("int", 2), seed=82)
+    p = fb.problem(M, N, K, R, 0, tile_config=cfg)
+    full, cut, k = fb.flux_split_plan(fb.FLUX_OP_RS, p)
+    assert full > 0 and cut > 0 and k > 1, (full, cut, k)
+    rank = 6
+    _say("tail split rs cfg", cfg, (full, cut, k))
+    A, B, peers = fi.make_rs_inputs(wr, rank)
+    _, want = gh.oracle_rs(wr, rank, A, B, peers)
+    p = fb.problem(M, N, K, R, rank, wr.partial_dtype, wr.out_dtype, cfg)
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
+    ws = gh.workspace_for(fb.FLUX_OP_RS, p)
+    ws.fill_(-1)
+    fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+    for rep in range(2):
+        outs = [torch.full((wr.S, N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(R)]
+        fb.flux_gemm_rs(p, dA, dB, dpeers, outs, ws)
+        torch.cuda.synchronize()
+        for r in range(R):
+            gh.assert_bits_equal(outs[r], want[r], f"rep {rep} slice {r}")
+    _say("tail split ag cfg", cfg)
+    chunks, B, arrival = fi.make_ag_inputs(wa, rank)
+    Cg, _, signals, status = gh.run_ag(wa, rank, chunks, B, arrival, tile_config=cfg, repeat=2)
+    assert status == (fb.FLUX_OK, 0)
+    _, want = gh.oracle_ag(wa, chunks, B)
+    gh.assert_bits_equal(Cg, want, f"cfg {cfg}")
+    # the flag switches the cut off; same bits
+    Cn, _, _, status = gh.run_ag(wa, rank, chunks, B, arrival, tile_config=cfg, flags=fb.FLUX_FLAG_NO_TAIL_SPLIT)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_bits_equal(Cn, want, f"cfg {cfg} no tail split")
+
+
 # ---------------------------------------------------------------------------------------------
 # AllGather protocol: orders, signals, copy engines, timing
 # ---------------------------------------------------------------------------------------------
@@ -262,6 +299,28 @@ def test_ag_delayed_copy_stream_still_correct():
     gh.assert_close(Cg, C64, w.out_dtype)
 
 
+def test_ag_waiting_workgroups_move_the_data_themselves():
+    """The copy driver is held back ~10 ms (host-forced) while a GEMM grid larger than the chip, in
+    natural tile order from a non-zero rank, starts with tiles that all have to wait.  The waiting
+    workgroups claim and move the pieces themselves: the GEMM kernel is over long before the copy
+    driver may even start, and the driver then finds nothing left to do."""
+    w = fi.scaled(W["c2_ag"], M=4096, N=2048, K=512)
+    rank = 5
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    for flags in (fb.FLUX_FLAG_NO_SWIZZLE, 0):
+        _say("cooperative copy, flags", flags)
+        e0, e1 = fb.HipEvent(), fb.HipEvent()
+        fb.flux_profile_next_gemm(e0, e1)
+        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=4, flags=flags,
+                                               delay_copy_cycles=20_000_000)
+        assert status == (fb.FLUX_OK, 0)
+        gh.assert_close(Cg, C64, w.out_dtype)
+        gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+        assert signals.cpu().tolist() == [1 if c == rank else 0 for c in range(w.R)]
+        assert e0.elapsed_ms(e1) < 5.0, "the GEMM kernel waited for the delayed copy driver"
+
+
 def test_ag_link_paced_copy_driver():
     """Emulated slow link (20 GB/s: each 256 KB chunk is released ~13 us after the previous one):
     tiles really wait for their chunk; results and the signal reset are unaffected."""
@@ -269,7 +328,7 @@ def test_ag_link_paced_copy_driver():
     rank = 4
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
     C64, _ = gh.oracle_ag(w, chunks, B)
-    for ctpc, flags in ((1, 0), (4, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE), (1, fb.FLUX_FLAG_COPY_FIRST)):
+    for ctpc, flags in ((1, 0), (4, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE)):
         Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, comm_tiles_per_chunk=ctpc, flags=flags,
                                            link_gbps=20, repeat=2)
         assert status == (fb.FLUX_OK, 0)
@@ -304,7 +363,8 @@ def test_ag_signal_wait_times_out_cleanly():
     w = AG_SMALL
     rank = 2
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
-    Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, delay_copy_cycles=20_000_000, timeout_ticks=1)
+    Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, delay_copy_cycles=20_000_000, timeout_ticks=1,
+                                       flags=fb.FLUX_FLAG_COPY_MEMCPY)      # plain waiting: nobody else moves the data
     code, detail = status
     assert code == fb.FLUX_ERR_TIMEOUT
     assert 0 <= detail < w.R and detail != rank

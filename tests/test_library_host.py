@@ -144,3 +144,26 @@ def test_workspace_bytes():
     assert shape.split_k == 4
     tiles = -(-64 // shape.tile_m) * (8192 // shape.tile_n)
     assert fb.flux_workspace_bytes(fb.FLUX_OP_RS, d) >= 4 * tiles * shape.tile_m * shape.tile_n * 4
+
+
+def test_split_plan_cuts_only_a_partly_filled_last_round():
+    # 32 x 18 tiles of 256x256 on 256 CUs: two full rounds, then 64 tiles -> those are cut 4 ways
+    p = fb.problem(8192, 4608, 12288, 8, 0)
+    for op in (fb.FLUX_OP_RS, fb.FLUX_OP_AG):
+        full, cut, k = fb.flux_split_plan(op, p)
+        assert (full, cut, k) == (512, 64, 4)
+        shape = fb.flux_tile_shape(op, p)
+        assert (shape.tile_m, shape.tile_n, shape.split_k) == (256, 256, 4)
+        assert fb.flux_workspace_bytes(op, p) >= 4 * 64 * 256 * 256 * 4
+    # switched off by flag, and an explicit split_k is a uniform one
+    q = fb.problem(8192, 4608, 12288, 8, 0, flags=fb.FLUX_FLAG_NO_TAIL_SPLIT)
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, q) == (0, 576, 1)
+    assert fb.flux_workspace_bytes(fb.FLUX_OP_RS, q) == 0
+    u = fb.problem(8192, 4608, 12288, 8, 0, split_k=2)
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, u) == (0, 576, 2)
+    # a last round that is more than half full, or a grid of exactly whole rounds, is left alone
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 6144, 12288, 8, 0)) == (0, 768, 1)
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 5632, 12288, 8, 0))[2] == 1   # 704 = 2.75 rounds
+    # short K: every part keeps at least four K slabs
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 4608, 512, 8, 0)) == (512, 64, 2)
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 4608, 256, 8, 0)) == (0, 576, 1)
