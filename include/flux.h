@@ -117,7 +117,10 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  * given a compute unit yet, a GEMM workgroup that has to wait for a tile moves pieces of it that
  * no one has started on, so the call completes even when the GEMM grid occupies every compute
  * unit first (its waiting workgroups do not leave).  With FLUX_FLAG_COPY_MEMCPY the driver is
- * hipMemcpyAsync plus a stream write per tile and the GEMM only waits.
+ * hipMemcpyAsync plus a stream write per tile and the GEMM only waits.  If the remote chunks add
+ * up to 8 MiB or less (decode), link_gbps is 0 and copy_workgroups is 0, no driver is launched
+ * and copy_stream stays unused: forking and joining a second stream would take longer than the
+ * transfer, so the waiting workgroups move all of it, each the tile it is waiting for.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.

@@ -13,11 +13,13 @@ namespace flux {
 
 // (not const: a const table of host function pointers would also be emitted for the device)
 CfgInfo g_cfgs[NUM_CFGS] = {
-    {256, 256, 64, 1, launch_cfg1}, {256, 128, 64, 1, launch_cfg2}, {128, 128, 64, 2, launch_cfg3},
-    {64, 64, 64, 2, launch_cfg4},   {64, 128, 64, 2, launch_cfg5},  {32, 128, 64, 2, launch_cfg6},
+    {256, 256, 64, 1, 2, launch_cfg1}, {256, 128, 64, 1, 2, launch_cfg2}, {128, 128, 64, 2, 2, launch_cfg3},
+    {64, 64, 64, 2, 2, launch_cfg4},   {64, 128, 64, 2, 2, launch_cfg5},  {32, 128, 64, 2, 2, launch_cfg6},
+    {64, 64, 64, 1, 6, launch_cfg7},   {32, 128, 64, 1, 6, launch_cfg8},  {64, 128, 64, 1, 4, launch_cfg9},
 };
 
 constexpr int N_CU = 256;                      // compute units of an MI355X
+constexpr unsigned long long SELF_COPY_MAX_BYTES = 8ull << 20;
 constexpr int N_XCD = 8;                       // accelerator dies of an MI355X, one L2 each
 constexpr unsigned long long DEFAULT_TIMEOUT_TICKS = 1000000000ull;   // 10 s at 100 MHz
 
@@ -170,6 +172,7 @@ struct Plan {
   // AllGather copy driver
   int copy_wgs;             // workgroups of the copy kernel = pieces per communication tile
   int copy_help;            // waiting GEMM workgroups may take pieces
+  int copy_self;            // no copy kernel at all: the waiting workgroups move everything
   size_t claim_bytes;       // claim words in the workspace, after the header
 };
 
@@ -206,16 +209,16 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   int cfg;
   if (p->tile_config > 0) {
     cfg = p->tile_config - 1;
-  } else if (p->M <= 32) {
-    cfg = 5;
-  } else if (p->M <= 64) {
-    cfg = 4;
-  } else if ((long long)p->M * p->N <= 256ll * 1024) {
-    cfg = 3;
-  } else if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 128) {
-    cfg = 0;          // 256x256: the least operand traffic per flop
   } else {
-    cfg = 2;          // 128x128: enough tiles to fill the chip on mid-sized problems
+    // few rows: the tile is bound by memory, so take the deep load pipeline if the shape allows its
+    // direct-to-LDS loads (whole tiles along N and K; M may be ragged), else the two-stage twin
+    const bool deep_ok = p->K % 64 == 0;
+    if (p->M <= 32) cfg = (deep_ok && p->N % 128 == 0) ? 7 : 5;          // 32x128
+    else if (p->M <= 64) cfg = (deep_ok && p->N % 64 == 0 && p->M == 64) ? 6 : 4;   // 64x64 deep, else 64x128
+    else if ((long long)p->M * p->N <= 256ll * 1024) cfg = 3;            // 64x64, small problems
+    else if (p->M <= 256 && p->M % 64 == 0 && deep_ok && p->N % 128 == 0) cfg = 8;   // 64x128 deep
+    else if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 128) cfg = 0;   // 256x256: the least operand traffic per flop
+    else cfg = 2;                                                        // 128x128: enough tiles to fill the chip on mid-sized problems
   }
   pl->cfg = cfg;
   pl->bm = g_cfgs[cfg].bm; pl->bn = g_cfgs[cfg].bn; pl->bk = g_cfgs[cfg].bk;
@@ -228,7 +231,12 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   int split = p->split_k;
   if (split <= 0) {
     split = 1;
-    if (tiles < 256) {                          // too few tiles to fill the chip: cut K as well
+    const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
+    if (g_cfgs[cfg].stages > 2) {
+      // deep pipeline, one workgroup per CU: as many K parts as still give a single round, each
+      // long enough for the pipeline to fill
+      if (tiles < slots) split = (int)std::max<long long>(1, std::min<long long>(slots / tiles, kt / 8));
+    } else if (tiles < 256) {                   // too few tiles to fill the chip: cut K as well
       split = (int)std::min<long long>((512 + tiles - 1) / tiles, 16);
       split = std::max(1, std::min(split, kt / 4));
       // parked fp32 partials (written and re-read) should not outweigh the operands themselves
@@ -256,10 +264,16 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   pl->k_per_split = kt_per * pl->bk;
   pl->split_tiles = split > 1 ? (int)split_tiles : (int)tiles;
   pl->full_tiles = (int)tiles - pl->split_tiles;
-  pl->edge = (p->M % pl->bm != 0) || (p->N % pl->bn != 0) || (p->K % pl->bk != 0);
+  // 0: the tile divides the shape; 1: ragged (register-staged kernel); 2: only M is ragged and the
+  // configuration has the deep pipeline, which reads rows past M as zeros.  That relies on the
+  // buffer range check, so it is only used where a lane's row is entirely part of its own offset
+  // (32-row tiles: one load instruction per wave covers all rows), not added per instruction.
+  if ((p->N % pl->bn != 0) || (p->K % pl->bk != 0)) pl->edge = 1;
+  else if (p->M % pl->bm != 0) pl->edge = (g_cfgs[cfg].stages > 2 && pl->bm == 32) ? 2 : 1;   // (see below)
+  else pl->edge = 0;
   pl->n_xcd = (p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_NO_XCD_REMAP)) ? 1 : N_XCD;
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
-  pl->copy_wgs = 0; pl->copy_help = 0; pl->claim_bytes = 0;
+  pl->copy_wgs = 0; pl->copy_help = 0; pl->copy_self = 0; pl->claim_bytes = 0;
   if (op == FLUX_OP_AG) {
     // unpaced: one workgroup per CU, over before most tiles need their rows; paced: a few are enough
     int wgs = p->copy_workgroups > 0 ? p->copy_workgroups : (p->link_gbps > 0 ? 32 : 256);
@@ -268,6 +282,19 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (tile_vec + 255) / 256));
     pl->copy_wgs = wgs;
     pl->copy_help = !(p->flags & FLUX_FLAG_COPY_MEMCPY);
+    // A transfer this small is over sooner than a second stream can be forked and joined: the
+    // GEMM grid pulls the tiles itself (every waiting workgroup helps) and no driver is launched.
+    const unsigned long long remote_bytes = (unsigned long long)(p->R - 1) * (p->M / p->R) * p->K * 2;
+    pl->copy_self = pl->copy_help && p->link_gbps == 0 && p->copy_workgroups == 0 && remote_bytes <= SELF_COPY_MAX_BYTES;
+    if (pl->copy_self) {
+      // about one piece per workgroup and tile it waits for: the workgroups that share an m-tile
+      // (all n-tiles, all K parts) split the communication tiles that m-tile covers
+      const int rows_per_signal = std::max(1, (p->M / p->R) / pl->ctpc);
+      const long long tiles_per_mtile = std::max(1, std::min(p->R * pl->ctpc, pl->bm / rows_per_signal));
+      const long long sharers = (long long)pl->tiles_n * pl->split_k;
+      wgs = (int)std::max<long long>(1, std::min<long long>(wgs, sharers / tiles_per_mtile));
+      pl->copy_wgs = wgs;
+    }
     pl->claim_bytes = (((size_t)p->R * pl->ctpc * wgs * 4) + 255) / 256 * 256;
   }
   return FLUX_OK;
@@ -618,6 +645,7 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   const uint32_t call_id = next_call_id();
   if (pl.copy_help && p->R > 1) {
     a.copy_pieces = pl.copy_wgs;
+    a.copy_driver_wgs = pl.copy_self ? 0 : pl.copy_wgs;
     a.copy_call_id = call_id;
     a.copy_tile_vec = (unsigned long long)chunk_elems / 8 / pl.ctpc;
     for (int r = 0; r < p->R; ++r) a.outs[r] = const_cast<void*>(A_chunks[r]);   // chunk sources by rank
@@ -630,6 +658,10 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
     int self = p->rank;
     st = launch_copy(p, pl, A_chunks, A_agg, &self, 1, false, nullptr, nullptr, 0, cs);
     if (st != FLUX_OK) return st;
+  }
+  if (pl.copy_self || p->R == 1) {
+    // nothing runs beside the GEMM grid: no fork, no join
+    return launch_gemm(pl, EPI_PLAIN, 1, a, cs);
   }
   // fork: the copy driver may start once everything queued so far on compute_stream is done
   FLUX_HIP(hipEventRecord(ev_fork, cs));

@@ -86,7 +86,9 @@ struct GemmArgs {
   uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
   uint32_t* copy_counters;   // [n_signals] pieces finished
   uint32_t copy_call_id;
-  int32_t copy_pieces;
+  int32_t copy_pieces;       // pieces per communication tile
+  int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none, the
+                             // waiting workgroups move everything)
   unsigned long long copy_tile_vec;   // 16-byte vectors per communication tile
   uint32_t* status;
   unsigned long long timeout_ticks;
@@ -165,7 +167,8 @@ struct TileCfg {
   static constexpr int A_VEC = BM * BK / 8 / NT, B_VEC = BK * BN / 8 / NT;
   static constexpr int EP_STRIDE = WTN + 8;                       // floats; 4 rows apart = 128 B off
   static constexpr int EP_BYTES = WAVES_M * WAVES_N * 32 * EP_STRIDE * 4;
-  static constexpr int MAIN_BYTES = NSTAGE * STAGE_BYTES > EP_BYTES ? NSTAGE * STAGE_BYTES : EP_BYTES;
+  static constexpr int ESTAGE = NSTAGE >= 2 ? 2 : 1;              // stages of the register-staged kernel
+  static constexpr int MAIN_BYTES = ESTAGE * STAGE_BYTES > EP_BYTES ? ESTAGE * STAGE_BYTES : EP_BYTES;
   static constexpr int MISC_OFF = MAIN_BYTES;              // 16 B: one int shared by the workgroup
   static constexpr int PTRS_OFF = MAIN_BYTES + 16;         // FLUX_MAX_RANKS output slice pointers
   static constexpr int LDS_BYTES = PTRS_OFF + 8 * FLUX_MAX_RANKS;
@@ -440,6 +443,7 @@ __device__ __forceinline__ void finish_piece(uint32_t* counter, uint32_t* signal
 // workgroup of this call has been or will be counted, and the next call starts after the driver
 // has finished).  Nothing is ever reset, so a workgroup that starts late cannot spoil a count.
 __device__ __forceinline__ bool driver_fully_started(const uint32_t* started, int workgroups) {
+  if (workgroups == 0) return false;
   const uint32_t total = __hip_atomic_load(started, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   const uint32_t base = __hip_atomic_load(started + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return total - base >= (uint32_t)workgroups;
@@ -449,64 +453,81 @@ __device__ __forceinline__ bool driver_fully_started(const uint32_t* started, in
 // then an acquire fence makes the copied rows visible; the workgroup barrier hands that to the
 // other waves.  As long as every workgroup of the copy driver is running, that is all.  If some
 // of them have not been given a compute unit yet (the GEMM grid may have taken them all, and its
-// waiting workgroups do not leave), waiting would not end: the workgroup then claims and moves
-// pieces of the communication tile it waits for itself.  Bounded: past `timeout_ticks` the tile is
-// given up and the status block says so.  A workgroup never looks at the signals again after
-// this, so the last workgroup of the grid to get here puts the signal array back into its preset
-// state for the next call (the reset "after the GEMM" of Sec. 4.3, without a separate launch).
+// waiting workgroups do not leave), or if no driver was launched at all (small transfers),
+// waiting would not end: the workgroup then claims and moves pieces of the communication tiles
+// it waits for itself, starting its search at a place that depends on its index so that the
+// workgroups of a grid spread over the pieces instead of racing for the same one.  Bounded: past
+// `timeout_ticks` the tile is given up and the status block says so.  A workgroup never looks at
+// the signals again after this, so the last workgroup of the grid to get here puts the signal
+// array back into its preset state for the next call (the reset "after the GEMM" of Sec. 4.3,
+// without a separate launch).
 // `lds` is 4 ints shared by the workgroup; `lds_srcs` holds the chunk sources by rank.
 __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, int* lds, void* const* lds_srcs) {
   const int tid = threadIdx.x;
   const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
   const unsigned long long t0 = wall_clock64();
   enum : int { ARRIVED = 1, GIVE_UP = 2, HELP = 3 };
+  const int nf = f1 - f0 + 1;
+  const int total = nf * a.copy_pieces;                    // pieces of all tiles waited for (<= 16 * 256)
+  uint32_t salt = (uint32_t)blockIdx.x * 0x9E3779B9u;      // varies per workgroup and per attempt
+  bool may_help = a.copy_pieces > 0;                       // until a search finds nothing left to take
   bool ok = true;
-  for (int f = f0; f <= f1 && ok; ++f) {
-    const bool can_help = a.copy_pieces > 0 && !(f >= a.sig_local_lo && f < a.sig_local_hi);
-    for (;;) {
-      if (tid == 0) {
-        int st;
-        for (int polls = 0;; ++polls) {
-          if (__hip_atomic_load(a.signals + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) { st = ARRIVED; break; }
-          if (wall_clock64() - t0 > a.timeout_ticks) {
-            if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)f;
-            st = GIVE_UP;
-            break;
-          }
-          if (can_help && polls >= 8 && !driver_fully_started(a.started_counter, a.copy_pieces)) { st = HELP; break; }
-          __builtin_amdgcn_s_sleep(16);
+  for (;;) {
+    if (tid == 0) {
+      int st;
+      for (int polls = 0;; ++polls) {
+        int f = f0;
+        while (f <= f1 && __hip_atomic_load(a.signals + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) ++f;
+        if (f > f1) { st = ARRIVED; break; }
+        if (wall_clock64() - t0 > a.timeout_ticks) {
+          if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)f;
+          st = GIVE_UP;
+          break;
         }
-        lds[0] = st;
-        lds[1] = 0x7fffffff;
+        if (may_help && (polls >= 8 || a.copy_driver_wgs == 0) &&
+            !driver_fully_started(a.started_counter, a.copy_driver_wgs)) { st = HELP; break; }
+        __builtin_amdgcn_s_sleep(16);
       }
-      __syncthreads();
-      const int st = lds[0];
-      __syncthreads();                    // everyone has read it before thread 0 can write again
-      if (st == ARRIVED) break;
-      if (st == GIVE_UP) { ok = false; break; }
-      // lowest piece of this tile that nobody has claimed
-      uint32_t* claims = a.copy_claims + (size_t)f * a.copy_pieces;
-      if (tid < a.copy_pieces &&
-          __hip_atomic_load(claims + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.copy_call_id)
-        atomicMin(&lds[1], tid);
-      __syncthreads();
-      const int piece = lds[1];
-      if (piece != 0x7fffffff) {
-        if (tid == 0) lds[2] = claim_piece(claims + piece, a.copy_call_id) ? 1 : 0;
-        __syncthreads();
-        if (lds[2]) {
-          const int ctpc = a.n_signals / a.R;
-          const uint4* src = static_cast<const uint4*>(lds_srcs[f / ctpc]) + (unsigned long long)(f % ctpc) * a.copy_tile_vec;
-          uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
-          copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
-          finish_piece(a.copy_counters + f, a.signals + f, a.copy_pieces);
-        }
-      } else {
-        // every piece is in the hands of a workgroup that is running: only waiting is left
-        __builtin_amdgcn_s_sleep(32);
-      }
-      __syncthreads();                    // lds[1], lds[2] are rewritten in the next round
+      lds[0] = st;
+      lds[1] = 0x7fffffff;
     }
+    __syncthreads();
+    const int st = lds[0];
+    __syncthreads();                    // everyone has read it before thread 0 can write again
+    if (st == ARRIVED) break;
+    if (st == GIVE_UP) { ok = false; break; }
+    // One of the unclaimed pieces among the tiles waited for, picked by a hash that differs per
+    // workgroup and attempt: workgroups that wait for the same tiles then rarely go for the same
+    // piece (taking "the first free one" would make them queue up behind each other).  The local
+    // chunk's tiles are never copied by anyone, their signals are preset.
+    salt = salt * 1664525u + 1013904223u;
+    for (int i = tid; i < total; i += blockDim.x) {
+      const int f = f0 + i / a.copy_pieces;
+      if (f >= a.sig_local_lo && f < a.sig_local_hi) continue;
+      if (__hip_atomic_load(a.copy_claims + (size_t)f * a.copy_pieces + i % a.copy_pieces, __ATOMIC_RELAXED,
+                            __HIP_MEMORY_SCOPE_AGENT) != a.copy_call_id) {
+        const uint32_t h = ((uint32_t)i * 2654435761u) ^ salt;
+        atomicMin(&lds[1], (int)(((h >> 14) << 12) | (uint32_t)i));   // 18 hash bits above the 12-bit index: below the "none" value
+      }
+    }
+    __syncthreads();
+    const int key = lds[1];
+    if (key != 0x7fffffff) {
+      const int i = key & 4095;
+      const int f = f0 + i / a.copy_pieces, piece = i % a.copy_pieces;
+      if (tid == 0) lds[2] = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + piece, a.copy_call_id) ? 1 : 0;
+      __syncthreads();
+      if (lds[2]) {
+        const int ctpc = a.n_signals / a.R;
+        const uint4* src = static_cast<const uint4*>(lds_srcs[f / ctpc]) + (unsigned long long)(f % ctpc) * a.copy_tile_vec;
+        uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
+        copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
+        finish_piece(a.copy_counters + f, a.signals + f, a.copy_pieces);
+      }
+    } else {
+      may_help = false;                 // every piece is in the hands of a workgroup that is running
+    }
+    __syncthreads();                    // lds[1], lds[2] are rewritten in the next round
   }
   if (tid == 0) {
     __atomic_thread_fence(__ATOMIC_ACQUIRE);   // system scope: covers copy kernels and DMA writers
@@ -515,8 +536,8 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
       for (int i = 0; i < a.n_signals; ++i)
         __hip_atomic_store(a.signals + i, (i >= a.sig_local_lo && i < a.sig_local_hi) ? 1u : 0u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
-      if (a.copy_pieces > 0)
-        __hip_atomic_fetch_add(a.started_counter + 1, (uint32_t)a.copy_pieces, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (a.copy_driver_wgs > 0)
+        __hip_atomic_fetch_add(a.started_counter + 1, (uint32_t)a.copy_driver_wgs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.done_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
@@ -651,12 +672,12 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
     ld.store(smem, ra, rb);
     __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
-      unsigned char* cur = smem + (C::NSTAGE == 2 ? (kt & 1) * C::STAGE_BYTES : 0);
+      unsigned char* cur = smem + (C::ESTAGE == 2 ? (kt & 1) * C::STAGE_BYTES : 0);
       const bool more = kt + 1 < KT;
       if (more) ld.load(a, k_begin + (kt + 1) * C::BK, k_end, ra, rb);
       mma_stage<C>(cur, wm, wn, lane, acc);
-      if (C::NSTAGE == 1) __syncthreads();
-      if (more) ld.store(smem + (C::NSTAGE == 2 ? ((kt + 1) & 1) * C::STAGE_BYTES : 0), ra, rb);
+      if (C::ESTAGE == 1) __syncthreads();
+      if (more) ld.store(smem + (C::ESTAGE == 2 ? ((kt + 1) & 1) * C::STAGE_BYTES : 0), ra, rb);
       __syncthreads();
     }
   }
@@ -755,6 +776,51 @@ __device__ __forceinline__ bf16x8 frag_b(const unsigned char* stage, int ks, int
   return __builtin_bit_cast(bf16x8, w);
 }
 
+// The same two fragment reads as instructions the compiler cannot look into.  For every LDS read
+// it can see, the compiler works out by itself how many of the direct-to-LDS loads still in flight
+// must land first; around a ring of more than two stages it gets that wrong on the safe side and
+// drains the pipeline.  With these reads the waits are the kernel's own: the counter wait before
+// the workgroup barrier for the loads, wait_lds_reads() for the fragments.
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+__device__ __forceinline__ uint32_t lds_address(const unsigned char* p) {
+  return (uint32_t)reinterpret_cast<uintptr_t>((const lds_byte_t*)p);
+}
+
+template <class C>
+__device__ __forceinline__ bf16x8 frag_a_opaque(uint32_t stage, int ks, int mi, int wm, int lane) {
+  const int row = wm * C::WTM + mi * 32 + (lane & 31);
+  const int q = ks * 2 + (lane >> 5);
+  const uint32_t addr = stage + row * (C::BK * 2) + ((q ^ swz_a<C::A_SLOTS>(row)) << 4);
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <class C>
+__device__ __forceinline__ bf16x8 frag_b_opaque(uint32_t stage, int ks, int ni, int wn, int lane) {
+  const int g = lane >> 4, i = lane & 15;
+  const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
+  const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);
+  const uint32_t addr = stage + C::A_BYTES + k * (C::BN * 2) + ((((n >> 3) ^ swz_b<C::B_SLOTS>(k))) << 4) + ((n >> 2) & 1) * 8;
+  typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+  u32x2 lo, hi;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr) : "memory");
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(addr + 4 * C::BN * 2) : "memory");
+  const u32x4 w = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+// All LDS reads issued so far have returned.  The fragments pass through it so that nothing that
+// uses them can be moved in front of the wait.
+template <int MI, int NI>
+__device__ __forceinline__ void wait_lds_reads(bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < MI; ++i) asm volatile("" : "+v"(af[i]));
+#pragma unroll
+  for (int i = 0; i < NI; ++i) asm volatile("" : "+v"(bfr[i]));
+}
+
 // One K-slab out of LDS stage `cur`, software-pipelined by hand:
 //   * the MFMAs run in (ks, mi) groups of NI; the fragments of k-step ks+1 are fetched while the
 //     MFMAs of ks run (two register sets);
@@ -793,6 +859,71 @@ __device__ __forceinline__ void mma_stage_dma(const unsigned char* cur, unsigned
         for (int m2 = 0; m2 < C::MI; ++m2) af[(ks + 1) & 1][m2] = frag_a<C>(cur, ks + 1, m2, wm, lane);
 #pragma unroll
         for (int ni = 0; ni < C::NI; ++ni) bfr[(ks + 1) & 1][ni] = frag_b<C>(cur, ks + 1, ni, wn, lane);
+      }
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][mi], bfr[ks & 1][ni], acc[mi][ni], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// mma_stage_dma with the opaque fragment reads: the fragments of k-step ks are waited for at the
+// top of the step, then those of ks+1 are requested, then the MFMAs of ks run.
+template <class C>
+__device__ __forceinline__ void mma_stage_dma_opaque(const unsigned char* cur_p, unsigned char* nxt, const DmaLoader<C>& ld,
+                                                     const GemmArgs& a, int k_next, int wave, int wm, int wn, int lane,
+                                                     f32x16 (&acc)[C::MI][C::NI]) {
+  constexpr int KS = C::BK / 16;
+  constexpr int G = KS * C::MI;
+  constexpr int L = DmaLoader<C>::N_INSTR;
+  constexpr int GS = (G * 3 + 3) / 4;
+  const uint32_t cur = lds_address(cur_p);
+  if constexpr (C::MI * C::NI == 1) {
+    // One MFMA per k-step (the 32x32 wave tiles of the decode configurations): nothing to
+    // hide fragment reads behind, and the tile is bound by memory anyway.  Request the next slab
+    // first, fetch all fragments of this one in one go, wait once.
+    ld.issue(a, nxt, k_next, wave);
+    bf16x8 af[KS * C::MI], bfr[KS * C::NI];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi) af[ks * C::MI + mi] = frag_a_opaque<C>(cur, ks, mi, wm, lane);
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni) bfr[ks * C::NI + ni] = frag_b_opaque<C>(cur, ks, ni, wn, lane);
+    }
+    wait_lds_reads<KS * C::MI, KS * C::NI>(af, bfr);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks * C::MI + mi], bfr[ks * C::NI + ni], acc[mi][ni], 0, 0, 0);
+    return;
+  }
+  bf16x8 af[2][C::MI], bfr[2][C::NI];
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi) af[0][mi] = frag_a_opaque<C>(cur, 0, mi, wm, lane);
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) bfr[0][ni] = frag_b_opaque<C>(cur, 0, ni, wn, lane);
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    wait_lds_reads<C::MI, C::NI>(af[ks & 1], bfr[ks & 1]);
+    if (ks + 1 < KS) {
+#pragma unroll
+      for (int m2 = 0; m2 < C::MI; ++m2) af[(ks + 1) & 1][m2] = frag_a_opaque<C>(cur, ks + 1, m2, wm, lane);
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni) bfr[(ks + 1) & 1][ni] = frag_b_opaque<C>(cur, ks + 1, ni, wn, lane);
+    }
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi) {
+      const int g = ks * C::MI + mi;
+      if (g < GS) {
+        const int lo = g * L / GS, hi = (g + 1) * L / GS;
+#pragma unroll
+        for (int idx = 0; idx < L; ++idx)
+          if (idx >= lo && idx < hi) ld.issue_dyn(idx, a, nxt, k_next, wave);
       }
 #pragma unroll
       for (int ni = 0; ni < C::NI; ++ni)
@@ -867,6 +998,105 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
     wait_vm0_and_barrier();
   }
   gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, is_split, m0, n0, tid, lane, wave, wm, wn);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same pipeline with NSTAGE >= 3 LDS stages, for tiles that have little arithmetic per byte
+// (few rows: decode).  Such a tile is bound by how many bytes its compute unit keeps in flight:
+// slab kt is computed while the loads of slabs kt+1 .. kt+NSTAGE-1 are outstanding.  Loads land in
+// issue order, so "all but the (NSTAGE-2) youngest slabs have landed" is a plain counter wait.
+// Stages are separate arrays (see above); the epilogue has its own staging area, so the tail of
+// the load pipeline need not drain before it starts.
+// ---------------------------------------------------------------------------------------------
+template <int N>
+__device__ __forceinline__ void wait_vm_at_most() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));   // expcnt and lgkmcnt: no wait
+}
+
+// Workgroup barrier that lets this wave's younger loads stay in flight.  The compiler puts a wait
+// for ALL outstanding memory operations in front of every barrier instruction it can see, which
+// would empty the pipeline once per slab; it does not look inside this one.  What the barrier has
+// to order is covered by the counter wait placed before it.
+__device__ __forceinline__ void barrier_keeping_loads_in_flight() {
+  asm volatile("s_barrier" ::: "memory");
+}
+
+// MASK: M is not a multiple of the tile height.  Rows past M are read as zeros (they lie outside
+// the buffer resource of A) and the epilogue leaves them out.
+template <class C, int EPI, bool WAIT, bool MASK>
+__global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const GemmArgs a) {
+  constexpr int NS = C::NSTAGE;
+  static_assert(NS >= 3 && NS <= 6, "3 to 6 stages");
+  constexpr int L = DmaLoader<C>::N_INSTR;                  // loads per slab and wave
+  static_assert((NS - 2) * L < 64, "outstanding loads must fit the counter");
+#define FLUX_STAGE_BYTES(i) ((i) < NS ? C::STAGE_BYTES : 16)
+  __shared__ __attribute__((aligned(1024))) unsigned char st0[FLUX_STAGE_BYTES(0)];
+  __shared__ __attribute__((aligned(1024))) unsigned char st1[FLUX_STAGE_BYTES(1)];
+  __shared__ __attribute__((aligned(1024))) unsigned char st2[FLUX_STAGE_BYTES(2)];
+  __shared__ __attribute__((aligned(1024))) unsigned char st3[FLUX_STAGE_BYTES(3)];
+  __shared__ __attribute__((aligned(1024))) unsigned char st4[FLUX_STAGE_BYTES(4)];
+  __shared__ __attribute__((aligned(1024))) unsigned char st5[FLUX_STAGE_BYTES(5)];
+#undef FLUX_STAGE_BYTES
+  __shared__ __attribute__((aligned(16))) unsigned char ep_stage[C::EP_BYTES];
+  __shared__ int lds_misc[4];
+  __shared__ void* lds_outs[FLUX_MAX_RANKS];
+  unsigned char* const st[6] = {st0, st1, st2, st3, st4, st5};
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+
+  int tile, split;
+  bool is_split;
+  map_block(a, (int)blockIdx.x, tile, split, is_split);
+  int mt, nt;
+  tile_coord(a.tm, tile, mt, nt);
+  const int m0 = mt * C::BM, n0 = nt * C::BN;
+
+  if (EPI == EPI_RS || WAIT) {
+#pragma unroll
+    for (int j = 0; j < FLUX_MAX_RANKS; ++j)
+      if (tid == j) lds_outs[j] = a.outs[j];
+  }
+  if (WAIT) {
+    const int m1 = (!MASK || m0 + C::BM < a.M) ? m0 + C::BM : a.M;
+    if (!wait_signals(a, m0, m1, lds_misc, lds_outs)) return;
+  }
+
+  const int k_begin = is_split ? split * a.k_per_split : 0;
+  const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
+  const int KT = (k_end - k_begin) / C::BK;
+
+  f32x16 acc[C::MI][C::NI];
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
+
+  DmaLoader<C> ld;
+  ld.init(a, m0, n0, wave, lane);
+  // Slabs past the end are replaced by the last one: every step issues the same number of loads,
+  // which keeps the counter wait a constant and the loop one shape.  Such a repeat lands in a
+  // stage whose slab has been consumed, never in the one the last slab is read from.
+  const int last = KT - 1;
+#pragma unroll
+  for (int j = 0; j < NS - 1; ++j) ld.issue(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
+  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+      const int kt = kt0 + j;
+      if (kt < KT) {
+        wait_vm_at_most<(NS - 2) * L>();     // slab kt has landed (this wave's part of it)
+        barrier_keeping_loads_in_flight();   // ... everyone's part; and slab kt-1 has been read by all
+        const int kn = kt + NS - 1 < last ? kt + NS - 1 : last;
+        mma_stage_dma_opaque<C>(st[j], st[(j + NS - 1) % NS], ld, a, k_begin + kn * C::BK, wave, wm, wn, lane, acc);
+      }
+    }
+  }
+  wait_vm_at_most<0>();
+  gemm_tail<C, EPI, MASK>(a, ep_stage, lds_misc, lds_outs, acc, tile, split, is_split, m0, n0, tid, lane, wave, wm, wn);
 }
 
 }  // namespace flux

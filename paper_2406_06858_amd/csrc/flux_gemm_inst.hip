@@ -16,19 +16,33 @@ typedef TileCfg<64, 64, 64, 2, 2, 2, 2> Cfg;     // 32x32 per wave, small proble
 typedef TileCfg<64, 128, 64, 2, 2, 2, 2> Cfg;    // decode, M <= 64
 #elif FLUX_CFG_ID == 6
 typedef TileCfg<32, 128, 64, 1, 4, 2, 2> Cfg;    // decode, M <= 32
+#elif FLUX_CFG_ID == 7
+typedef TileCfg<64, 64, 64, 2, 2, 6, 1> Cfg;     // decode, M <= 64: six LDS stages, one workgroup per CU
+#elif FLUX_CFG_ID == 8
+typedef TileCfg<32, 128, 64, 1, 4, 6, 1> Cfg;    // decode, M <= 32: six LDS stages
+#elif FLUX_CFG_ID == 9
+typedef TileCfg<64, 128, 64, 2, 2, 4, 1> Cfg;    // M <= 256: four LDS stages
 #else
-#error "FLUX_CFG_ID must be 1..6"
+#error "FLUX_CFG_ID must be 1..9"
 #endif
 
-// Shapes the tile divides take the direct-to-LDS kernel; ragged shapes the register-staged one,
-// which masks rows, columns and the K tail.
-template <int EPI, bool WAIT, bool EDGE>
+// Shapes the tile divides take a direct-to-LDS kernel (two stages, or the deep pipeline for
+// configurations with more); ragged shapes the register-staged one, which masks rows, columns
+// and the K tail.  The deep pipeline also takes shapes where only M is ragged (edge = 2).
+enum : int { EDGE_NONE = 0, EDGE_ANY = 1, EDGE_ROWS = 2 };
+
+template <int EPI, bool WAIT, int EDGE>
 static hipError_t launch_one(const GemmArgs& a, int grid, hipStream_t s) {
-  if constexpr (!EDGE && Cfg::NSTAGE == 2) {
+  if constexpr (EDGE == EDGE_NONE && Cfg::NSTAGE == 2) {
     hipLaunchKernelGGL((gemm_kernel_dma<Cfg, EPI, WAIT>), dim3(grid), dim3(Cfg::NT), 0, s, a);
     return hipGetLastError();
+  } else if constexpr (EDGE != EDGE_ANY && Cfg::NSTAGE >= 3) {
+    hipLaunchKernelGGL((gemm_kernel_dma_deep<Cfg, EPI, WAIT, EDGE == EDGE_ROWS>), dim3(grid), dim3(Cfg::NT), 0, s, a);
+    return hipGetLastError();
+  } else if constexpr (EDGE == EDGE_ROWS) {
+    return hipErrorInvalidValue;     // only asked of the deep pipeline
   } else {
-    auto k = gemm_kernel<Cfg, EPI, WAIT, EDGE>;
+    auto k = gemm_kernel<Cfg, EPI, WAIT, EDGE == EDGE_ANY>;
     static bool attr_set = false;
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k),
@@ -41,13 +55,20 @@ static hipError_t launch_one(const GemmArgs& a, int grid, hipStream_t s) {
   }
 }
 
+template <int EPI, bool WAIT>
+static hipError_t launch_edge(int edge, const GemmArgs& a, int grid, hipStream_t s) {
+  if (edge == EDGE_ANY) return launch_one<EPI, WAIT, EDGE_ANY>(a, grid, s);
+  if (edge == EDGE_ROWS) return launch_one<EPI, WAIT, EDGE_ROWS>(a, grid, s);
+  return launch_one<EPI, WAIT, EDGE_NONE>(a, grid, s);
+}
+
 #define FLUX_CAT2(a, b) a##b
 #define FLUX_CAT(a, b) FLUX_CAT2(a, b)
 
 hipError_t FLUX_CAT(launch_cfg, FLUX_CFG_ID)(int epi, int wait, int edge, const GemmArgs& a, int grid, hipStream_t s) {
-  if (epi == EPI_RS) return edge ? launch_one<EPI_RS, false, true>(a, grid, s) : launch_one<EPI_RS, false, false>(a, grid, s);
-  if (wait) return edge ? launch_one<EPI_PLAIN, true, true>(a, grid, s) : launch_one<EPI_PLAIN, true, false>(a, grid, s);
-  return edge ? launch_one<EPI_PLAIN, false, true>(a, grid, s) : launch_one<EPI_PLAIN, false, false>(a, grid, s);
+  if (epi == EPI_RS) return launch_edge<EPI_RS, false>(edge, a, grid, s);
+  if (wait) return launch_edge<EPI_PLAIN, true>(edge, a, grid, s);
+  return launch_edge<EPI_PLAIN, false>(edge, a, grid, s);
 }
 
 void FLUX_CAT(info_cfg, FLUX_CFG_ID)(int* bm, int* bn, int* bk) {

@@ -10,10 +10,11 @@ namespace flux {
 struct CfgInfo {
   int bm, bn, bk;
   int occupancy;   // workgroups per CU the kernel is built for
+  int stages;      // LDS stages of the direct-to-LDS kernel (more than two: the deep pipeline)
   hipError_t (*launch)(int epi, int wait, int edge, const GemmArgs& a, int grid, hipStream_t s);
 };
 
-constexpr int NUM_CFGS = 6;
+constexpr int NUM_CFGS = 9;
 extern CfgInfo g_cfgs[NUM_CFGS];
 
 #define FLUX_DECLARE_CFG(ID) \
@@ -25,5 +26,8 @@ FLUX_DECLARE_CFG(3)
 FLUX_DECLARE_CFG(4)
 FLUX_DECLARE_CFG(5)
 FLUX_DECLARE_CFG(6)
+FLUX_DECLARE_CFG(7)
+FLUX_DECLARE_CFG(8)
+FLUX_DECLARE_CFG(9)
 
 }  // namespace flux

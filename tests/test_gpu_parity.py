@@ -14,7 +14,7 @@ import gpu_harness as gh
 pytestmark = pytest.mark.gpu
 
 W = fi.WORKLOADS
-ALL_CFGS = [1, 2, 3, 4, 5, 6]
+ALL_CFGS = [1, 2, 3, 4, 5, 6, 7, 8, 9]
 
 
 def _say(*a):
@@ -80,7 +80,8 @@ def test_ag_exact_integers_bitwise(cfg):
         _say("int_ag cfg", cfg, "rank", rank)
         chunks, B, arrival = fi.make_ag_inputs(w, rank)
         # three calls in a row on the same buffers: each must leave signals and counters ready
-        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=cfg, repeat=3)
+        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=cfg, repeat=3,
+                                               copy_workgroups=16 if rank else 0)    # copy kernel / none
         assert status == (fb.FLUX_OK, 0)
         _, want = gh.oracle_ag(w, chunks, B)
         gh.assert_bits_equal(Cg, want, f"cfg {cfg}")
@@ -279,11 +280,13 @@ def test_ag_arrival_orders_and_copy_engines(order, flags):
         arrival = list(reversed(fo.default_order(rank, w.R)))
     _say("ag order", order, "flags", flags)
     C64, _ = gh.oracle_ag(w, chunks, B)
-    for ctpc in (0, 2, 4):
+    # copy_workgroups = 0 lets the library choose: for a transfer this small, no copy kernel at all
+    # (the waiting workgroups pull the tiles); a number asks for the copy kernel on the copy stream
+    for ctpc, cw in ((0, 0), (2, 0), (4, 0), (0, 48), (2, 48), (4, 7)):
         Cg, _, signals, status = gh.run_ag(w, rank, chunks, B, arrival, flags=flags, comm_tiles_per_chunk=ctpc,
-                                           tile_config=3)
+                                           tile_config=3, copy_workgroups=cw)
         assert status == (fb.FLUX_OK, 0)
-        gh.assert_close(Cg, C64, w.out_dtype, f"ctpc {ctpc}")
+        gh.assert_close(Cg, C64, w.out_dtype, f"ctpc {ctpc} cw {cw}")
         n = max(1, ctpc)
         assert signals.cpu().tolist() == [1 if i // n == rank else 0 for i in range(w.R * n)]
 
@@ -294,7 +297,7 @@ def test_ag_delayed_copy_stream_still_correct():
     rank = 0
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
     C64, _ = gh.oracle_ag(w, chunks, B)
-    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival, delay_copy_cycles=20_000_000)
+    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival, delay_copy_cycles=20_000_000, copy_workgroups=64)
     assert status == (fb.FLUX_OK, 0)
     gh.assert_close(Cg, C64, w.out_dtype)
 
@@ -313,7 +316,7 @@ def test_ag_waiting_workgroups_move_the_data_themselves():
         e0, e1 = fb.HipEvent(), fb.HipEvent()
         fb.flux_profile_next_gemm(e0, e1)
         Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=4, flags=flags,
-                                               delay_copy_cycles=20_000_000)
+                                               delay_copy_cycles=20_000_000, copy_workgroups=256)
         assert status == (fb.FLUX_OK, 0)
         gh.assert_close(Cg, C64, w.out_dtype)
         gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
