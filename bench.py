@@ -116,8 +116,10 @@ def main() -> int:
             os_ = 2 if w.out_dtype == "bf16" else 4
             return 2.0 * (w.M * w.K + w.K * w.N) + (w.R - 1) * w.M * w.N * ps + w.M * w.N * os_
 
-    def time_calls(fn, reps, warm):
-        """Median wall time (ms) of `fn` measured with events on the compute stream."""
+    def time_calls(fn, reps, warm, batch=8):
+        """Median time per call (ms), measured with events on the compute stream around `batch` calls
+        enqueued back to back: the steady state of a stream that is kept fed (the way an operator runs
+        inside a model), not the latency of one call on an idle device."""
         t_w = time.perf_counter()
         while time.perf_counter() - t_w < 0.3:      # keep the clocks where sustained load puts them
             fn()
@@ -129,10 +131,11 @@ def main() -> int:
         for _ in range(reps):
             e0, e1 = fb.HipEvent(), fb.HipEvent()
             e0.record(compute)
-            fn()
+            for _ in range(batch):
+                fn()
             e1.record(compute)
             e1.synchronize()
-            ts.append(e0.elapsed_ms(e1))
+            ts.append(e0.elapsed_ms(e1) / batch)
         return statistics.median(ts)
 
     def overlap_block(op, reps=20, warm=5):
@@ -142,8 +145,8 @@ def main() -> int:
         t_unf = time_calls(lambda: op.unfused(fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM), reps, warm)
         t_fus = time_calls(op.fused, reps, warm)
         # duration of the fused GEMM kernel alone (events recorded by the library around its
-        # launch): what the per-kernel roofline figures use; the call times above also carry
-        # launch and cross-stream latencies, which dominate the decode shapes
+        # launch): what the per-kernel roofline figures use; the per-call times above also carry
+        # what is left of launch and cross-stream latencies in a stream that is kept fed
         ks = []
         for _ in range(reps):
             k0, k1 = fb.HipEvent(), fb.HipEvent()

@@ -113,14 +113,16 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
 /*
  * AllGather-GEMM, fused (Alg. 2 kernel + Alg. 3 host driver, pull form).
  * The copy driver is a kernel on copy_stream that moves the remote chunks communication tile by
- * communication tile in `arrival_order`.  While some of the driver's workgroups have not been
- * given a compute unit yet, a GEMM workgroup that has to wait for a tile moves pieces of it that
- * no one has started on, so the call completes even when the GEMM grid occupies every compute
- * unit first (its waiting workgroups do not leave).  With FLUX_FLAG_COPY_MEMCPY the driver is
+ * communication tile in `arrival_order` and sets each tile's signal.  A GEMM workgroup that has to
+ * wait for a tile occupies its compute unit anyway, so instead of only spinning it moves pieces of
+ * that tile which no one has started on (pieces are claimed, so nothing is moved twice).  This
+ * also means the call completes when the GEMM grid takes every compute unit before the driver got
+ * one.  Exceptions: a paced driver (link_gbps > 0) stands for a link, so workgroups only step in
+ * while part of the driver has not started; with FLUX_FLAG_COPY_MEMCPY the driver is
  * hipMemcpyAsync plus a stream write per tile and the GEMM only waits.  If the remote chunks add
  * up to 8 MiB or less (decode), link_gbps is 0 and copy_workgroups is 0, no driver is launched
  * and copy_stream stays unused: forking and joining a second stream would take longer than the
- * transfer, so the waiting workgroups move all of it, each the tile it is waiting for.
+ * transfer, so the waiting workgroups move all of it, each the tiles it is waiting for.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.

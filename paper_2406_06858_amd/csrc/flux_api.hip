@@ -275,8 +275,9 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
   pl->copy_wgs = 0; pl->copy_help = 0; pl->copy_self = 0; pl->claim_bytes = 0;
   if (op == FLUX_OP_AG) {
-    // unpaced: one workgroup per CU, over before most tiles need their rows; paced: a few are enough
-    int wgs = p->copy_workgroups > 0 ? p->copy_workgroups : (p->link_gbps > 0 ? 32 : 256);
+    // A small driver: it keeps the later chunks coming in the background while waiting GEMM
+    // workgroups pull what they need now; a large one would sit on compute units the GEMM wants.
+    int wgs = p->copy_workgroups > 0 ? p->copy_workgroups : 32;
     wgs = std::min(wgs, MAX_COPY_PIECES);
     const unsigned long long tile_vec = (unsigned long long)(p->M / p->R) * p->K / 8 / pl->ctpc;
     wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (tile_vec + 255) / 256));
@@ -646,6 +647,9 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   if (pl.copy_help && p->R > 1) {
     a.copy_pieces = pl.copy_wgs;
     a.copy_driver_wgs = pl.copy_self ? 0 : pl.copy_wgs;
+    // A waiting workgroup holds a whole compute unit: unless the driver stands for a link of a given
+    // rate, it moves pieces of what it waits for right away instead of spinning next to the driver.
+    a.copy_eager = pl.copy_self || p->link_gbps == 0;
     a.copy_call_id = call_id;
     a.copy_tile_vec = (unsigned long long)chunk_elems / 8 / pl.ctpc;
     for (int r = 0; r < p->R; ++r) a.outs[r] = const_cast<void*>(A_chunks[r]);   // chunk sources by rank

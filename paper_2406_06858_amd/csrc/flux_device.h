@@ -89,6 +89,7 @@ struct GemmArgs {
   int32_t copy_pieces;       // pieces per communication tile
   int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none, the
                              // waiting workgroups move everything)
+  int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
   unsigned long long copy_tile_vec;   // 16-byte vectors per communication tile
   uint32_t* status;
   unsigned long long timeout_ticks;
@@ -484,8 +485,10 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
           st = GIVE_UP;
           break;
         }
-        if (may_help && (polls >= 8 || a.copy_driver_wgs == 0) &&
-            !driver_fully_started(a.started_counter, a.copy_driver_wgs)) { st = HELP; break; }
+        if (may_help && (a.copy_eager || (polls >= 8 && !driver_fully_started(a.started_counter, a.copy_driver_wgs)))) {
+          st = HELP;
+          break;
+        }
         __builtin_amdgcn_s_sleep(16);
       }
       lds[0] = st;
