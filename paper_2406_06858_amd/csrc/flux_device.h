@@ -316,7 +316,7 @@ __device__ __forceinline__ void make_peer_bufs(const GemmArgs& a, int m0, int n0
 // columns of a row per pass.  With the reduce-scatter epilogue the peer loads of BATCH passes are
 // issued together before any of them is used (PF32: fp32 partials, two 16-byte loads per peer);
 // the peers are added in ascending rank order.
-template <class C, int EPI, bool EDGE, bool PF32, int BATCH>
+template <class C, int EPI, bool EDGE, bool PF32, int BATCH, int NP>
 __device__ __forceinline__ void epilogue_block(const GemmArgs& a, void* const* lds_outs, const float* ep, const PeerBufs& pb,
                                                int row_base, int col_base, int m0, int n0, int lane) {
   constexpr int CH = C::WTN / 8;          // 8-column pieces per row of the wave tile
@@ -324,13 +324,12 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& a, void* const* l
   constexpr int NIT = 32 / RPP;
   constexpr int B = BATCH < NIT ? BATCH : NIT;
   constexpr int LPP = PF32 ? 2 : 1;
-  constexpr int NP = FLUX_MAX_RANKS - 1;
   constexpr int NT_HINT = 2;              // cache policy: streamed once, do not keep
   static_assert(NIT % B == 0, "batch must divide the passes");
   const int cc = lane % CH, rl = lane / CH;
 #pragma unroll
   for (int it0 = 0; it0 < NIT; it0 += B) {
-    u32x4 w[B][NP][LPP];
+    u32x4 w[B][NP > 0 ? NP : 1][LPP];
     bool ok[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) {
@@ -365,11 +364,14 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& a, void* const* l
       }
       if (ok[b]) store_row8<EPI>(a, lds_outs, m0 + row_base + r, n0 + col_base + cc * 8, v);
     }
+    // one batch of peer loads in flight at a time: left alone, the scheduler hoists the loads of
+    // later batches up here too and has to spill accumulators to make room for them
+    if (EPI == EPI_RS) __builtin_amdgcn_sched_barrier(0);
   }
 }
 
 // The whole epilogue of one wave: its accumulators pass through LDS 32 rows at a time.
-template <class C, int EPI, bool EDGE, bool PF32, int BATCH>
+template <class C, int EPI, bool EDGE, bool PF32, int BATCH, int NP>
 __device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds_outs, float* ep, f32x16 (&acc)[C::MI][C::NI],
                                              int m0, int n0, int lane, int wm, int wn) {
   PeerBufs pb;
@@ -384,7 +386,7 @@ __device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds
         ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
       }
     __builtin_amdgcn_wave_barrier();
-    epilogue_block<C, EPI, EDGE, PF32, BATCH>(a, lds_outs, ep, pb, wm * C::WTM + mi * 32, wn * C::WTN, m0, n0, lane);
+    epilogue_block<C, EPI, EDGE, PF32, BATCH, NP>(a, lds_outs, ep, pb, wm * C::WTM + mi * 32, wn * C::WTN, m0, n0, lane);
     __builtin_amdgcn_wave_barrier();
   }
 }
@@ -620,12 +622,19 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
 
   // ---- epilogue: registers -> LDS (per wave, 32 rows at a time) -> 8 columns per lane ----
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * C::EP_STRIDE);
-  // (the dtype test stays outside the loop over blocks: inside it, the accumulators would no
-  // longer be kept in registers)
-  if (EPI == EPI_RS && a.partial_f32)
-    epilogue_all<C, EPI, EDGE, true, 2>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
-  else
-    epilogue_all<C, EPI, EDGE, false, 4>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  // (the dtype and rank-count tests stay outside the loop over blocks: inside it, the accumulators
+  // would no longer be kept in registers.  Up to 8 ranks, 7 peer loads per piece are issued, else 15:
+  // loads from absent peers return zeros but still cost an issue slot and four registers each.)
+  constexpr int NP_ALL = FLUX_MAX_RANKS - 1, NP_8 = 7;
+  if (EPI != EPI_RS) {
+    epilogue_all<C, EPI, EDGE, false, 2, 0>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  } else if (a.R <= NP_8 + 1) {
+    if (a.partial_f32) epilogue_all<C, EPI, EDGE, true, 1, NP_8>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+    else epilogue_all<C, EPI, EDGE, false, 2, NP_8>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  } else {
+    if (a.partial_f32) epilogue_all<C, EPI, EDGE, true, 1, NP_ALL>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+    else epilogue_all<C, EPI, EDGE, false, 1, NP_ALL>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  }
 }
 
 template <class C, int EPI, bool WAIT, bool EDGE>

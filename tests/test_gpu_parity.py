@@ -59,6 +59,31 @@ def test_rs_exact_integers_bitwise(cfg, pd, od):
             gh.assert_bits_equal(outs[r], want[r], f"cfg {cfg} slice {r}")
 
 
+@pytest.mark.parametrize("R,rank", [(16, 0), (16, 9), (12, 11), (1, 0), (3, 1)])
+@pytest.mark.parametrize("pd,od", [("bf16", "bf16"), ("f32", "f32")])
+def test_rank_counts_bitwise(R, rank, pd, od):
+    """Other numbers of virtual ranks than 8: up to 8 ranks the epilogue issues 7 peer loads per piece,
+    above that 15; one rank has no peers at all.  Same for the AllGather signals and chunks."""
+    wr = fi.Workload("int_rs_r", "rs", 192 * R // (R if R < 4 else 4), 256, 192, R, a_dist=("int", 2), b_dist=("int", 2),
+                     peer_dist=("int", 4), partial_dtype=pd, out_dtype=od, seed=83)
+    _say("ranks", R, rank, pd, od, "M", wr.M)
+    A, B, peers = fi.make_rs_inputs(wr, rank)
+    _, want = gh.oracle_rs(wr, rank, A, B, peers)
+    for cfg in (0, 1, 4):
+        outs = gh.run_rs(wr, rank, A, B, peers, tile_config=cfg)
+        for r in range(R):
+            gh.assert_bits_equal(outs[r], want[r], f"cfg {cfg} slice {r}")
+    if pd == "bf16":
+        wa = fi.Workload("int_ag_r", "ag", wr.M, 256, 192, R, a_dist=("int", 2), b_dist=("int", 2), seed=84)
+        chunks, Ba, arrival = fi.make_ag_inputs(wa, rank)
+        _, want = gh.oracle_ag(wa, chunks, Ba)
+        for cw in (0, 8):
+            Cg, _, signals, status = gh.run_ag(wa, rank, chunks, Ba, arrival, copy_workgroups=cw, repeat=2)
+            assert status == (fb.FLUX_OK, 0)
+            gh.assert_bits_equal(Cg, want, f"ag cw {cw}")
+            assert signals.cpu().tolist() == [1 if c == rank else 0 for c in range(R)]
+
+
 @pytest.mark.parametrize("cfg", ALL_CFGS)
 def test_rs_ragged_shapes_bitwise(cfg):
     # M, N, K are multiples of neither tile size; slice height 125 straddles tiles
