@@ -471,43 +471,60 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   const unsigned long long t0 = wall_clock64();
   enum : int { ARRIVED = 1, GIVE_UP = 2, HELP = 3 };
   const int nf = f1 - f0 + 1;
-  const int total = nf * a.copy_pieces;                    // pieces of all tiles waited for (<= 16 * 256)
+  // The search for a piece covers a window of at most 4096 pieces (12 index bits in the key below),
+  // starting at the first tile whose signal is still missing, so it moves on as tiles complete.
+  const int window_tiles = a.copy_pieces > 0 ? (4096 / a.copy_pieces < nf ? 4096 / a.copy_pieces : nf) : 0;
   uint32_t salt = (uint32_t)blockIdx.x * 0x9E3779B9u;      // varies per workgroup and per attempt
-  bool may_help = a.copy_pieces > 0;                       // until a search finds nothing left to take
+  int dead_w0 = -1;                                        // window start at which a search found nothing left to take
   bool ok = true;
   for (;;) {
-    if (tid == 0) {
+    if (tid < 64) {
+      // the first wave polls, one signal per lane: one memory round trip per 64 signals, however
+      // many the tile waits for (a decode tile waits for all of them)
       int st;
+      int first_missing = 0;
       for (int polls = 0;; ++polls) {
-        int f = f0;
-        while (f <= f1 && __hip_atomic_load(a.signals + f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) ++f;
-        if (f > f1) { st = ARRIVED; break; }
+        first_missing = -1;
+        for (int base = 0; base < nf && first_missing < 0; base += 64) {
+          const bool unset = base + tid < nf &&
+                             __hip_atomic_load(a.signals + f0 + base + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u;
+          const unsigned long long missing = __ballot(unset);
+          if (missing != 0) first_missing = f0 + base + __builtin_ctzll(missing);
+        }
+        if (first_missing < 0) { st = ARRIVED; break; }
         if (wall_clock64() - t0 > a.timeout_ticks) {
-          if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)f;
+          if (tid == 0 && atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)first_missing;
           st = GIVE_UP;
           break;
         }
-        if (may_help && (a.copy_eager || (polls >= 8 && !driver_fully_started(a.started_counter, a.copy_driver_wgs)))) {
+        if (a.copy_pieces > 0 && first_missing != dead_w0 &&
+            (a.copy_eager || (polls >= 8 && !driver_fully_started(a.started_counter, a.copy_driver_wgs)))) {
           st = HELP;
           break;
         }
         __builtin_amdgcn_s_sleep(16);
       }
-      lds[0] = st;
-      lds[1] = 0x7fffffff;
+      if (tid == 0) {
+        lds[0] = st;
+        lds[1] = 0x7fffffff;
+        lds[3] = first_missing;
+      }
     }
     __syncthreads();
     const int st = lds[0];
-    __syncthreads();                    // everyone has read it before thread 0 can write again
+    const int w0 = lds[3];                // first tile of the search window
+    __syncthreads();                    // everyone has read them before the first wave can write again
     if (st == ARRIVED) break;
     if (st == GIVE_UP) { ok = false; break; }
-    // One of the unclaimed pieces among the tiles waited for, picked by a hash that differs per
+    // One of the unclaimed pieces among the tiles of the window, picked by a hash that differs per
     // workgroup and attempt: workgroups that wait for the same tiles then rarely go for the same
     // piece (taking "the first free one" would make them queue up behind each other).  The local
     // chunk's tiles are never copied by anyone, their signals are preset.
+    const int wt = f1 - w0 + 1 < window_tiles ? f1 - w0 + 1 : window_tiles;
+    const int total = wt * a.copy_pieces;
     salt = salt * 1664525u + 1013904223u;
     for (int i = tid; i < total; i += blockDim.x) {
-      const int f = f0 + i / a.copy_pieces;
+      const int f = w0 + i / a.copy_pieces;
       if (f >= a.sig_local_lo && f < a.sig_local_hi) continue;
       if (__hip_atomic_load(a.copy_claims + (size_t)f * a.copy_pieces + i % a.copy_pieces, __ATOMIC_RELAXED,
                             __HIP_MEMORY_SCOPE_AGENT) != a.copy_call_id) {
@@ -519,7 +536,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
     const int key = lds[1];
     if (key != 0x7fffffff) {
       const int i = key & 4095;
-      const int f = f0 + i / a.copy_pieces, piece = i % a.copy_pieces;
+      const int f = w0 + i / a.copy_pieces, piece = i % a.copy_pieces;
       if (tid == 0) lds[2] = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + piece, a.copy_call_id) ? 1 : 0;
       __syncthreads();
       if (lds[2]) {
@@ -530,7 +547,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
         finish_piece(a.copy_counters + f, a.signals + f, a.copy_pieces);
       }
     } else {
-      may_help = false;                 // every piece is in the hands of a workgroup that is running
+      dead_w0 = w0;                     // every piece of this window is in the hands of a workgroup that is running
     }
     __syncthreads();                    // lds[1], lds[2] are rewritten in the next round
   }

@@ -349,6 +349,24 @@ def test_ag_waiting_workgroups_move_the_data_themselves():
         assert e0.elapsed_ms(e1) < 5.0, "the GEMM kernel waited for the delayed copy driver"
 
 
+def test_ag_tile_waiting_for_many_signals():
+    """One 256-row tile that waits for 32 signals of 1 MiB communication tiles in 256 pieces each: more
+    pieces than one search of a waiting workgroup covers, so its search window has to move on as
+    tiles complete.  The copy driver is held back, the waiting workgroups move everything."""
+    w = fi.Workload("int_ag_many", "ag", 256, 256, 65536, 2, a_dist=("int", 2), b_dist=("int", 2), seed=85)
+    rank = 1
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    _, want = gh.oracle_ag(w, chunks, B)
+    for delay in (20_000_000, 0):
+        _say("many signals, delay", delay)
+        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=1, comm_tiles_per_chunk=16,
+                                               copy_workgroups=256, delay_copy_cycles=delay, repeat=2)
+        assert status == (fb.FLUX_OK, 0)
+        gh.assert_bits_equal(Cg, want, "C")
+        gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+        assert signals.cpu().tolist() == [1 if i // 16 == rank else 0 for i in range(32)]
+
+
 def test_ag_link_paced_copy_driver():
     """Emulated slow link (20 GB/s: each 256 KB chunk is released ~13 us after the previous one):
     tiles really wait for their chunk; results and the signal reset are unaffected."""
