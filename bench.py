@@ -59,6 +59,14 @@ def main() -> int:
     compute = torch.cuda.current_stream()
     copy = torch.cuda.Stream()
 
+    def chunk_workspace(op, p):
+        n = fb.flux_chunked_workspace_bytes(op, p)
+        if n == 0:
+            return None
+        ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev)
+        fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+        return ws
+
     class AG:
         def __init__(self, w, rank, **kw):
             self.w, self.rank = w, rank
@@ -83,6 +91,13 @@ def main() -> int:
         def unfused(self, phases):
             fb.flux_gemm_ref_unfused(fb.FLUX_OP_AG, phases, self.p, A_chunks=self.chunks, A_agg=self.A_agg,
                                      B=self.B, Cout=self.C, workspace=self.ws, stream=compute)
+
+        def chunked(self):
+            if not hasattr(self, "ws_chunk"):
+                self.ws_chunk = chunk_workspace(fb.FLUX_OP_AG, self.p)
+            fb.flux_gemm_ref_chunked(fb.FLUX_OP_AG, self.p, A_chunks=self.chunks, A_agg=self.A_agg, B=self.B,
+                                     Cout=self.C, arrival_order=self.arrival, workspace=self.ws_chunk,
+                                     compute_stream=compute, comm_stream=copy)
 
         def alg_bytes(self):     # fused kernel: A_agg + B read once, C written once
             w = self.w
@@ -109,6 +124,13 @@ def main() -> int:
         def unfused(self, phases):
             fb.flux_gemm_ref_unfused(fb.FLUX_OP_RS, phases, self.p, A=self.A, B=self.B, peer_partials=self.peers,
                                      out_slices=self.outs, Cout=self.tmp, workspace=self.ws, stream=compute)
+
+        def chunked(self):
+            if not hasattr(self, "ws_chunk"):
+                self.ws_chunk = chunk_workspace(fb.FLUX_OP_RS, self.p)
+            fb.flux_gemm_ref_chunked(fb.FLUX_OP_RS, self.p, A=self.A, B=self.B, peer_partials=self.peers,
+                                     out_slices=self.outs, Cout=self.tmp, workspace=self.ws_chunk,
+                                     compute_stream=compute, comm_stream=copy)
 
         def alg_bytes(self):
             w = self.w
@@ -144,6 +166,7 @@ def main() -> int:
         t_comm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_COMM), reps, warm)
         t_unf = time_calls(lambda: op.unfused(fb.FLUX_PHASE_GEMM | fb.FLUX_PHASE_COMM), reps, warm)
         t_fus = time_calls(op.fused, reps, warm)
+        t_chk = time_calls(op.chunked, reps, warm)      # medium-grained: R GEMMs, communication beside the next one
         # duration of the fused GEMM kernel alone (events recorded by the library around its
         # launch): what the per-kernel roofline figures use; the per-call times above also carry
         # what is left of launch and cross-stream latencies in a stream that is kept fed
@@ -159,7 +182,8 @@ def main() -> int:
         E = 1.0 - ect_ov / ect_no if ect_no > 0 else None
         w = op.w
         return {"ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
-                "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4),
+                "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4), "ms_chunked": round(t_chk, 4),
+                "overlap_efficiency_chunked": None if ect_no <= 0 else round(1.0 - (t_chk - t_gemm) / ect_no, 4),
                 "kernel_alg_GBs": round(op.alg_bytes() / t_k / 1e6, 1),
                 "kernel_frac_hbm_peak": round(op.alg_bytes() / t_k / 1e6 / HBM_PEAK_GBS, 4),
                 "kernel_tflops": round(w.flops / t_k / 1e9, 1),

@@ -190,6 +190,27 @@ int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_orde
                     int32_t block, int32_t* m_tile, int32_t* n_tile);
 
 /*
+ * Medium-grained baseline: the decomposition the paper compares against (Sec. 2.2): the GEMM is
+ * cut into R GEMMs of M/R rows, one per slice / chunk, and the communication of one part runs on
+ * comm_stream beside the GEMM of the next on compute_stream.
+ *   op = FLUX_OP_RS:  for each slice (ring order after `rank`, own slice last): C rows = A rows . B
+ *                     on compute_stream, then out_slices[slice] = C rows + sum peers on comm_stream.
+ *   op = FLUX_OP_AG:  chunk copies into A_agg on comm_stream in `arrival_order`; the GEMM of a
+ *                     chunk's rows on compute_stream as soon as that chunk has been copied (local
+ *                     chunk first).
+ * Arguments as for flux_gemm_ref_unfused (C: device [M,N] of out_dtype; for RS a temporary).  Each
+ * part is planned like a GEMM of its own shape; if that plan cuts K, `workspace` must hold
+ * flux_chunked_workspace_bytes(op, p) bytes, initialised with flux_init_buffers.  The two streams
+ * must differ; on return compute_stream is ordered after everything the call enqueued.
+ */
+int flux_gemm_ref_chunked(int op, const flux_problem_t* p,
+                          const void* A, const void* const* A_chunks, void* A_agg, const void* B,
+                          const void* const* peer_partials, void* const* out_slices, void* C,
+                          const int32_t* arrival_order, void* workspace, size_t workspace_bytes,
+                          void* compute_stream, void* comm_stream);
+size_t flux_chunked_workspace_bytes(int op, const flux_problem_t* p);
+
+/*
  * How a call would cut K: the first *full_tiles tiles in TileCoord order are computed by one
  * workgroup each, the remaining *split_tiles tiles by *split_k workgroups each (a uniform split has
  * full_tiles = 0; no split has split_k = 1 and split_tiles = all tiles).  The grid has

@@ -29,7 +29,8 @@ EXPORTS = [
     "flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_workspace_bytes",
     "flux_query_status", "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
     "flux_tile_config_info", "flux_default_order", "flux_status_string", "flux_last_hip_error",
-    "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan",
+    "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan", "flux_gemm_ref_chunked",
+    "flux_chunked_workspace_bytes",
 ]
 
 
@@ -67,6 +68,9 @@ def lib():
         L.flux_gemm_rs.argtypes = [pp, vp, vp, pvp, pvp, vp, C.c_size_t, vp]
         L.flux_ag_gemm.argtypes = [pp, pvp, vp, vp, vp, vp, pi32, vp, C.c_size_t, vp, vp]
         L.flux_gemm_ref_unfused.argtypes = [C.c_int, C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, vp, C.c_size_t, vp]
+        L.flux_gemm_ref_chunked.argtypes = [C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, pi32, vp, C.c_size_t, vp, vp]
+        L.flux_chunked_workspace_bytes.argtypes = [C.c_int, pp]
+        L.flux_chunked_workspace_bytes.restype = C.c_size_t
         L.flux_workspace_bytes.argtypes = [C.c_int, pp]
         L.flux_workspace_bytes.restype = C.c_size_t
         L.flux_init_buffers.argtypes = [C.c_int, pp, vp, C.c_size_t, vp, vp]
@@ -82,7 +86,7 @@ def lib():
         for name in ("flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_query_status",
                      "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
                      "flux_tile_config_info", "flux_default_order", "flux_last_hip_error", "flux_version",
-                     "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan"):
+                     "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan", "flux_gemm_ref_chunked"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -156,6 +160,20 @@ def flux_gemm_ref_unfused(op, phases, p, A=None, A_chunks=None, A_agg=None, B=No
         None if peer_partials is None else _ptr_list(peer_partials),
         None if out_slices is None else _ptr_list(out_slices), _ptr(Cout), _ptr(workspace), ws_bytes,
         _stream(stream)), "flux_gemm_ref_unfused")
+
+
+def flux_gemm_ref_chunked(op, p, A=None, A_chunks=None, A_agg=None, B=None, peer_partials=None, out_slices=None,
+                          Cout=None, arrival_order=None, workspace=None, compute_stream=None, comm_stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().flux_gemm_ref_chunked(
+        op, C.byref(p), _ptr(A), None if A_chunks is None else _ptr_list(A_chunks), _ptr(A_agg), _ptr(B),
+        None if peer_partials is None else _ptr_list(peer_partials),
+        None if out_slices is None else _ptr_list(out_slices), _ptr(Cout), _i32_list(arrival_order),
+        _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)), "flux_gemm_ref_chunked")
+
+
+def flux_chunked_workspace_bytes(op, p) -> int:
+    return int(lib().flux_chunked_workspace_bytes(op, C.byref(p)))
 
 
 def flux_query_status(workspace):

@@ -107,14 +107,15 @@ struct ReduceArgs {
   const void* peers[FLUX_MAX_RANKS];
   void* outs[FLUX_MAX_RANKS];
   int32_t M, N, R, rank, S, partial_f32, out_f32;
+  int32_t row0, rows;                 // rows [row0, row0 + rows) of the [M,N] matrices
 };
 
 // Baseline reduce-scatter: out[r] = C + sum of peer partials, 8 columns per thread.
 __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
-  const long long nvec = (long long)a.M * a.N / 8;
+  const long long nvec = (long long)a.rows * a.N / 8;
   const int nv_row = a.N / 8;
   for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (long long)gridDim.x * blockDim.x) {
-    const int gm = (int)(v / nv_row);
+    const int gm = a.row0 + (int)(v / nv_row);
     const int gn = (int)(v % nv_row) * 8;
     const size_t off = (size_t)gm * a.N + gn;
     float x[8];
@@ -463,6 +464,17 @@ static int get_events(hipEvent_t* fork, hipEvent_t* join) {
   return FLUX_OK;
 }
 
+static hipEvent_t g_chunk_events[FLUX_MAX_RANKS] = {nullptr};
+
+static int get_chunk_events(hipEvent_t** events) {
+  std::lock_guard<std::mutex> lk(g_event_mu);
+  for (int i = 0; i < FLUX_MAX_RANKS; ++i)
+    if (g_chunk_events[i] == nullptr) FLUX_HIP(hipEventCreateWithFlags(&g_chunk_events[i], hipEventDisableTiming));
+  *events = g_chunk_events;
+  return FLUX_OK;
+}
+
+
 }  // namespace flux
 
 // ------------------------------------------------------------------------------------------
@@ -742,6 +754,7 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
       r.C = C; r.M = p->M; r.N = p->N; r.R = p->R; r.rank = p->rank; r.S = p->M / p->R;
       r.partial_f32 = p->partial_dtype == FLUX_F32;
       r.out_f32 = p->out_dtype == FLUX_F32;
+      r.row0 = 0; r.rows = p->M;
       const long long nvec = (long long)p->M * p->N / 8;
       const int grid = (int)std::min<long long>((nvec + 255) / 256, 256 * 8);
       hipLaunchKernelGGL(rs_reduce_kernel, dim3(grid), dim3(256), 0, s, r);
@@ -768,6 +781,124 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
   if (do_gemm) {
     a.A = static_cast<const __bf16*>(A_agg);
     st = launch_gemm(pl, EPI_PLAIN, 0, a, s);
+    if (st != FLUX_OK) return st;
+  }
+  return FLUX_OK;
+}
+
+static flux_problem_t chunk_problem(const flux_problem_t* p) {
+  flux_problem_t q = *p;
+  q.M = p->M / p->R; q.R = 1; q.rank = 0;
+  q.flags = FLUX_FLAG_NO_SWIZZLE;
+  return q;
+}
+
+size_t flux_chunked_workspace_bytes(int op, const flux_problem_t* p) {
+  if (validate_problem(op, p) != FLUX_OK) return 0;
+  flux_problem_t q = chunk_problem(p);
+  Plan plq;
+  if (make_plan(FLUX_OP_RS, &q, &plq) != FLUX_OK || plq.split_k <= 1) return 0;
+  return workspace_need(plq);
+}
+
+int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const void* const* A_chunks, void* A_agg,
+                          const void* B, const void* const* peer_partials, void* const* out_slices, void* C,
+                          const int32_t* arrival_order, void* workspace, size_t workspace_bytes,
+                          void* compute_stream, void* comm_stream) {
+  int st = validate_problem(op, p);
+  if (st != FLUX_OK) return st;
+  if (!B || !C || !aligned16(B) || !aligned16(C)) return FLUX_ERR_INVALID_ARG;
+  if (compute_stream == comm_stream) return FLUX_ERR_INVALID_ARG;
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream), xs = static_cast<hipStream_t>(comm_stream);
+  const int R = p->R, S = p->M / p->R;
+  const size_t out_size = p->out_dtype == FLUX_F32 ? 4 : 2;
+
+  // one rank-less GEMM of S rows per chunk, planned like any other GEMM of that shape
+  flux_problem_t q = chunk_problem(p);
+  Plan plq;
+  st = make_plan(FLUX_OP_RS, &q, &plq);
+  if (st != FLUX_OK) return st;
+  if (plq.split_k > 1 && (workspace == nullptr || workspace_bytes < workspace_need(plq) || !aligned16(workspace)))
+    return FLUX_ERR_WORKSPACE;
+  GemmArgs g;
+  fill_common(&g, &q, plq, plq.split_k > 1 ? workspace : nullptr);
+  g.B = static_cast<const __bf16*>(B);
+  build_tile_map(FLUX_OP_RS, &q, plq, nullptr, &g.tm);
+  g.tm.n_xcd = plq.n_xcd;
+  g.tm.band_h = 1;
+
+  hipEvent_t* ev;
+  st = get_chunk_events(&ev);
+  if (st != FLUX_OK) return st;
+  hipEvent_t ev_fork, ev_join;
+  st = get_events(&ev_fork, &ev_join);
+  if (st != FLUX_OK) return st;
+
+  if (op == FLUX_OP_RS) {
+    if (!A || !aligned16(A) || !peer_partials || !out_slices) return FLUX_ERR_INVALID_ARG;
+    ReduceArgs r;
+    std::memset(&r, 0, sizeof(r));
+    for (int j = 0; j < R; ++j) {
+      if (!out_slices[j] || !aligned16(out_slices[j])) return FLUX_ERR_INVALID_ARG;
+      if (j != p->rank && (!peer_partials[j] || !aligned16(peer_partials[j]))) return FLUX_ERR_INVALID_ARG;
+      r.peers[j] = peer_partials[j];
+      r.outs[j] = out_slices[j];
+    }
+    r.C = C; r.M = p->M; r.N = p->N; r.R = R; r.rank = p->rank; r.S = S;
+    r.partial_f32 = p->partial_dtype == FLUX_F32;
+    r.out_f32 = p->out_dtype == FLUX_F32;
+    const long long nvec = (long long)S * p->N / 8;
+    const int grid = (int)std::max<long long>(1, std::min<long long>((nvec + 255) / 256, 256 * 8));
+    // slices in the order of the fused kernel: the ring after the local rank, the own slice last
+    for (int d = 1; d <= R; ++d) {
+      const int slice = (p->rank + d) % R;
+      g.A = static_cast<const __bf16*>(A) + (size_t)slice * S * p->K;
+      g.C = static_cast<unsigned char*>(C) + (size_t)slice * S * p->N * out_size;
+      st = launch_gemm(plq, EPI_PLAIN, 0, g, cs);
+      if (st != FLUX_OK) return st;
+      FLUX_HIP(hipEventRecord(ev[slice], cs));
+      FLUX_HIP(hipStreamWaitEvent(xs, ev[slice], 0));
+      r.row0 = slice * S; r.rows = S;
+      hipLaunchKernelGGL(rs_reduce_kernel, dim3(grid), dim3(256), 0, xs, r);
+      FLUX_HIP(hipGetLastError());
+    }
+    FLUX_HIP(hipEventRecord(ev_join, xs));
+    FLUX_HIP(hipStreamWaitEvent(cs, ev_join, 0));
+    return FLUX_OK;
+  }
+
+  // AllGather: chunk copies on comm_stream in arrival order, each chunk's GEMM once its copy is done
+  if (!A_chunks || !A_agg || !aligned16(A_agg)) return FLUX_ERR_INVALID_ARG;
+  const size_t chunk_elems = (size_t)S * p->K;
+  if (chunk_elems % 8 != 0) return FLUX_ERR_SHAPE;
+  for (int r = 0; r < R; ++r)
+    if (!A_chunks[r] || !aligned16(A_chunks[r])) return FLUX_ERR_INVALID_ARG;
+  int order[FLUX_MAX_RANKS];
+  st = check_arrival(p, arrival_order, order);
+  if (st != FLUX_OK) return st;
+  Plan plc;                                   // only its copy parameters are used
+  st = make_plan(FLUX_OP_AG, p, &plc);
+  if (st != FLUX_OK) return st;
+  const __bf16* agg = static_cast<const __bf16*>(A_agg);
+  if (A_chunks[p->rank] != static_cast<const void*>(agg + (size_t)p->rank * chunk_elems)) {
+    int self = p->rank;
+    st = launch_copy(p, plc, A_chunks, A_agg, &self, 1, false, nullptr, nullptr, 0, cs);
+    if (st != FLUX_OK) return st;
+  }
+  FLUX_HIP(hipEventRecord(ev_fork, cs));
+  FLUX_HIP(hipStreamWaitEvent(xs, ev_fork, 0));
+  for (int i = 0; i < R - 1; ++i) {
+    const int c = order[i];
+    st = launch_copy(p, plc, A_chunks, A_agg, &c, 1, false, nullptr, nullptr, 0, xs);
+    if (st != FLUX_OK) return st;
+    FLUX_HIP(hipEventRecord(ev[c], xs));
+  }
+  for (int i = -1; i < R - 1; ++i) {
+    const int c = i < 0 ? p->rank : order[i];
+    if (i >= 0) FLUX_HIP(hipStreamWaitEvent(cs, ev[c], 0));
+    g.A = agg + (size_t)c * chunk_elems;
+    g.C = static_cast<unsigned char*>(C) + (size_t)c * S * p->N * out_size;
+    st = launch_gemm(plq, EPI_PLAIN, 0, g, cs);
     if (st != FLUX_OK) return st;
   }
   return FLUX_OK;

@@ -471,3 +471,60 @@ def test_unfused_baseline_matches_oracle():
     torch.cuda.synchronize()
     C64, _ = gh.oracle_ag(wa, chunks, B)
     gh.assert_close(Cout, C64, wa.out_dtype)
+
+
+def _chunk_ws(op, p):
+    n = fb.flux_chunked_workspace_bytes(op, p)
+    if n == 0:
+        return None
+    ws = torch.full(((n + 3) // 4,), -1, dtype=torch.int32, device=gh.DEV)
+    fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+    return ws
+
+
+@pytest.mark.parametrize("R,rank", [(8, 3), (4, 0), (1, 0)])
+def test_chunked_baseline_matches_oracle(R, rank):
+    """The medium-grained decomposition (one GEMM per slice / chunk, communication of one part beside
+    the GEMM of the next on a second stream) gives the same results as the other two paths: on
+    integer-valued inputs bit for bit, on random inputs within the tolerance."""
+    comm = torch.cuda.Stream()
+    compute = torch.cuda.current_stream()
+    for ints in (True, False):
+        kw = dict(a_dist=("int", 2), b_dist=("int", 2), peer_dist=("int", 8)) if ints else {}
+        w = fi.Workload("rs_chunked", "rs", 128 * R, 384, 320, R, seed=86, **kw)
+        _say("chunked rs", R, rank, "ints" if ints else "random")
+        A, B, peers = fi.make_rs_inputs(w, rank)
+        p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype)
+        dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+        dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
+        ws = _chunk_ws(fb.FLUX_OP_RS, p)
+        for rep in range(2):
+            outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
+            tmp = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+            fb.flux_gemm_ref_chunked(fb.FLUX_OP_RS, p, A=dA, B=dB, peer_partials=dpeers, out_slices=outs, Cout=tmp,
+                                     workspace=ws, compute_stream=compute, comm_stream=comm)
+            torch.cuda.synchronize()
+            s64, sbits = gh.oracle_rs(w, rank, A, B, peers)
+            for r in range(w.R):
+                if ints:       # integers below 2^8 in the GEMM result: the extra bf16 rounding of the temporary is exact
+                    gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+                else:
+                    gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+        wa = fi.Workload("ag_chunked", "ag", 128 * R, 384, 320, R, seed=87, **kw)
+        _say("chunked ag", R, rank)
+        chunks, Ba, arrival = fi.make_ag_inputs(wa, rank)
+        pa = fb.problem(wa.M, wa.N, wa.K, wa.R, rank, "bf16", wa.out_dtype)
+        dchunks = [c.to(gh.DEV) for c in chunks]
+        C64, Cbits = gh.oracle_ag(wa, chunks, Ba)
+        ws = _chunk_ws(fb.FLUX_OP_AG, pa)
+        for rep in range(2):
+            A_agg = torch.full((wa.M, wa.K), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+            Cout = torch.full((wa.M, wa.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+            fb.flux_gemm_ref_chunked(fb.FLUX_OP_AG, pa, A_chunks=dchunks, A_agg=A_agg, B=Ba.to(gh.DEV), Cout=Cout,
+                                     arrival_order=arrival, workspace=ws, compute_stream=compute, comm_stream=comm)
+            torch.cuda.synchronize()
+            if ints:
+                gh.assert_bits_equal(Cout, Cbits, "C")
+            else:
+                gh.assert_close(Cout, C64, wa.out_dtype)
+            gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
