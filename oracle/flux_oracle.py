@@ -276,6 +276,31 @@ def gemm_rs(A, B, peers, R: int, rank: int, partial_dtype: str, out_dtype: str,
     return slices64, [round_to(s, out_dtype) for s in slices64]
 
 
+def gemm_scatter(A, B, R: int, out_dtype: str, ab_dtype: str = BF16):
+    """GEMM with the Write branch of Alg. 1 (Sec. 3.1, 4.2: the AlltoAll flavour of ReduceScatter):
+    the tile is not reduced, each row of this rank's partial product A.B goes to the slice of the
+    rank that owns the row.  Returns (slices64, slices_rounded): R arrays [M/R, N]."""
+    full = gemm_f64(A, B, ab_dtype)
+    S = slice_rows(full.shape[0], R)
+    slices64 = [full[r * S:(r + 1) * S, :] for r in range(R)]
+    return slices64, [round_to(s, out_dtype) for s in slices64]
+
+
+def reduce_slice(staged, staged_dtype: str, out_dtype: str):
+    """The local reduction that follows the AlltoAll (Sec. 3.1): `staged` holds, for one slice, the
+    R partial results [M/R, N] the R ranks wrote for it (in `staged_dtype`); the slice is their sum,
+    rounded once.  Returns (sum64, rounded)."""
+    if len(staged) == 0:
+        raise ValueError("need at least one partial")
+    total = to_f64(staged[0], staged_dtype).copy()
+    for s in staged[1:]:
+        t = to_f64(s, staged_dtype)
+        if t.shape != total.shape:
+            raise ValueError("partials differ in shape")
+        total = total + t
+    return total, round_to(total, out_dtype)
+
+
 def gemm_rs_rows(A, B, peers, R: int, rank: int, partial_dtype: str, rows, ab_dtype: str = BF16):
     """The same definition as `gemm_rs`, evaluated for a subset of global rows only (used where
     the full problem is too large to finish in seconds).  Returns a list of

@@ -205,3 +205,40 @@ def test_row_subset_variants_agree_with_full_definitions():
     chunks = [bf16(A[r * 4:(r + 1) * 4]) for r in range(R)]
     C64, _ = fo.ag_gemm(chunks, bf16(B), "f32")
     assert np.array_equal(fo.ag_gemm_rows(chunks, bf16(B), rows), C64[rows])
+
+
+def test_alltoall_flavour_equals_reduce_scatter():
+    """Write branch + local reduction (Sec. 3.1: ReduceScatter = AlltoAll + reduction): every rank
+    scatters its partial product by owner, every owner sums the R partials staged for its slice.
+    On integer inputs that is exactly the unsharded GEMM over the concatenated K, slice by slice,
+    and exactly what the Reduce branch gives; a dropped rank or a wrong row range changes it."""
+    rng = np.random.default_rng(21)
+    M, N, Kr, R = 8, 6, 5, 4
+    S = M // R
+    As = [rand_int(rng, (M, Kr), 2) for _ in range(R)]
+    Bs = [rand_int(rng, (Kr, N), 2) for _ in range(R)]
+    unsharded = np.concatenate(As, axis=1).astype(np.int64) @ np.concatenate(Bs, axis=0).astype(np.int64)
+    scattered = [fo.gemm_scatter(bf16(a), bf16(b), R, "f32")[1] for a, b in zip(As, Bs)]   # [rank][slice]
+    for j in range(R):      # brute force: slice r of rank j's scatter is rows r*S.. of its own product
+        own = As[j].astype(np.int64) @ Bs[j].astype(np.int64)
+        for r in range(R):
+            assert np.array_equal(fo.to_f64(scattered[j][r], "f32"), own[r * S:(r + 1) * S].astype(np.float64))
+    for r in range(R):
+        total, rounded = fo.reduce_slice([scattered[j][r] for j in range(R)], "f32", "f32")
+        assert np.array_equal(total, unsharded[r * S:(r + 1) * S].astype(np.float64))
+        assert np.array_equal(fo.to_f64(rounded, "f32"), total)
+    # same as the Reduce branch seen from any rank
+    partials = [fo.partial_of(bf16(a), bf16(b), "f32") for a, b in zip(As, Bs)]
+    s64, _ = fo.gemm_rs(bf16(As[1]), bf16(Bs[1]), [None if j == 1 else partials[j] for j in range(R)], R, 1, "f32", "f32")
+    for r in range(R):
+        assert np.array_equal(s64[r], fo.reduce_slice([scattered[j][r] for j in range(R)], "f32", "f32")[0])
+    with pytest.raises(ValueError):
+        fo.reduce_slice([scattered[0][0], scattered[0][0][:1]], "f32", "f32")
+
+
+def test_reduce_slice_rounds_once():
+    # three bf16 values whose exact sum needs more than 8 significand bits: rounded once, to even
+    vals = [bf16(np.array([[256.0]])), bf16(np.array([[1.0]])), bf16(np.array([[2.0]]))]   # 259 -> 260 (tie 258/260? no: 259 is between 258 and 260)
+    total, rounded = fo.reduce_slice(vals, "bf16", "bf16")
+    assert total[0, 0] == 259.0
+    assert fo.to_f64(rounded, "bf16")[0, 0] == 260.0      # 259 = 258 + 1 is a tie of (258, 260): even significand wins
