@@ -132,6 +132,19 @@ def main() -> int:
                                      out_slices=self.outs, Cout=self.tmp, workspace=self.ws_chunk,
                                      compute_stream=compute, comm_stream=copy)
 
+        def alltoall_flavour(self):
+            # Write branch + local reduction: what ONE rank of a real group does (its GEMM scattered
+            # by owner, then the sum of the R partials staged for its own slice)
+            if not hasattr(self, "p_wo"):
+                w = self.w
+                self.p_wo = fb.problem(w.M, w.N, w.K, w.R, self.rank, w.partial_dtype, w.out_dtype,
+                                       flags=fb.FLUX_FLAG_RS_WRITE_ONLY)
+                lo, hi = self.rank * w.S, (self.rank + 1) * w.S
+                self.staged = [self.outs[self.rank] if j == self.rank else self.peers[j][lo:hi] for j in range(w.R)]
+                self.own = torch.zeros_like(self.outs[self.rank])
+            fb.flux_gemm_rs(self.p_wo, self.A, self.B, None, self.outs, self.ws, compute)
+            fb.flux_rs_reduce_slice(self.p_wo, self.staged, self.own, compute)
+
         def alg_bytes(self):
             w = self.w
             ps = 2 if w.partial_dtype == "bf16" else 4
@@ -178,10 +191,12 @@ def main() -> int:
             torch.cuda.synchronize()
             ks.append(k0.elapsed_ms(k1))
         t_k = statistics.median(ks)
+        t_a2a = time_calls(op.alltoall_flavour, reps, warm) if hasattr(op, "alltoall_flavour") else None
         ect_no, ect_ov = t_unf - t_gemm, t_fus - t_gemm
         E = 1.0 - ect_ov / ect_no if ect_no > 0 else None
         w = op.w
-        return {"ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
+        more = {} if t_a2a is None else {"ms_write_only_plus_slice_reduce": round(t_a2a, 4)}
+        return {**more, "ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
                 "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4), "ms_chunked": round(t_chk, 4),
                 "overlap_efficiency_chunked": None if ect_no <= 0 else round(1.0 - (t_chk - t_gemm) / ect_no, 4),
                 "kernel_alg_GBs": round(op.alg_bytes() / t_k / 1e6, 1),

@@ -72,6 +72,10 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
 #define FLUX_FLAG_NO_TAIL_SPLIT 0x10u /* with split_k = 0: do not cut the tiles of a partly filled last
                                         round of the grid along K (see flux_split_plan) */
 
+#define FLUX_FLAG_RS_WRITE_ONLY 0x20u /* flux_gemm_rs: Write branch of Alg. 1: no peers are read, each row of
+                                        A.B is converted and stored into its owner's slice (the AlltoAll
+                                        flavour of Sec. 3.1; flux_rs_reduce_slice is the reduction after it) */
+
 /* flux_gemm_ref_unfused phases */
 #define FLUX_PHASE_GEMM 0x1
 #define FLUX_PHASE_COMM 0x2
@@ -99,7 +103,7 @@ typedef struct flux_problem {
 /*
  * GEMM-ReduceScatter, fused (Alg. 1 with the Reduce branch).
  *   A, B            device, bf16, [M,K] and [K,N].
- *   peer_partials   host array [R] of device pointers to [M,N] matrices of partial_dtype;
+ *   peer_partials   (NULL allowed with FLUX_FLAG_RS_WRITE_ONLY) host array [R] of device pointers to [M,N] matrices of partial_dtype;
  *                   entry [rank] is ignored (may be NULL).
  *   out_slices      host array [R] of device pointers to [M/R,N] matrices of out_dtype, all
  *                   written (every element exactly once).
@@ -188,6 +192,14 @@ int flux_query_status(const void* workspace, int32_t* code, int32_t* detail);
  */
 int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_order,
                     int32_t block, int32_t* m_tile, int32_t* n_tile);
+
+/*
+ * The local reduction that follows the AlltoAll when flux_gemm_rs runs with FLUX_FLAG_RS_WRITE_ONLY
+ * (Sec. 3.1: ReduceScatter = AlltoAll + reduction; Sec. 4.2): `staged` is a host array [R] of device
+ * pointers, staged[j] = the [M/R,N] partial (partial_dtype) that rank j wrote for THIS rank's slice;
+ * out [M/R,N] (out_dtype) = their sum in rank order, fp32, converted once.  One kernel on `stream`.
+ */
+int flux_rs_reduce_slice(const flux_problem_t* p, const void* const* staged, void* out, void* stream);
 
 /*
  * Medium-grained baseline: the decomposition the paper compares against (Sec. 2.2): the GEMM is

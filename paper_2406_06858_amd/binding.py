@@ -22,6 +22,7 @@ FLUX_BF16, FLUX_F32 = 0, 1
 FLUX_OP_RS, FLUX_OP_AG = 0, 1
 FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY = 0x1, 0x2, 0x4
 FLUX_FLAG_NO_TAIL_SPLIT = 0x10
+FLUX_FLAG_RS_WRITE_ONLY = 0x20
 FLUX_PHASE_GEMM, FLUX_PHASE_COMM = 0x1, 0x2
 FLUX_MAX_RANKS = 16
 
@@ -30,7 +31,7 @@ EXPORTS = [
     "flux_query_status", "flux_tile_coord", "flux_tile_shape", "flux_tile_config_count",
     "flux_tile_config_info", "flux_default_order", "flux_status_string", "flux_last_hip_error",
     "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan", "flux_gemm_ref_chunked",
-    "flux_chunked_workspace_bytes",
+    "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
 ]
 
 
@@ -70,6 +71,8 @@ def lib():
         L.flux_gemm_ref_unfused.argtypes = [C.c_int, C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, vp, C.c_size_t, vp]
         L.flux_gemm_ref_chunked.argtypes = [C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, pi32, vp, C.c_size_t, vp, vp]
         L.flux_chunked_workspace_bytes.argtypes = [C.c_int, pp]
+        L.flux_rs_reduce_slice.argtypes = [pp, pvp, vp, vp]
+        L.flux_rs_reduce_slice.restype = C.c_int
         L.flux_chunked_workspace_bytes.restype = C.c_size_t
         L.flux_workspace_bytes.argtypes = [C.c_int, pp]
         L.flux_workspace_bytes.restype = C.c_size_t
@@ -141,7 +144,8 @@ def flux_init_buffers(op, p, workspace=None, signals=None, stream=None):
 
 def flux_gemm_rs(p, A, B, peer_partials, out_slices, workspace=None, stream=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().flux_gemm_rs(C.byref(p), _ptr(A), _ptr(B), _ptr_list(peer_partials), _ptr_list(out_slices),
+    _check(lib().flux_gemm_rs(C.byref(p), _ptr(A), _ptr(B),
+                              None if peer_partials is None else _ptr_list(peer_partials), _ptr_list(out_slices),
                               _ptr(workspace), ws_bytes, _stream(stream)), "flux_gemm_rs")
 
 
@@ -170,6 +174,10 @@ def flux_gemm_ref_chunked(op, p, A=None, A_chunks=None, A_agg=None, B=None, peer
         None if peer_partials is None else _ptr_list(peer_partials),
         None if out_slices is None else _ptr_list(out_slices), _ptr(Cout), _i32_list(arrival_order),
         _ptr(workspace), ws_bytes, _stream(compute_stream), _stream(comm_stream)), "flux_gemm_ref_chunked")
+
+
+def flux_rs_reduce_slice(p, staged, out, stream=None):
+    _check(lib().flux_rs_reduce_slice(C.byref(p), _ptr_list(staged), _ptr(out), _stream(stream)), "flux_rs_reduce_slice")
 
 
 def flux_chunked_workspace_bytes(op, p) -> int:

@@ -107,6 +107,7 @@ struct ReduceArgs {
   const void* peers[FLUX_MAX_RANKS];
   void* outs[FLUX_MAX_RANKS];
   int32_t M, N, R, rank, S, partial_f32, out_f32;
+  int32_t c_f32;                      // dtype of C
   int32_t row0, rows;                 // rows [row0, row0 + rows) of the [M,N] matrices
 };
 
@@ -119,7 +120,7 @@ __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
     const int gn = (int)(v % nv_row) * 8;
     const size_t off = (size_t)gm * a.N + gn;
     float x[8];
-    if (a.out_f32) {
+    if (a.c_f32) {
       const float* p = static_cast<const float*>(a.C) + off;
       const uint4 u = ld_stream16(p), w = ld_stream16(p + 4);
       x[0] = __uint_as_float(u.x); x[1] = __uint_as_float(u.y); x[2] = __uint_as_float(u.z); x[3] = __uint_as_float(u.w);
@@ -602,10 +603,11 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   Plan pl;
   int st = make_plan(FLUX_OP_RS, p, &pl);
   if (st != FLUX_OK) return st;
-  if (!A || !B || !peer_partials || !out_slices || !aligned16(A) || !aligned16(B)) return FLUX_ERR_INVALID_ARG;
+  const bool write_only = p->flags & FLUX_FLAG_RS_WRITE_ONLY;
+  if (!A || !B || (!peer_partials && !write_only) || !out_slices || !aligned16(A) || !aligned16(B)) return FLUX_ERR_INVALID_ARG;
   for (int r = 0; r < p->R; ++r) {
     if (!out_slices[r] || !aligned16(out_slices[r])) return FLUX_ERR_INVALID_ARG;
-    if (r != p->rank && (!peer_partials[r] || !aligned16(peer_partials[r]))) return FLUX_ERR_INVALID_ARG;
+    if (!write_only && r != p->rank && (!peer_partials[r] || !aligned16(peer_partials[r]))) return FLUX_ERR_INVALID_ARG;
   }
   st = check_workspace(pl, FLUX_OP_RS, workspace, workspace_bytes);
   if (st != FLUX_OK) return st;
@@ -615,9 +617,10 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   a.A = static_cast<const __bf16*>(A);
   a.B = static_cast<const __bf16*>(B);
   // the kernel wants the R-1 peers packed, ascending rank
+  a.write_only = write_only;
   for (int r = 0, j = 0; r < p->R; ++r) {
     a.outs[r] = out_slices[r];
-    if (r != p->rank) a.peers[j++] = peer_partials[r];
+    if (!write_only && r != p->rank) a.peers[j++] = peer_partials[r];
   }
   build_tile_map(FLUX_OP_RS, p, pl, nullptr, &a.tm);
   return launch_gemm(pl, EPI_RS, 0, a, s);
@@ -754,6 +757,7 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
       r.C = C; r.M = p->M; r.N = p->N; r.R = p->R; r.rank = p->rank; r.S = p->M / p->R;
       r.partial_f32 = p->partial_dtype == FLUX_F32;
       r.out_f32 = p->out_dtype == FLUX_F32;
+      r.c_f32 = r.out_f32;
       r.row0 = 0; r.rows = p->M;
       const long long nvec = (long long)p->M * p->N / 8;
       const int grid = (int)std::min<long long>((nvec + 255) / 256, 256 * 8);
@@ -783,6 +787,32 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
     st = launch_gemm(pl, EPI_PLAIN, 0, a, s);
     if (st != FLUX_OK) return st;
   }
+  return FLUX_OK;
+}
+
+int flux_rs_reduce_slice(const flux_problem_t* p, const void* const* staged, void* out, void* stream) {
+  int st = validate_problem(FLUX_OP_RS, p);
+  if (st != FLUX_OK) return st;
+  if (!staged || !out || !aligned16(out)) return FLUX_ERR_INVALID_ARG;
+  ReduceArgs r;
+  std::memset(&r, 0, sizeof(r));
+  for (int j = 0; j < p->R; ++j) {
+    if (!staged[j] || !aligned16(staged[j])) return FLUX_ERR_INVALID_ARG;
+    r.peers[j] = staged[j];
+  }
+  // one slice of S rows: the first partial plays the part of C, the others are added in rank order
+  const int S = p->M / p->R;
+  r.C = staged[0];
+  r.outs[0] = out;
+  r.M = S; r.N = p->N; r.R = p->R; r.rank = 0; r.S = S;
+  r.partial_f32 = p->partial_dtype == FLUX_F32;
+  r.c_f32 = r.partial_f32;
+  r.out_f32 = p->out_dtype == FLUX_F32;
+  r.row0 = 0; r.rows = S;
+  const long long nvec = (long long)S * p->N / 8;
+  const int grid = (int)std::max<long long>(1, std::min<long long>((nvec + 255) / 256, 256 * 8));
+  hipLaunchKernelGGL(rs_reduce_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), r);
+  FLUX_HIP(hipGetLastError());
   return FLUX_OK;
 }
 
@@ -847,6 +877,7 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
     r.C = C; r.M = p->M; r.N = p->N; r.R = R; r.rank = p->rank; r.S = S;
     r.partial_f32 = p->partial_dtype == FLUX_F32;
     r.out_f32 = p->out_dtype == FLUX_F32;
+    r.c_f32 = r.out_f32;
     const long long nvec = (long long)S * p->N / 8;
     const int grid = (int)std::max<long long>(1, std::min<long long>((nvec + 255) / 256, 256 * 8));
     // slices in the order of the fused kernel: the ring after the local rank, the own slice last

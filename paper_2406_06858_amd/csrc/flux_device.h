@@ -74,6 +74,7 @@ struct GemmArgs {
   const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
   void* outs[FLUX_MAX_RANKS];
   int32_t R, rank, S;        // S = M / R
+  int32_t write_only;        // reduce-scatter epilogue without the reduction (Write branch of Alg. 1)
   int32_t partial_f32, out_f32;
   // all-gather prologue
   uint32_t* signals;
@@ -643,7 +644,7 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
   // would no longer be kept in registers.  Up to 8 ranks, 7 peer loads per piece are issued, else 15:
   // loads from absent peers return zeros but still cost an issue slot and four registers each.)
   constexpr int NP_ALL = FLUX_MAX_RANKS - 1, NP_8 = 7;
-  if (EPI != EPI_RS) {
+  if (EPI != EPI_RS || a.write_only) {
     epilogue_all<C, EPI, EDGE, false, 2, 0>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
   } else if (a.R <= NP_8 + 1) {
     if (a.partial_f32) epilogue_all<C, EPI, EDGE, true, 1, NP_8>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);

@@ -528,3 +528,44 @@ def test_chunked_baseline_matches_oracle(R, rank):
             else:
                 gh.assert_close(Cout, C64, wa.out_dtype)
             gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 3, 4, 7])
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_rs_write_only_then_slice_reduce(cfg, dt):
+    """The AlltoAll flavour (Write branch of Alg. 1 + local reduction): every virtual rank scatters its
+    own partial product by owner; one owner then sums the R partials staged for its slice.  Integer
+    inputs: bit for bit against the oracle at both steps; random inputs: within the tolerance, and
+    the reduction bit for bit when both sides start from the same staged values."""
+    R, owner = 4, 2
+    for ints in (True, False):
+        kw = dict(a_dist=("int", 2), b_dist=("int", 2)) if ints else {}
+        w = fi.Workload("rs_wo", "rs", 512, 384, 256, R, partial_dtype=dt, out_dtype=dt, seed=88, **kw)
+        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+        staged_gpu, staged_ref = [], []
+        for j in range(R):
+            _say("write-only cfg", cfg, dt, "ints" if ints else "random", "rank", j)
+            A, B, _ = fi.make_rs_inputs(w, j)
+            p = fb.problem(w.M, w.N, w.K, R, j, dt, dt, tile_config=cfg, flags=fb.FLUX_FLAG_RS_WRITE_ONLY)
+            outs = [torch.full((w.S, w.N), float("nan"), dtype=tdt, device=gh.DEV) for _ in range(R)]
+            ws = gh.workspace_for(fb.FLUX_OP_RS, p)
+            if ws is not None:
+                fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+            fb.flux_gemm_rs(p, A.to(gh.DEV), B.to(gh.DEV), None, outs, ws)
+            torch.cuda.synchronize()
+            s64, sbits = fo.gemm_scatter(fi.to_numpy(A), fi.to_numpy(B), R, dt)
+            for r in range(R):
+                if ints:
+                    gh.assert_bits_equal(outs[r], sbits[r], f"rank {j} slice {r}")
+                else:
+                    gh.assert_close(outs[r], s64[r], dt, f"rank {j} slice {r}")
+            staged_gpu.append(outs[owner])
+            staged_ref.append(sbits[owner])
+        p = fb.problem(w.M, w.N, w.K, R, owner, dt, dt)
+        out = torch.full((w.S, w.N), float("nan"), dtype=tdt, device=gh.DEV)
+        fb.flux_rs_reduce_slice(p, staged_gpu, out)
+        torch.cuda.synchronize()
+        total, rounded = fo.reduce_slice([fi.to_numpy(t) for t in staged_gpu], dt, dt)
+        gh.assert_close(out, total, dt, "slice reduce")
+        if ints:
+            gh.assert_bits_equal(out, fo.reduce_slice(staged_ref, dt, dt)[1], "slice reduce, integers")
