@@ -83,6 +83,9 @@ def main() -> int:
             self.signals = torch.zeros(w.R * max(1, kw.get("comm_tiles_per_chunk", 0)), dtype=torch.int32, device=dev)
             self.ws = torch.zeros(fb.flux_workspace_bytes(fb.FLUX_OP_AG, self.p) // 4 + 1, dtype=torch.int32, device=dev)
             fb.flux_init_buffers(fb.FLUX_OP_AG, self.p, self.ws, self.signals)
+            # steady state: A_agg holds the previous step's gathered activations, not zeros (a GEMM
+            # over zeros draws less power and runs at a higher clock: a flattering baseline)
+            self.unfused(fb.FLUX_PHASE_COMM)
 
         def fused(self):
             fb.flux_ag_gemm(self.p, self.chunks, self.A_agg, self.B, self.C, self.signals, self.arrival,
@@ -310,6 +313,14 @@ def main() -> int:
             extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50)
             del op
             torch.cuda.empty_cache()
+        # Second workload: the paper's op-level sweep (Sec. 5.1), GPT-3-175B MLP shapes at TP=8
+        sweep = {}
+        for name in ("op_ag_m512", "op_rs_m512", "op_ag_m2048", "op_rs_m2048", "op_ag_m8192", "op_rs_m8192"):
+            op = AG(W[name], 2) if W[name].op == "ag" else RS(W[name], 2)
+            sweep[name] = overlap_block(op, reps=10, warm=3)
+            del op
+            torch.cuda.empty_cache()
+        extra["op_level_sweep"] = sweep
         # Secondary, labelled: the copy driver paced to an inbound link of 7 x 153 GB/s (what one
         # rank of an 8-GPU xGMI mesh receives), so that communication is a paper-like fraction
         # of the GEMM time; communication tile = chunk / ctpc (Sec. 4.3), swizzle on and off.

@@ -90,8 +90,10 @@ typedef struct flux_problem {
   uint32_t flags;           /* FLUX_FLAG_*                                                        */
   int32_t comm_tiles_per_chunk; /* AG: signals per chunk (Sec. 4.3 "communication tile size");
                                    0 or 1 = one per chunk; must divide M/R                        */
-  int32_t copy_workgroups;  /* AG copy kernel grid size; 0 = library picks.  The fused call uses at
-                               most 256: a communication tile moves in one piece per workgroup.    */
+  int32_t copy_workgroups;  /* AG copy kernel grid size; 0 = library picks (for the fused call: no
+                               copy kernel at all unless link_gbps is set, see flux_ag_gemm).  The
+                               fused call uses at most 256: a communication tile moves in one
+                               piece per workgroup.                                                */
   int32_t link_gbps;        /* AG copy kernel: 0 = copy at memory speed; else emulate an inbound
                                link of that many GB/s: communication tile i is not signalled
                                before (i+1)*tile_bytes/link_gbps after the driver started       */
@@ -115,18 +117,26 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * AllGather-GEMM, fused (Alg. 2 kernel + Alg. 3 host driver, pull form).
- * The copy driver is a kernel on copy_stream that moves the remote chunks communication tile by
- * communication tile in `arrival_order` and sets each tile's signal.  A GEMM workgroup that has to
- * wait for a tile occupies its compute unit anyway, so instead of only spinning it moves pieces of
- * that tile which no one has started on (pieces are claimed, so nothing is moved twice).  This
- * also means the call completes when the GEMM grid takes every compute unit before the driver got
- * one.  Exceptions: a paced driver (link_gbps > 0) stands for a link, so workgroups only step in
- * while part of the driver has not started; with FLUX_FLAG_COPY_MEMCPY the driver is
- * hipMemcpyAsync plus a stream write per tile and the GEMM only waits.  If the remote chunks add
- * up to 8 MiB or less (decode), link_gbps is 0 and copy_workgroups is 0, no driver is launched
- * and copy_stream stays unused: forking and joining a second stream would take longer than the
- * transfer, so the waiting workgroups move all of it, each the tiles it is waiting for.
+ * AllGather-GEMM, fused (Alg. 2 kernel + the data transfer of Alg. 3, pull form).
+ * Who moves the remote chunks (communication tile by communication tile in `arrival_order`,
+ * setting each tile's signal when it is complete) depends on the problem:
+ *   - link_gbps == 0, copy_workgroups == 0, no FLUX_FLAG_COPY_MEMCPY (the default): no copy kernel
+ *     is launched and copy_stream stays unused.  The first workgroups of the GEMM grid (as many as
+ *     run at once) share the pieces of all tiles out among themselves by index and move them
+ *     before they look at their own signals.  A GEMM workgroup takes the whole register file of
+ *     its compute unit, so a separate driver cannot run beside it: it would hold units the grid
+ *     wants, and a waiting workgroup holds its unit anyway.
+ *   - copy_workgroups > 0 or link_gbps > 0: the driver of Alg. 3 is a kernel on copy_stream.  A
+ *     GEMM workgroup that has to wait for a tile moves pieces of that tile which no one has started
+ *     on (pieces are claimed, so nothing is moved twice); the call therefore also completes when
+ *     the GEMM grid takes every compute unit before the driver got one.  A paced driver
+ *     (link_gbps > 0) stands for a link, so workgroups only step in while part of the driver has
+ *     not started.
+ *   - FLUX_FLAG_COPY_MEMCPY: the driver is hipMemcpyAsync plus a stream write per tile and the
+ *     GEMM only waits.
+ * In the first two cases a piece is claimed before it is moved, whoever moves it, and a workgroup
+ * that waits takes over unclaimed pieces of the tiles it waits for, so a mover that has not been
+ * given a compute unit yet cannot stall the grid.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.

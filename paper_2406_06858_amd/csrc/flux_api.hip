@@ -13,13 +13,12 @@ namespace flux {
 
 // (not const: a const table of host function pointers would also be emitted for the device)
 CfgInfo g_cfgs[NUM_CFGS] = {
-    {256, 256, 64, 1, 2, launch_cfg1}, {256, 128, 64, 1, 2, launch_cfg2}, {128, 128, 64, 2, 2, launch_cfg3},
+    {256, 256, 64, 1, 2, launch_cfg1}, {256, 128, 64, 1, 3, launch_cfg2}, {128, 128, 64, 2, 2, launch_cfg3},
     {64, 64, 64, 2, 2, launch_cfg4},   {64, 128, 64, 2, 2, launch_cfg5},  {32, 128, 64, 2, 2, launch_cfg6},
     {64, 64, 64, 1, 6, launch_cfg7},   {32, 128, 64, 1, 6, launch_cfg8},  {64, 128, 64, 1, 4, launch_cfg9},
 };
 
 constexpr int N_CU = 256;                      // compute units of an MI355X
-constexpr unsigned long long SELF_COPY_MAX_BYTES = 8ull << 20;
 constexpr int N_XCD = 8;                       // accelerator dies of an MI355X, one L2 each
 constexpr unsigned long long DEFAULT_TIMEOUT_TICKS = 1000000000ull;   // 10 s at 100 MHz
 
@@ -59,16 +58,18 @@ struct CopyArgs {
   unsigned long long tile_vec;        // 16-byte vectors per communication tile
   uint32_t* signals;                  // may be null (baseline copy: nothing to claim, count or signal)
   uint32_t* counters;
-  uint32_t* claims;                   // [signals][gridDim.x]
+  uint32_t* claims;                   // [signals][pieces]
+  int pieces;                         // pieces per communication tile; workgroup w takes w, w + gridDim.x, ...
   uint32_t call_id;
   uint32_t* started;                  // may be null
   unsigned long long pace_ticks;      // 100 MHz ticks per communication tile, 0 = unpaced
 };
 
 // Copy driver as one kernel: all workgroups move communication tile after communication tile
-// in transfer order (DataTransfer of Alg. 3), workgroup w taking piece w of each unless a waiting
-// GEMM workgroup got to that piece first; whoever finishes a tile's last piece sets its signal
-// (SetSignal).  The data is stored write-through and each wave waits for its stores to be
+// in transfer order (DataTransfer of Alg. 3), workgroup w taking pieces w, w + gridDim.x, ... of each
+// unless a waiting GEMM workgroup got to a piece first; whoever finishes a tile's last piece sets
+// its signal (SetSignal).  A tile has more pieces than the driver has workgroups, so that many
+// waiting workgroups can share one tile.  The data is stored write-through and each wave waits for its stores to be
 // acknowledged before the workgroup counts itself in, so no cache write-back fence (which would
 // sweep the whole L2 of the die, per tile) is needed to publish a tile.
 __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
@@ -84,21 +85,26 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
     const int chunk = c.order[idx / c.tiles_per_chunk];
     const int t = idx % c.tiles_per_chunk;
     const int flag = chunk * c.tiles_per_chunk + t;
-    // link emulation: the tile "arrives" no earlier than a link of the given rate allows
-    // (its data may move while the link is still busy with the tile before)
-    if (c.signals != nullptr) {
-      if (threadIdx.x == 0) mine = claim_piece(c.claims + (size_t)flag * gridDim.x + blockIdx.x, c.call_id) ? 1 : 0;
-      __syncthreads();
-      const bool take = mine != 0;
-      __syncthreads();
-      if (!take) continue;
-    }
     const uint4* src = c.src[chunk] + (unsigned long long)t * c.tile_vec;
     uint4* dst = c.dst + (unsigned long long)chunk * c.chunk_vec + (unsigned long long)t * c.tile_vec;
-    copy_piece(src, dst, c.tile_vec, (int)blockIdx.x, (int)gridDim.x, (int)threadIdx.x);
+    int moved = 0;
+    for (int piece = (int)blockIdx.x; piece < c.pieces; piece += (int)gridDim.x) {
+      if (c.signals != nullptr) {
+        if (threadIdx.x == 0) mine = claim_piece(c.claims + (size_t)flag * c.pieces + piece, c.call_id) ? 1 : 0;
+        __syncthreads();
+        const bool take = mine != 0;
+        __syncthreads();
+        if (!take) continue;
+      }
+      copy_piece(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x);
+      ++moved;
+    }
+    if (moved == 0) continue;
+    // link emulation: the tile "arrives" no earlier than a link of the given rate allows
+    // (its data may move while the link is still busy with the tile before)
     if (c.pace_ticks != 0 && threadIdx.x == 0)
       while (wall_clock64() - t_start < (unsigned long long)(idx + 1) * c.pace_ticks) __builtin_amdgcn_s_sleep(8);
-    if (c.signals != nullptr) finish_piece(c.counters + flag, c.signals + flag, (int)gridDim.x);
+    if (c.signals != nullptr) finish_pieces(c.counters + flag, c.signals + flag, c.pieces, moved);
   }
 }
 
@@ -172,9 +178,11 @@ struct Plan {
   int n_xcd;
   int ctpc;         // communication tiles per chunk
   // AllGather copy driver
-  int copy_wgs;             // workgroups of the copy kernel = pieces per communication tile
+  int copy_wgs;             // workgroups of the copy kernel
+  int copy_pieces;          // pieces per communication tile (the unit a workgroup claims and moves)
   int copy_help;            // waiting GEMM workgroups may take pieces
-  int copy_self;            // no copy kernel at all: the waiting workgroups move everything
+  int copy_self;            // no copy kernel at all: the GEMM grid moves everything
+  int copy_owners;          // ... its first copy_owners workgroups sharing the pieces out by index
   size_t claim_bytes;       // claim words in the workspace, after the header
 };
 
@@ -275,30 +283,34 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   else pl->edge = 0;
   pl->n_xcd = (p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_NO_XCD_REMAP)) ? 1 : N_XCD;
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
-  pl->copy_wgs = 0; pl->copy_help = 0; pl->copy_self = 0; pl->claim_bytes = 0;
+  pl->copy_wgs = 0; pl->copy_pieces = 0; pl->copy_help = 0; pl->copy_self = 0; pl->copy_owners = 0; pl->claim_bytes = 0;
   if (op == FLUX_OP_AG) {
-    // A small driver: it keeps the later chunks coming in the background while waiting GEMM
-    // workgroups pull what they need now; a large one would sit on compute units the GEMM wants.
+    // Driver: one piece of every communication tile per workgroup.  A small driver: it keeps the
+    // later chunks coming in the background while waiting GEMM workgroups pull what they need now;
+    // a large one would sit on compute units the GEMM wants.
     int wgs = p->copy_workgroups > 0 ? p->copy_workgroups : 32;
     wgs = std::min(wgs, MAX_COPY_PIECES);
     const unsigned long long tile_vec = (unsigned long long)(p->M / p->R) * p->K / 8 / pl->ctpc;
     wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (tile_vec + 255) / 256));
     pl->copy_wgs = wgs;
+    pl->copy_pieces = wgs;
     pl->copy_help = !(p->flags & FLUX_FLAG_COPY_MEMCPY);
-    // A transfer this small is over sooner than a second stream can be forked and joined: the
-    // GEMM grid pulls the tiles itself (every waiting workgroup helps) and no driver is launched.
-    const unsigned long long remote_bytes = (unsigned long long)(p->R - 1) * (p->M / p->R) * p->K * 2;
-    pl->copy_self = pl->copy_help && p->link_gbps == 0 && p->copy_workgroups == 0 && remote_bytes <= SELF_COPY_MAX_BYTES;
+    // Unless the driver stands for a link (link_gbps), or the caller asks for one (copy_workgroups,
+    // FLUX_FLAG_COPY_MEMCPY), none is launched: the GEMM grid moves the data itself before it looks
+    // at its signals.  A driver workgroup holds a compute unit that a GEMM workgroup cannot share
+    // (it needs the whole register file) and pushes that unit's tiles back by its own lifetime, a
+    // whole extra round where the grid divided evenly before; on a grid that leaves units free it
+    // still costs a second stream's fork and join, and waiting workgroups spin beside it.
+    pl->copy_self = pl->copy_help && p->link_gbps == 0 && p->copy_workgroups == 0;
     if (pl->copy_self) {
-      // about one piece per workgroup and tile it waits for: the workgroups that share an m-tile
-      // (all n-tiles, all K parts) split the communication tiles that m-tile covers
-      const int rows_per_signal = std::max(1, (p->M / p->R) / pl->ctpc);
-      const long long tiles_per_mtile = std::max(1, std::min(p->R * pl->ctpc, pl->bm / rows_per_signal));
-      const long long sharers = (long long)pl->tiles_n * pl->split_k;
-      wgs = (int)std::max<long long>(1, std::min<long long>(wgs, sharers / tiles_per_mtile));
-      pl->copy_wgs = wgs;
+      // the first workgroups of the grid, as many as surely run at once, own the pieces
+      pl->copy_wgs = 0;
+      // pieces of 16 KiB or more, as many as the claim table allows
+      pl->copy_pieces = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(MAX_COPY_PIECES, tile_vec / 1024));
+      const long long grid = (long long)pl->full_tiles + (long long)pl->split_tiles * pl->split_k;
+      pl->copy_owners = (int)std::min<long long>(grid, (long long)N_CU * g_cfgs[cfg].occupancy);
     }
-    pl->claim_bytes = (((size_t)p->R * pl->ctpc * wgs * 4) + 255) / 256 * 256;
+    pl->claim_bytes = (((size_t)p->R * pl->ctpc * pl->copy_pieces * 4) + 255) / 256 * 256;
   }
   return FLUX_OK;
 }
@@ -435,9 +447,11 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
     // bytes / (GB/s) = ns; 10 ns per tick
     c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
     wgs = pl.copy_wgs;
+    c.pieces = pl.copy_pieces;
   } else {
     wgs = p->copy_workgroups > 0 ? p->copy_workgroups : 1024;
     wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (c.tile_vec + 255) / 256));
+    c.pieces = wgs;
   }
   hipLaunchKernelGGL(ag_copy_kernel, dim3(wgs), dim3(256), 0, s, c);
   FLUX_HIP(hipGetLastError());
@@ -660,7 +674,7 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   a.sig_local_hi = (p->rank + 1) * pl.ctpc;
   const uint32_t call_id = next_call_id();
   if (pl.copy_help && p->R > 1) {
-    a.copy_pieces = pl.copy_wgs;
+    a.copy_pieces = pl.copy_pieces;
     a.copy_driver_wgs = pl.copy_self ? 0 : pl.copy_wgs;
     // A waiting workgroup holds a whole compute unit: unless the driver stands for a link of a given
     // rate, it moves pieces of what it waits for right away instead of spinning next to the driver.
@@ -668,6 +682,12 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
     a.copy_call_id = call_id;
     a.copy_tile_vec = (unsigned long long)chunk_elems / 8 / pl.ctpc;
     for (int r = 0; r < p->R; ++r) a.outs[r] = const_cast<void*>(A_chunks[r]);   // chunk sources by rank
+    if (pl.copy_self) {
+      a.copy_owner_wgs = pl.copy_owners;
+      a.copy_n_tiles = (p->R - 1) * pl.ctpc;
+      static_assert(FLUX_MAX_RANKS <= 16, "chunk indices are packed four bits each");
+      for (int i = 0; i < p->R - 1; ++i) a.copy_order4 |= (unsigned long long)order[i] << (4 * i);
+    }
   }
   build_tile_map(FLUX_OP_AG, p, pl, order, &a.tm);
 

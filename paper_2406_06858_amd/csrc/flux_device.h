@@ -91,6 +91,12 @@ struct GemmArgs {
   int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none, the
                              // waiting workgroups move everything)
   int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
+  // No driver at all (copy_owner_wgs > 0): piece g (counted over the remote communication tiles in
+  // transfer order, tile j lying in the chunk at position j / ctpc of copy_order4) belongs to workgroup g % copy_owner_wgs of
+  // this grid, which moves it before it looks at its own signals.
+  int32_t copy_owner_wgs;
+  int32_t copy_n_tiles;
+  unsigned long long copy_order4;   // chunk of position i in bits [4i, 4i+4)
   unsigned long long copy_tile_vec;   // 16-byte vectors per communication tile
   uint32_t* status;
   unsigned long long timeout_ticks;
@@ -408,16 +414,19 @@ __device__ __forceinline__ void store_through(uint4* p, const u32x4& d) {
 
 __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
                                            int piece, int pieces, int tid) {
+  // 16 vectors per thread in flight; the last batch is predicated, not walked one vector (one
+  // memory round trip) at a time
+  constexpr int DEPTH = 16;
   const unsigned long long stride = (unsigned long long)pieces * 256;
-  unsigned long long i = (unsigned long long)piece * 256 + tid;
-  for (; i + 7 * stride < tile_vec; i += 8 * stride) {
-    u32x4 v[8];
+  for (unsigned long long i = (unsigned long long)piece * 256 + tid; i < tile_vec; i += DEPTH * stride) {
+    u32x4 v[DEPTH];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i + u * stride));
+    for (int u = 0; u < DEPTH; ++u)
+      if (i + u * stride < tile_vec) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i + u * stride));
 #pragma unroll
-    for (int u = 0; u < 8; ++u) store_through(dst + i + u * stride, v[u]);
+    for (int u = 0; u < DEPTH; ++u)
+      if (i + u * stride < tile_vec) store_through(dst + i + u * stride, v[u]);
   }
-  for (; i < tile_vec; i += stride) store_through(dst + i, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i)));
 }
 
 // true if this workgroup now owns the piece (call from one thread)
@@ -427,18 +436,24 @@ __device__ __forceinline__ bool claim_piece(uint32_t* claim, uint32_t call_id) {
   return __hip_atomic_compare_exchange_strong(claim, &old, call_id, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// After the piece's stores: wait until they are acknowledged, count the piece in, set the signal
-// if it was the tile's last.  All threads of the workgroup call this.
-__device__ __forceinline__ void finish_piece(uint32_t* counter, uint32_t* signal, int pieces) {
+// After the stores of `n` pieces of one tile: wait until they are acknowledged, count the pieces
+// in, set the signal if they were the tile's last.  All threads of the workgroup call this.
+__device__ __forceinline__ void finish_pieces(uint32_t* counter, uint32_t* signal, int pieces, int n) {
   __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (prev == (uint32_t)pieces - 1) {
+    const uint32_t prev = __hip_atomic_fetch_add(counter, (uint32_t)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev + (uint32_t)n == (uint32_t)pieces) {
       __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
       __hip_atomic_store(signal, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
+  // Callers loop: without a barrier here, this one-thread block and the one-thread block that
+  // opens the caller's next iteration (a claim, a counter fetch) are adjacent across the back
+  // edge, and the compiler has been seen to merge them into one divergent region that the other
+  // lanes of the first wave skip on their way to the next iteration's barrier, which they then
+  // reach without thread 0 (and read what it has not written yet).
+  __syncthreads();
 }
 
 // The copy driver's workgroups count themselves in when they start: word 0 of `started` only ever
@@ -478,6 +493,55 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   uint32_t salt = (uint32_t)blockIdx.x * 0x9E3779B9u;      // varies per workgroup and per attempt
   int dead_w0 = -1;                                        // window start at which a search found nothing left to take
   bool ok = true;
+  if ((int)blockIdx.x < a.copy_owner_wgs) {
+    // No driver: the first copy_owner_wgs workgroups of the grid share the transfer out among
+    // themselves by index, each moving its pieces in transfer order before it looks at its own
+    // signals, whatever its own tile needs.  A piece still goes through the claim table (one
+    // word per piece, so nobody contends), which lets any waiting workgroup take over the piece of
+    // an owner that has not been given a compute unit yet.  The first wave claims up to 64 pieces
+    // in one round trip and, when they have been moved, counts them in in another.
+    const int ctpc = a.n_signals / a.R;
+    const int total = a.copy_n_tiles * a.copy_pieces;
+    const int G = a.copy_owner_wgs;
+    for (int base = (int)blockIdx.x; base < total; base += 64 * G) {
+      if (tid < 64) {
+        const int g = base + tid * G;
+        bool mine = false;
+        if (g < total) {
+          const int j = g / a.copy_pieces;
+          const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
+          mine = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + (g - j * a.copy_pieces), a.copy_call_id);
+        }
+        const unsigned long long won = __ballot(mine);
+        if (tid == 0) { lds[1] = (int)(uint32_t)won; lds[2] = (int)(uint32_t)(won >> 32); }
+      }
+      __syncthreads();
+      const unsigned long long won = (unsigned long long)(uint32_t)lds[1] | ((unsigned long long)(uint32_t)lds[2] << 32);
+      for (unsigned long long rest = won; rest != 0; rest &= rest - 1) {
+        const int g = base + __builtin_ctzll(rest) * G;
+        const int j = g / a.copy_pieces, piece = g - j * a.copy_pieces;
+        const int chunk = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15), t = j % ctpc;
+        const int f = chunk * ctpc + t;
+        const uint4* src = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)t * a.copy_tile_vec;
+        uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
+        copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
+      }
+      // count the pieces in, all at once: lane l of the first wave for the piece it claimed
+      __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
+      __syncthreads();
+      if (tid < 64 && ((won >> tid) & 1)) {
+        const int g = base + tid * G;
+        const int j = g / a.copy_pieces;
+        const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
+        const uint32_t prev = __hip_atomic_fetch_add(a.copy_counters + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1u == (uint32_t)a.copy_pieces) {
+          __hip_atomic_store(a.copy_counters + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+          __hip_atomic_store(a.signals + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+      }
+      __syncthreads();
+    }
+  }
   for (;;) {
     if (tid < 64) {
       // the first wave polls, one signal per lane: one memory round trip per 64 signals, however
@@ -545,7 +609,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
         const uint4* src = static_cast<const uint4*>(lds_srcs[f / ctpc]) + (unsigned long long)(f % ctpc) * a.copy_tile_vec;
         uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
         copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
-        finish_piece(a.copy_counters + f, a.signals + f, a.copy_pieces);
+        finish_pieces(a.copy_counters + f, a.signals + f, a.copy_pieces, 1);
       }
     } else {
       dead_w0 = w0;                     // every piece of this window is in the hands of a workgroup that is running
@@ -735,12 +799,13 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 template <class C>
 struct DmaLoader {
   static constexpr int NW = C::NT / 64;
-  static constexpr int A_INSTR = C::BM / 8 / NW;               // per wave
+  static constexpr int A_RPI = 8;                              // A rows per instruction (1 KiB of 128-byte rows)
+  static constexpr int A_INSTR = C::BM / A_RPI / NW;           // per wave
   static constexpr int RPI = 512 / C::BN;                      // B k-rows per instruction
   static constexpr int B_INSTR = C::BK / RPI / NW;             // per wave
   static_assert(C::BK == 64, "A rows must be 128 B");
   static_assert(NW % 2 == 0 && (RPI * NW) % 4 == 0, "swizzle must not depend on the instruction index");
-  static_assert(C::BM % (8 * NW) == 0 && C::BK % (RPI * NW) == 0 && 512 % C::BN == 0, "loader shape");
+  static_assert(C::BM % (A_RPI * NW) == 0 && C::BK % (RPI * NW) == 0 && 512 % C::BN == 0, "loader shape");
 
   __amdgpu_buffer_rsrc_t ra, rb;
   int voff_a, voff_b;
@@ -748,8 +813,8 @@ struct DmaLoader {
   __device__ __forceinline__ void init(const GemmArgs& a, int m0, int n0, int wave, int lane) {
     ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.A), 0, (int)((unsigned)a.M * (unsigned)a.K * 2u), 0x00027000);
     rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0, (int)((unsigned)a.K * (unsigned)a.N * 2u), 0x00027000);
-    const int r_in = lane >> 3, sp = lane & 7;
-    const int row = 8 * wave + r_in;
+    const int r_in = lane / C::A_SLOTS, sp = lane % C::A_SLOTS;
+    const int row = A_RPI * wave + r_in;
     voff_a = ((m0 + row) * a.K + ((sp ^ swz_a<C::A_SLOTS>(row)) << 3)) * 2;
     const int k_in = lane / C::B_SLOTS, spb = lane % C::B_SLOTS;
     const int k = RPI * wave + k_in;
@@ -762,7 +827,7 @@ struct DmaLoader {
   __device__ __forceinline__ void issue_dyn(int idx, const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
     if (idx < A_INSTR) {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (idx * NW + wave) * 1024), 16, voff_a,
-                                               (k0 + idx * 8 * NW * a.K) * 2, 0, 0);
+                                               (k0 + idx * A_RPI * NW * a.K) * 2, 0, 0);
     } else {
       const int p = idx - A_INSTR;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
@@ -775,7 +840,7 @@ struct DmaLoader {
 #pragma unroll
     for (int p = 0; p < A_INSTR; ++p)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (p * NW + wave) * 1024), 16, voff_a,
-                                               (k0 + p * 8 * NW * a.K) * 2, 0, 0);
+                                               (k0 + p * A_RPI * NW * a.K) * 2, 0, 0);
 #pragma unroll
     for (int p = 0; p < B_INSTR; ++p)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
@@ -1060,18 +1125,14 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
   static_assert(NS >= 3 && NS <= 6, "3 to 6 stages");
   constexpr int L = DmaLoader<C>::N_INSTR;                  // loads per slab and wave
   static_assert((NS - 2) * L < 64, "outstanding loads must fit the counter");
-#define FLUX_STAGE_BYTES(i) ((i) < NS ? C::STAGE_BYTES : 16)
-  __shared__ __attribute__((aligned(1024))) unsigned char st0[FLUX_STAGE_BYTES(0)];
-  __shared__ __attribute__((aligned(1024))) unsigned char st1[FLUX_STAGE_BYTES(1)];
-  __shared__ __attribute__((aligned(1024))) unsigned char st2[FLUX_STAGE_BYTES(2)];
-  __shared__ __attribute__((aligned(1024))) unsigned char st3[FLUX_STAGE_BYTES(3)];
-  __shared__ __attribute__((aligned(1024))) unsigned char st4[FLUX_STAGE_BYTES(4)];
-  __shared__ __attribute__((aligned(1024))) unsigned char st5[FLUX_STAGE_BYTES(5)];
-#undef FLUX_STAGE_BYTES
-  __shared__ __attribute__((aligned(16))) unsigned char ep_stage[C::EP_BYTES];
+  // One pool: the stages, and over them (once the main loop is done) the epilogue's staging area.
+  constexpr int POOL_BYTES = NS * C::STAGE_BYTES > C::EP_BYTES ? NS * C::STAGE_BYTES : C::EP_BYTES;
+  __shared__ __attribute__((aligned(1024))) unsigned char pool[POOL_BYTES];
   __shared__ int lds_misc[4];
   __shared__ void* lds_outs[FLUX_MAX_RANKS];
-  unsigned char* const st[6] = {st0, st1, st2, st3, st4, st5};
+  unsigned char* const st[6] = {pool, pool + C::STAGE_BYTES, pool + 2 * C::STAGE_BYTES, pool + (NS > 3 ? 3 : 0) * C::STAGE_BYTES,
+                                pool + (NS > 4 ? 4 : 0) * C::STAGE_BYTES, pool + (NS > 5 ? 5 : 0) * C::STAGE_BYTES};
+  unsigned char* const ep_stage = pool;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
@@ -1126,6 +1187,7 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
     }
   }
   wait_vm_at_most<0>();
+  __syncthreads();       // the epilogue's staging area lies over stages other waves may still be reading
   gemm_tail<C, EPI, MASK>(a, ep_stage, lds_misc, lds_outs, acc, tile, split, is_split, m0, n0, tid, lane, wave, wm, wn);
 }
 

@@ -7,7 +7,7 @@ namespace flux {
 #if FLUX_CFG_ID == 1
 typedef TileCfg<256, 256, 64, 2, 2, 2, 1> Cfg;   // 128x128 per wave, one workgroup per CU
 #elif FLUX_CFG_ID == 2
-typedef TileCfg<256, 128, 64, 2, 2, 2, 1> Cfg;   // 128x64 per wave: twice the tiles of 256x256
+typedef TileCfg<256, 128, 64, 2, 2, 3, 1> Cfg;   // 128x64 per wave: twice the tiles of 256x256; three LDS stages
 #elif FLUX_CFG_ID == 3
 typedef TileCfg<128, 128, 64, 2, 2, 2, 2> Cfg;   // 64x64 per wave
 #elif FLUX_CFG_ID == 4
