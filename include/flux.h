@@ -76,6 +76,11 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
                                         A.B is converted and stored into its owner's slice (the AlltoAll
                                         flavour of Sec. 3.1; flux_rs_reduce_slice is the reduction after it) */
 
+#define FLUX_FLAG_AG_ABSENT_OWNERS 0x40u /* flux_ag_gemm without a copy kernel: share the pieces out over twice as
+                                        many workgroups as the grid has, so that every second piece has an
+                                        owner that never runs and is taken over by a workgroup that waits for
+                                        it.  For tests of that take-over; costs time, never correctness. */
+
 /* flux_gemm_ref_unfused phases */
 #define FLUX_PHASE_GEMM 0x1
 #define FLUX_PHASE_COMM 0x2

@@ -309,6 +309,7 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
       pl->copy_pieces = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(MAX_COPY_PIECES, tile_vec / 1024));
       const long long grid = (long long)pl->full_tiles + (long long)pl->split_tiles * pl->split_k;
       pl->copy_owners = (int)std::min<long long>(grid, (long long)N_CU * g_cfgs[cfg].occupancy);
+      if (p->flags & FLUX_FLAG_AG_ABSENT_OWNERS) pl->copy_owners = (int)std::min<long long>(2 * grid, 1 << 20);
     }
     pl->claim_bytes = (((size_t)p->R * pl->ctpc * pl->copy_pieces * 4) + 255) / 256 * 256;
   }

@@ -349,6 +349,28 @@ def test_ag_waiting_workgroups_move_the_data_themselves():
         assert e0.elapsed_ms(e1) < 5.0, "the GEMM kernel waited for the delayed copy driver"
 
 
+@pytest.mark.parametrize("shape", [dict(M=4096, N=2048, K=512), dict(M=2048, N=1024, K=1024), dict(M=64, N=1024, K=2048)])
+@pytest.mark.parametrize("ctpc", [1, 4])
+def test_ag_without_copy_kernel(shape, ctpc):
+    """The default: no copy kernel, the first workgroups of the GEMM grid share the pieces out by index
+    (a grid of several rounds, one that leaves compute units free, a decode shape).  With
+    FLUX_FLAG_AG_ABSENT_OWNERS every second piece belongs to a workgroup that never runs, so the
+    workgroups that wait for it have to take it over through the claim table.  Two calls in a row:
+    the second relies on the counters, claims and signals the first left behind."""
+    w = fi.scaled(W["c2_ag"], **shape)
+    rank = 6
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    for flags in (0, fb.FLUX_FLAG_AG_ABSENT_OWNERS, fb.FLUX_FLAG_AG_ABSENT_OWNERS | fb.FLUX_FLAG_NO_SWIZZLE):
+        _say("no copy kernel", shape, "ctpc", ctpc, "flags", flags)
+        Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, flags=flags, comm_tiles_per_chunk=ctpc,
+                                               repeat=2)
+        assert status == (fb.FLUX_OK, 0)
+        gh.assert_close(Cg, C64, w.out_dtype)
+        gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+        assert signals.cpu().tolist() == [1 if i // ctpc == rank else 0 for i in range(w.R * ctpc)]
+
+
 def test_ag_tile_waiting_for_many_signals():
     """One 256-row tile that waits for 32 signals of 1 MiB communication tiles in 256 pieces each: more
     pieces than one search of a waiting workgroup covers, so its search window has to move on as
