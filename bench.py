@@ -102,9 +102,9 @@ def main() -> int:
                                      Cout=self.C, arrival_order=self.arrival, workspace=self.ws_chunk,
                                      compute_stream=compute, comm_stream=copy)
 
-        def alg_bytes(self):     # fused kernel: A_agg + B read once, C written once
-            w = self.w
-            return 2.0 * (w.M * w.K + w.K * w.N + w.M * w.N)
+        def alg_bytes(self):     # fused kernel: A_agg + B read once, C written once; the default call has no
+            w = self.w           # copy kernel, so the R-1 remote chunks are read and written by this kernel too
+            return 2.0 * (w.M * w.K + w.K * w.N + w.M * w.N) + 2 * 2.0 * (w.R - 1) * w.S * w.K
 
     class RS:
         def __init__(self, w, rank, **kw):
@@ -280,8 +280,8 @@ def main() -> int:
 
     # Traffic behind the L2 per launch, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
     # `bench.py --serial-kernels 10`, each scaled by what the same counter reads for the 58.7 MB chunk
-    # copy (1.9972 and 0.9996 KiB per count); profiles/bench_c2ag_c3rs_pmc_traffic.txt.
-    traffic = {"rs": 830.8e6 + 75.5e6, "ag": 608.9e6 + 64.6e6}
+    # copy (1.9964 and 1.0000 KiB per count); profiles/bench_c2ag_c3rs_pmc_traffic.txt.
+    traffic = {"rs": 821.4e6 + 67.1e6, "ag": 563.5e6 + 88.2e6}
     alg = {"rs": rs.alg_bytes(), "ag": ag.alg_bytes()}
 
     def kernel_line(name, which, w, ms):
@@ -306,6 +306,21 @@ def main() -> int:
     if not args.no_extra:
         extra["c2_ag"] = overlap_block(ag)
         extra["c3_rs"] = overlap_block(rs)
+        # Context, not a target and not part of the path: the vendor library's plain GEMM (hipBLASLt
+        # behind torch.matmul) on the same operands, and on zeros.  With normally distributed operands
+        # the chip runs into its power limit and every GEMM, this one included, slows down by a
+        # fifth or so; the MFMA peak is not reachable on such data by any kernel.
+        lib = {}
+        for key, A_, B_ in (("c2_ag", ag.A_agg, ag.B), ("c3_rs", rs.A, rs.B)):
+            out_ = torch.empty((A_.shape[0], B_.shape[1]), dtype=torch.bfloat16, device=dev)
+            fl = 2.0 * A_.shape[0] * A_.shape[1] * B_.shape[1]
+            t_data = time_calls(lambda: torch.matmul(A_, B_, out=out_), 20, 5)
+            Az, Bz = torch.zeros_like(A_), torch.zeros_like(B_)
+            t_zero = time_calls(lambda: torch.matmul(Az, Bz, out=out_), 20, 5)
+            lib[key] = {"ms_workload_operands": round(t_data, 4), "tflops_workload_operands": round(fl / t_data / 1e9, 1),
+                        "ms_zero_operands": round(t_zero, 4), "tflops_zero_operands": round(fl / t_zero / 1e9, 1)}
+            del Az, Bz, out_
+        extra["library_gemm_context"] = lib
         del ag, rs
         torch.cuda.empty_cache()
         for name in ("c4_ag", "c4_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):

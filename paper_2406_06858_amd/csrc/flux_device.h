@@ -429,11 +429,10 @@ __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4*
   }
 }
 
-// true if this workgroup now owns the piece (call from one thread)
+// true if the caller now owns the piece.  One exchange, one round trip: whoever swaps the call's id
+// in first sees something else come back; anyone later swaps the id for itself.
 __device__ __forceinline__ bool claim_piece(uint32_t* claim, uint32_t call_id) {
-  uint32_t old = __hip_atomic_load(claim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (old == call_id) return false;
-  return __hip_atomic_compare_exchange_strong(claim, &old, call_id, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __hip_atomic_exchange(claim, call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != call_id;
 }
 
 // After the stores of `n` pieces of one tile: wait until they are acknowledged, count the pieces
