@@ -213,35 +213,13 @@ static int validate_problem(int op, const flux_problem_t* p) {
   return FLUX_OK;
 }
 
-static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
-  int st = validate_problem(op, p);
-  if (st != FLUX_OK) return st;
-  int cfg;
-  if (p->tile_config > 0) {
-    cfg = p->tile_config - 1;
-  } else {
-    // few rows: the tile is bound by memory, so take the deep load pipeline if the shape allows its
-    // direct-to-LDS loads (whole tiles along N and K; M may be ragged), else the two-stage twin
-    const bool deep_ok = p->K % 64 == 0;
-    if (p->M <= 32) cfg = (deep_ok && p->N % 128 == 0) ? 7 : 5;          // 32x128
-    else if (p->M <= 64) cfg = (deep_ok && p->N % 64 == 0 && p->M == 64) ? 6 : 4;   // 64x64 deep, else 64x128
-    else if ((long long)p->M * p->N <= 256ll * 1024) cfg = 3;            // 64x64, small problems
-    else if (p->M <= 256 && p->M % 64 == 0 && deep_ok && p->N % 128 == 0) cfg = 8;   // 64x128 deep
-    else if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 128) cfg = 0;   // 256x256: the least operand traffic per flop
-    else cfg = 2;                                                        // 128x128: enough tiles to fill the chip on mid-sized problems
-  }
-  pl->cfg = cfg;
-  pl->bm = g_cfgs[cfg].bm; pl->bn = g_cfgs[cfg].bn; pl->bk = g_cfgs[cfg].bk;
-  pl->tiles_m = (p->M + pl->bm - 1) / pl->bm;
-  pl->tiles_n = (p->N + pl->bn - 1) / pl->bn;
-  if (pl->tiles_m > FLUX_MAX_M_TILES) return FLUX_ERR_UNSUPPORTED;
-  const long long tiles = (long long)pl->tiles_m * pl->tiles_n;
-  if (tiles > (1ll << 24)) return FLUX_ERR_UNSUPPORTED;
-  const int kt = (p->K + pl->bk - 1) / pl->bk;
+// How K is cut for configuration `cfg`: `split` parts for the last `split_tiles` tiles of the grid
+// (all of them for a uniform split), none for the others.
+static void plan_split(const flux_problem_t* p, int cfg, long long tiles, int kt, int* split_out, long long* split_tiles_out) {
   int split = p->split_k;
+  const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
   if (split <= 0) {
     split = 1;
-    const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
     if (g_cfgs[cfg].stages > 2) {
       // deep pipeline, one workgroup per CU: as many K parts as still give a single round, each
       // long enough for the pipeline to fill
@@ -259,13 +237,76 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   if (p->split_k <= 0 && split == 1 && !(p->flags & FLUX_FLAG_NO_TAIL_SPLIT)) {
     // A grid of a few rounds whose last round fills at most half of the chip: cut only that
     // round's tiles along K so that it too occupies every CU, for a fraction of a round's time.
-    const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
     const long long rem = tiles % slots;
     if (tiles > slots && tiles < 8 * slots && rem > 0 && 2 * rem <= slots) {
       const int ts = (int)std::min<long long>(std::min<long long>(slots / rem, 8), kt / 4);
       if (ts > 1) { split = ts; split_tiles = rem; }
     }
   }
+  *split_out = std::max(1, std::min(split, kt));
+  *split_tiles_out = split_tiles;
+}
+
+// Estimated time of the GEMM under configuration `cfg`, in arbitrary units: rounds of the grid
+// over the chip's workgroup slots, times the tile's area, over the configuration's rate per slot
+// (from measurements of full grids: 256x256 = 1, 256x128 on three stages 0.84, 128x128 two per
+// CU 0.8 per CU; a ragged shape runs the register-staged kernel at about 0.7 of that).
+static double plan_cost(const flux_problem_t* p, int cfg) {
+  const int bm = g_cfgs[cfg].bm, bn = g_cfgs[cfg].bn, bk = g_cfgs[cfg].bk;
+  const long long tiles = (long long)((p->M + bm - 1) / bm) * ((p->N + bn - 1) / bn);
+  const int kt = (p->K + bk - 1) / bk;
+  const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
+  int split;
+  long long split_tiles;
+  plan_split(p, cfg, tiles, kt, &split, &split_tiles);
+  const double part = (1.0 + 0.04 * (split - 1)) / split;          // a K part, with its hand-over
+  double rounds;
+  if (split > 1 && split_tiles < tiles) rounds = (double)((tiles - split_tiles) / slots) + part * (double)((split_tiles * split + slots - 1) / slots);
+  else rounds = part * (double)((tiles * split + slots - 1) / slots);
+  double rate = cfg == 0 ? 1.0 : cfg == 1 ? 0.84 : 0.8 / g_cfgs[cfg].occupancy;
+  if (p->M % bm != 0 || p->N % bn != 0 || p->K % bk != 0) rate *= 0.7;
+  return rounds * (double)bm * (double)bn / rate;
+}
+
+static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
+  int st = validate_problem(op, p);
+  if (st != FLUX_OK) return st;
+  int cfg;
+  if (p->tile_config > 0) {
+    cfg = p->tile_config - 1;
+  } else {
+    // few rows: the tile is bound by memory, so take the deep load pipeline if the shape allows its
+    // direct-to-LDS loads (whole tiles along N and K; M may be ragged), else the two-stage twin
+    const bool deep_ok = p->K % 64 == 0;
+    if (p->M <= 32) cfg = (deep_ok && p->N % 128 == 0) ? 7 : 5;          // 32x128
+    else if (p->M <= 64) cfg = (deep_ok && p->N % 64 == 0 && p->M == 64) ? 6 : 4;   // 64x64 deep, else 64x128
+    else if ((long long)p->M * p->N <= 256ll * 1024) cfg = 3;            // 64x64, small problems
+    else if (p->M <= 256 && p->M % 64 == 0 && deep_ok && p->N % 128 == 0) cfg = 8;   // 64x128 deep
+    else {
+      // Large tiles: 256x256 moves the least operand data per flop but needs a grid that fills the
+      // chip round by round; 256x128 and 128x128 give two and four times the tiles.  Take the one
+      // with the least estimated time.  256x256 with a uniform K split is never worth it.
+      cfg = 2;
+      double best = plan_cost(p, 2);
+      const double c1 = plan_cost(p, 1);
+      if (c1 < best) { best = c1; cfg = 1; }
+      if ((long long)((p->M + 255) / 256) * ((p->N + 255) / 256) >= 128) {
+        const double c0 = plan_cost(p, 0);
+        if (c0 <= best) { best = c0; cfg = 0; }
+      }
+    }
+  }
+  pl->cfg = cfg;
+  pl->bm = g_cfgs[cfg].bm; pl->bn = g_cfgs[cfg].bn; pl->bk = g_cfgs[cfg].bk;
+  pl->tiles_m = (p->M + pl->bm - 1) / pl->bm;
+  pl->tiles_n = (p->N + pl->bn - 1) / pl->bn;
+  if (pl->tiles_m > FLUX_MAX_M_TILES) return FLUX_ERR_UNSUPPORTED;
+  const long long tiles = (long long)pl->tiles_m * pl->tiles_n;
+  if (tiles > (1ll << 24)) return FLUX_ERR_UNSUPPORTED;
+  const int kt = (p->K + pl->bk - 1) / pl->bk;
+  int split;
+  long long split_tiles;
+  plan_split(p, cfg, tiles, kt, &split, &split_tiles);
   split = std::max(1, std::min(split, kt));
   const int kt_per = (kt + split - 1) / split;
   split = (kt + kt_per - 1) / kt_per;             // no empty splits

@@ -156,14 +156,30 @@ def test_split_plan_cuts_only_a_partly_filled_last_round():
         assert (shape.tile_m, shape.tile_n, shape.split_k) == (256, 256, 4)
         assert fb.flux_workspace_bytes(op, p) >= 4 * 64 * 256 * 256 * 4
     # switched off by flag, and an explicit split_k is a uniform one
-    q = fb.problem(8192, 4608, 12288, 8, 0, flags=fb.FLUX_FLAG_NO_TAIL_SPLIT)
+    q = fb.problem(8192, 4608, 12288, 8, 0, tile_config=1, flags=fb.FLUX_FLAG_NO_TAIL_SPLIT)
     assert fb.flux_split_plan(fb.FLUX_OP_AG, q) == (0, 576, 1)
     assert fb.flux_workspace_bytes(fb.FLUX_OP_RS, q) == 0
-    u = fb.problem(8192, 4608, 12288, 8, 0, split_k=2)
+    u = fb.problem(8192, 4608, 12288, 8, 0, tile_config=1, split_k=2)
     assert fb.flux_split_plan(fb.FLUX_OP_AG, u) == (0, 576, 2)
     # a last round that is more than half full, or a grid of exactly whole rounds, is left alone
-    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 6144, 12288, 8, 0)) == (0, 768, 1)
-    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 5632, 12288, 8, 0))[2] == 1   # 704 = 2.75 rounds
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 6144, 12288, 8, 0, tile_config=1)) == (0, 768, 1)
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 5632, 12288, 8, 0, tile_config=1))[2] == 1   # 704 = 2.75 rounds
     # short K: every part keeps at least four K slabs
-    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 4608, 512, 8, 0)) == (512, 64, 2)
-    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 4608, 256, 8, 0)) == (0, 576, 1)
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 4608, 512, 8, 0, tile_config=1)) == (512, 64, 2)
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, fb.problem(8192, 4608, 256, 8, 0, tile_config=1)) == (0, 576, 1)
+
+
+def test_tile_choice_follows_how_well_the_grid_fills_the_chip():
+    """The library picks among the 256x256, 256x128 and 128x128 tiles by estimated time: the largest
+    tile where its grid fills the chip round by round, a smaller one where that leaves units idle."""
+    def tile(M, N, K):
+        s = fb.flux_tile_shape(fb.FLUX_OP_AG, fb.problem(M, N, K, 8, 0))
+        return (s.tile_m, s.tile_n)
+    assert tile(4096, 3584, 8192) == (256, 256)      # 224 tiles, one round
+    assert tile(4096, 8192, 3584) == (256, 256)      # 512 tiles, two rounds
+    assert tile(8192, 6144, 12288) == (256, 256)     # 768 tiles, three rounds
+    assert tile(8192, 4608, 12288) == (256, 256)     # 2.25 rounds, the last one cut along K
+    assert tile(2048, 6144, 12288) == (256, 128)     # 192 tiles of 256x256 would leave a quarter of the chip idle
+    assert tile(1024, 8192, 3584) == (256, 128)      # 128 tiles of 256x256: half the chip
+    assert tile(2048, 8192, 3584) == (256, 256)      # exactly one round
+    assert tile(512, 6144, 12288)[0] in (128, 256) and tile(512, 6144, 12288) != (256, 256)
