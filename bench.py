@@ -87,9 +87,9 @@ def main() -> int:
             # over zeros draws less power and runs at a higher clock: a flattering baseline)
             self.unfused(fb.FLUX_PHASE_COMM)
 
-        def fused(self):
+        def fused(self, stream=None):
             fb.flux_ag_gemm(self.p, self.chunks, self.A_agg, self.B, self.C, self.signals, self.arrival,
-                            self.ws, compute, copy)
+                            self.ws, stream or compute, copy)
 
         def unfused(self, phases):
             fb.flux_gemm_ref_unfused(fb.FLUX_OP_AG, phases, self.p, A_chunks=self.chunks, A_agg=self.A_agg,
@@ -121,8 +121,8 @@ def main() -> int:
             if self.ws is not None:
                 fb.flux_init_buffers(fb.FLUX_OP_RS, self.p, self.ws)
 
-        def fused(self):
-            fb.flux_gemm_rs(self.p, self.A, self.B, self.peers, self.outs, self.ws, compute)
+        def fused(self, stream=None):
+            fb.flux_gemm_rs(self.p, self.A, self.B, self.peers, self.outs, self.ws, stream or compute)
 
         def unfused(self, phases):
             fb.flux_gemm_ref_unfused(fb.FLUX_OP_RS, phases, self.p, A=self.A, B=self.B, peer_partials=self.peers,
@@ -176,7 +176,7 @@ def main() -> int:
             ts.append(e0.elapsed_ms(e1) / batch)
         return statistics.median(ts)
 
-    def overlap_block(op, reps=20, warm=5):
+    def overlap_block(op, reps=20, warm=5, graph=False):
         """Eq. 1-2 with GEMM_non-split := the plain kernel of the same tile configuration."""
         t_gemm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_GEMM), reps, warm)
         t_comm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_COMM), reps, warm)
@@ -195,10 +195,25 @@ def main() -> int:
             ks.append(k0.elapsed_ms(k1))
         t_k = statistics.median(ks)
         t_a2a = time_calls(op.alltoall_flavour, reps, warm) if hasattr(op, "alltoall_flavour") else None
+        # the same fused call recorded once in a HIP graph (8 calls per graph) and replayed: what a
+        # serving loop that cannot afford per-call launch work would run
+        t_graph = None
+        if graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(compute)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(8):
+                    op.fused(torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            t_graph = time_calls(g.replay, reps, warm, batch=1) / 8
+            del g
         ect_no, ect_ov = t_unf - t_gemm, t_fus - t_gemm
         E = 1.0 - ect_ov / ect_no if ect_no > 0 else None
         w = op.w
         more = {} if t_a2a is None else {"ms_write_only_plus_slice_reduce": round(t_a2a, 4)}
+        if t_graph is not None:
+            more["ms_fused_graph_replay"] = round(t_graph, 4)
         return {**more, "ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
                 "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4), "ms_chunked": round(t_chk, 4),
                 "overlap_efficiency_chunked": None if ect_no <= 0 else round(1.0 - (t_chk - t_gemm) / ect_no, 4),
@@ -325,7 +340,7 @@ def main() -> int:
         torch.cuda.empty_cache()
         for name in ("c4_ag", "c4_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):
             op = AG(W[name], 2) if W[name].op == "ag" else RS(W[name], 2)
-            extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50)
+            extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50, graph=name.startswith("c5"))
             del op
             torch.cuda.empty_cache()
         # Second workload: the paper's op-level sweep (Sec. 5.1), GPT-3-175B MLP shapes at TP=8

@@ -142,6 +142,10 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  * In the first two cases a piece is claimed before it is moved, whoever moves it, and a workgroup
  * that waits takes over unclaimed pieces of the tiles it waits for, so a mover that has not been
  * given a compute unit yet cannot stall the grid.
+ * Stream capture: in the default form the call is kernel launches on compute_stream only (one, or
+ * two if the local chunk has to be copied into place) and everything that changes from call to
+ * call lives in the workspace, so it may be recorded in a HIP graph and replayed.  The forms with a
+ * driver take a fresh claim id from the host on every call and are not meant to be replayed.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.

@@ -701,9 +701,6 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   if (st != FLUX_OK) return st;
   hipStream_t cs = static_cast<hipStream_t>(compute_stream);
   hipStream_t xs = static_cast<hipStream_t>(copy_stream);
-  hipEvent_t ev_fork, ev_join;
-  st = get_events(&ev_fork, &ev_join);
-  if (st != FLUX_OK) return st;
 
   GemmArgs a;
   fill_common(&a, p, pl, workspace);
@@ -721,7 +718,8 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
     // A waiting workgroup holds a whole compute unit: unless the driver stands for a link of a given
     // rate, it moves pieces of what it waits for right away instead of spinning next to the driver.
     a.copy_eager = pl.copy_self || p->link_gbps == 0;
-    a.copy_call_id = call_id;
+    a.copy_call_id = pl.copy_self ? 0u : call_id;   // without a copy kernel the id lives in the workspace
+    a.copy_call_seq = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + WS_CALLSEQ_OFF);
     a.copy_tile_vec = (unsigned long long)chunk_elems / 8 / pl.ctpc;
     for (int r = 0; r < p->R; ++r) a.outs[r] = const_cast<void*>(A_chunks[r]);   // chunk sources by rank
     if (pl.copy_self) {
@@ -744,6 +742,9 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
     // nothing runs beside the GEMM grid: no fork, no join
     return launch_gemm(pl, EPI_PLAIN, 1, a, cs);
   }
+  hipEvent_t ev_fork, ev_join;
+  st = get_events(&ev_fork, &ev_join);
+  if (st != FLUX_OK) return st;
   // fork: the copy driver may start once everything queued so far on compute_stream is done
   FLUX_HIP(hipEventRecord(ev_fork, cs));
   FLUX_HIP(hipStreamWaitEvent(xs, ev_fork, 0));

@@ -32,6 +32,7 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 constexpr size_t WS_STATUS_OFF = 0;        // uint32 code, uint32 detail
 constexpr size_t WS_DONE_OFF = 16;         // uint32: workgroups that are past their signal wait
 constexpr size_t WS_STARTED_OFF = 32;      // uint32: copy-driver workgroups that have started
+constexpr size_t WS_CALLSEQ_OFF = 48;      // uint32: calls without a copy kernel that have completed on this workspace
 constexpr size_t WS_COUNTER_OFF = 256;     // uint32 per communication tile (copy kernel arrivals)
 constexpr int MAX_COMM_TILES = 1024;
 constexpr size_t WS_TILECNT_OFF = WS_COUNTER_OFF + 4 * MAX_COMM_TILES;   // split-K arrival counters
@@ -86,7 +87,8 @@ struct GemmArgs {
   // (outs[] then holds the chunk sources, A is the gathered matrix); copy_pieces = 0: no copy kernel
   uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
   uint32_t* copy_counters;   // [n_signals] pieces finished
-  uint32_t copy_call_id;
+  uint32_t copy_call_id;     // 0: take the id from copy_call_seq (calls without a copy kernel)
+  uint32_t* copy_call_seq;
   int32_t copy_pieces;       // pieces per communication tile
   int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none, the
                              // waiting workgroups move everything)
@@ -492,6 +494,13 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   uint32_t salt = (uint32_t)blockIdx.x * 0x9E3779B9u;      // varies per workgroup and per attempt
   int dead_w0 = -1;                                        // window start at which a search found nothing left to take
   bool ok = true;
+  // The id that marks a piece as taken in this call.  With a copy kernel beside the grid the host
+  // hands out a fresh one per call.  Without, it is the number of such calls that have completed on
+  // this workspace (the last workgroup past its wait counts the call in, when every workgroup has
+  // long read the old value), so a call recorded in a graph gets a new id on every replay.
+  uint32_t call_id = a.copy_call_id;
+  if (a.copy_pieces > 0 && call_id == 0u)
+    call_id = 0x80000000u | __hip_atomic_load(a.copy_call_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if ((int)blockIdx.x < a.copy_owner_wgs) {
     // No driver: the first copy_owner_wgs workgroups of the grid share the transfer out among
     // themselves by index, each moving its pieces in transfer order before it looks at its own
@@ -509,7 +518,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
         if (g < total) {
           const int j = g / a.copy_pieces;
           const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
-          mine = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + (g - j * a.copy_pieces), a.copy_call_id);
+          mine = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + (g - j * a.copy_pieces), call_id);
         }
         const unsigned long long won = __ballot(mine);
         if (tid == 0) { lds[1] = (int)(uint32_t)won; lds[2] = (int)(uint32_t)(won >> 32); }
@@ -591,7 +600,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
       const int f = w0 + i / a.copy_pieces;
       if (f >= a.sig_local_lo && f < a.sig_local_hi) continue;
       if (__hip_atomic_load(a.copy_claims + (size_t)f * a.copy_pieces + i % a.copy_pieces, __ATOMIC_RELAXED,
-                            __HIP_MEMORY_SCOPE_AGENT) != a.copy_call_id) {
+                            __HIP_MEMORY_SCOPE_AGENT) != call_id) {
         const uint32_t h = ((uint32_t)i * 2654435761u) ^ salt;
         atomicMin(&lds[1], (int)(((h >> 14) << 12) | (uint32_t)i));   // 18 hash bits above the 12-bit index: below the "none" value
       }
@@ -601,7 +610,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
     if (key != 0x7fffffff) {
       const int i = key & 4095;
       const int f = w0 + i / a.copy_pieces, piece = i % a.copy_pieces;
-      if (tid == 0) lds[2] = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + piece, a.copy_call_id) ? 1 : 0;
+      if (tid == 0) lds[2] = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + piece, call_id) ? 1 : 0;
       __syncthreads();
       if (lds[2]) {
         const int ctpc = a.n_signals / a.R;
@@ -622,6 +631,8 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
       for (int i = 0; i < a.n_signals; ++i)
         __hip_atomic_store(a.signals + i, (i >= a.sig_local_lo && i < a.sig_local_hi) ? 1u : 0u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
+      if (a.copy_pieces > 0 && a.copy_call_id == 0u)
+        __hip_atomic_fetch_add(a.copy_call_seq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (a.copy_driver_wgs > 0)
         __hip_atomic_fetch_add(a.started_counter + 1, (uint32_t)a.copy_driver_wgs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(a.done_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
