@@ -469,18 +469,19 @@ __device__ __forceinline__ bool driver_fully_started(const uint32_t* started, in
   return total - base >= (uint32_t)workgroups;
 }
 
-// WaitSignal (Alg. 2): one lane polls every signal covering rows [m0, m1) with coherent loads,
-// then an acquire fence makes the copied rows visible; the workgroup barrier hands that to the
-// other waves.  As long as every workgroup of the copy driver is running, that is all.  If some
-// of them have not been given a compute unit yet (the GEMM grid may have taken them all, and its
-// waiting workgroups do not leave), or if no driver was launched at all (small transfers),
-// waiting would not end: the workgroup then claims and moves pieces of the communication tiles
-// it waits for itself, starting its search at a place that depends on its index so that the
-// workgroups of a grid spread over the pieces instead of racing for the same one.  Bounded: past
-// `timeout_ticks` the tile is given up and the status block says so.  A workgroup never looks at
-// the signals again after this, so the last workgroup of the grid to get here puts the signal
-// array back into its preset state for the next call (the reset "after the GEMM" of Sec. 4.3,
-// without a separate launch).
+// WaitSignal (Alg. 2), preceded by this workgroup's share of the data transfer where no copy kernel
+// runs beside the grid.  The first wave polls the signals covering rows [m0, m1) with coherent
+// loads, one lane per signal; when all are set, an acquire fence makes the copied rows visible and
+// the workgroup barrier hands that to the other waves.  A workgroup that finds a signal missing
+// and unclaimed pieces among the tiles it waits for claims and moves such pieces itself (at once;
+// beside a paced driver only while part of that driver has not been given a compute unit), picking
+// them by a hash that depends on its index so that the workgroups of a grid spread over the pieces
+// instead of racing for the same one: without that, a mover that never gets a compute unit (the
+// GEMM grid may have taken them all, and its waiting workgroups do not leave) would stall the grid
+// for good.  Bounded: past `timeout_ticks` the tile is given up and the status block says so.  A
+// workgroup never looks at the signals again after this, so the last workgroup of the grid to get
+// here puts the signal array back into its preset state for the next call (the reset "after the
+// GEMM" of Sec. 4.3, without a separate launch).
 // `lds` is 4 ints shared by the workgroup; `lds_srcs` holds the chunk sources by rank.
 __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, int* lds, void* const* lds_srcs) {
   const int tid = threadIdx.x;
