@@ -343,6 +343,26 @@ def main() -> int:
             extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50, graph=name.startswith("c5"))
             del op
             torch.cuda.empty_cache()
+        # The tuner (Sec. 4.4) on three shapes: what it picks and what that gains over the library's own choice
+        tuned = {}
+        for name in ("c4_ag", "c4_rs", "op_ag_m2048", "op_rs_m2048", "c5_ag_m64"):
+            w = W[name]
+            if w.op == "ag":
+                op = AG(w, 2)
+                op.signals = torch.zeros(fb.flux_autotune_signal_count(op.p), dtype=torch.int32, device=dev)
+                op.ws = torch.zeros(fb.flux_autotune_workspace_bytes(fb.FLUX_OP_AG, op.p) // 4 + 1, dtype=torch.int32, device=dev)
+                t, ms_best, ms_def = fb.flux_autotune_ag(op.p, op.chunks, op.A_agg, op.B, op.C, op.signals, op.arrival,
+                                                         op.ws, compute, copy, reps=5)
+            else:
+                op = RS(w, 2)
+                n = fb.flux_autotune_workspace_bytes(fb.FLUX_OP_RS, op.p)
+                op.ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev) if n else None
+                t, ms_best, ms_def = fb.flux_autotune_rs(op.p, op.A, op.B, op.peers, op.outs, op.ws, compute, reps=5)
+            tuned[name] = {"tile_config": t.tile_config, "comm_tiles_per_chunk": t.comm_tiles_per_chunk,
+                           "ms_tuned": round(ms_best, 4), "ms_library_pick": round(ms_def, 4)}
+            del op
+            torch.cuda.empty_cache()
+        extra["autotune"] = tuned
         # Second workload: the paper's op-level sweep (Sec. 5.1), GPT-3-175B MLP shapes at TP=8
         sweep = {}
         for name in ("op_ag_m512", "op_rs_m512", "op_ag_m2048", "op_rs_m2048", "op_ag_m8192", "op_rs_m8192"):

@@ -242,6 +242,31 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p,
 size_t flux_chunked_workspace_bytes(int op, const flux_problem_t* p);
 
 /*
+ * Tuner (Sec. 4.4; the communication tile size of Sec. 4.3 among the knobs).  Times the fused call
+ * on the caller's own buffers for every tile configuration that accepts the shape and, for the
+ * AllGather, for communication tiles of the chunk height halved down to the GEMM tile height (at
+ * most 8 per chunk), against what the library picks by itself, and writes the fastest problem
+ * description to *tuned (a copy of *p with tile_config and comm_tiles_per_chunk filled in; the
+ * library's own pick wins unless a candidate is more than 2 % faster).  *ms_best / *ms_default
+ * (either may be NULL) receive the median time per call of the winner and of the library's pick.
+ * Buffers as for flux_gemm_rs / flux_ag_gemm; outputs are overwritten with the (same) result.  The
+ * workspace must hold flux_autotune_workspace_bytes(op, p) bytes (candidates that need more than
+ * workspace_bytes are skipped) and `signals` flux_autotune_signal_count(p) words (signal_count says
+ * how many there are).  `reps` timed samples per candidate (0 = 5).  The call blocks until done and
+ * leaves workspace and signals initialised for *tuned.  Not for use under stream capture.
+ */
+int flux_autotune_rs(const flux_problem_t* p, const void* A, const void* B,
+                     const void* const* peer_partials, void* const* out_slices,
+                     void* workspace, size_t workspace_bytes, void* stream, int32_t reps,
+                     flux_problem_t* tuned, float* ms_best, float* ms_default);
+int flux_autotune_ag(const flux_problem_t* p, const void* const* A_chunks, void* A_agg, const void* B, void* C,
+                     uint32_t* signals, int32_t signal_count, const int32_t* arrival_order,
+                     void* workspace, size_t workspace_bytes, void* compute_stream, void* copy_stream,
+                     int32_t reps, flux_problem_t* tuned, float* ms_best, float* ms_default);
+size_t flux_autotune_workspace_bytes(int op, const flux_problem_t* p);
+int flux_autotune_signal_count(const flux_problem_t* p);
+
+/*
  * How a call would cut K: the first *full_tiles tiles in TileCoord order are computed by one
  * workgroup each, the remaining *split_tiles tiles by *split_k workgroups each (a uniform split has
  * full_tiles = 0; no split has split_k = 1 and split_tiles = all tiles).  The grid has

@@ -33,6 +33,7 @@ EXPORTS = [
     "flux_tile_config_info", "flux_default_order", "flux_status_string", "flux_last_hip_error",
     "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan", "flux_gemm_ref_chunked",
     "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
+    "flux_autotune_rs", "flux_autotune_ag", "flux_autotune_workspace_bytes", "flux_autotune_signal_count",
 ]
 
 
@@ -75,6 +76,12 @@ def lib():
         L.flux_rs_reduce_slice.argtypes = [pp, pvp, vp, vp]
         L.flux_rs_reduce_slice.restype = C.c_int
         L.flux_chunked_workspace_bytes.restype = C.c_size_t
+        pf = C.POINTER(C.c_float)
+        L.flux_autotune_rs.argtypes = [pp, vp, vp, pvp, pvp, vp, C.c_size_t, vp, C.c_int32, pp, pf, pf]
+        L.flux_autotune_ag.argtypes = [pp, pvp, vp, vp, vp, vp, C.c_int32, pi32, vp, C.c_size_t, vp, vp, C.c_int32, pp, pf, pf]
+        L.flux_autotune_workspace_bytes.argtypes = [C.c_int, pp]
+        L.flux_autotune_workspace_bytes.restype = C.c_size_t
+        L.flux_autotune_signal_count.argtypes = [pp]
         L.flux_workspace_bytes.argtypes = [C.c_int, pp]
         L.flux_workspace_bytes.restype = C.c_size_t
         L.flux_init_buffers.argtypes = [C.c_int, pp, vp, C.c_size_t, vp, vp]
@@ -179,6 +186,35 @@ def flux_gemm_ref_chunked(op, p, A=None, A_chunks=None, A_agg=None, B=None, peer
 
 def flux_rs_reduce_slice(p, staged, out, stream=None):
     _check(lib().flux_rs_reduce_slice(C.byref(p), _ptr_list(staged), _ptr(out), _stream(stream)), "flux_rs_reduce_slice")
+
+
+def flux_autotune_workspace_bytes(op, p) -> int:
+    return int(lib().flux_autotune_workspace_bytes(op, C.byref(p)))
+
+
+def flux_autotune_signal_count(p) -> int:
+    return int(lib().flux_autotune_signal_count(C.byref(p)))
+
+
+def flux_autotune_rs(p, A, B, peer_partials, out_slices, workspace=None, stream=None, reps=0):
+    """Returns (tuned problem, ms of the winner, ms of the library's own pick)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tuned, best, default = flux_problem_t(), C.c_float(), C.c_float()
+    _check(lib().flux_autotune_rs(C.byref(p), _ptr(A), _ptr(B), _ptr_list(peer_partials), _ptr_list(out_slices),
+                                  _ptr(workspace), ws_bytes, _stream(stream), reps, C.byref(tuned), C.byref(best),
+                                  C.byref(default)), "flux_autotune_rs")
+    return tuned, best.value, default.value
+
+
+def flux_autotune_ag(p, A_chunks, A_agg, B, Cout, signals, arrival_order, workspace, compute_stream, copy_stream, reps=0):
+    """Returns (tuned problem, ms of the winner, ms of the library's own pick)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tuned, best, default = flux_problem_t(), C.c_float(), C.c_float()
+    _check(lib().flux_autotune_ag(C.byref(p), _ptr_list(A_chunks), _ptr(A_agg), _ptr(B), _ptr(Cout), _ptr(signals),
+                                  signals.numel(), _i32_list(arrival_order), _ptr(workspace), ws_bytes,
+                                  _stream(compute_stream), _stream(copy_stream), reps, C.byref(tuned), C.byref(best),
+                                  C.byref(default)), "flux_autotune_ag")
+    return tuned, best.value, default.value
 
 
 def flux_chunked_workspace_bytes(op, p) -> int:

@@ -999,3 +999,173 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+// tuner (Sec. 4.4; communication tile size: Sec. 4.3)
+// ------------------------------------------------------------------------------------------
+namespace {
+
+struct Candidate { int32_t tile_config, ctpc; };
+
+// Every tile configuration that accepts the shape; for AllGather each with the communication tile
+// halved from the chunk down to the GEMM tile height (Sec. 4.3), at most 8 tiles per chunk.
+std::vector<Candidate> tune_candidates(int op, const flux_problem_t* p) {
+  std::vector<Candidate> out;
+  const int S = p->M / p->R;
+  for (int cfg = 1; cfg <= NUM_CFGS; ++cfg) {
+    flux_problem_t q = *p;
+    q.tile_config = cfg;
+    q.split_k = 0;
+    q.comm_tiles_per_chunk = 0;
+    Plan pl;
+    if (make_plan(op, &q, &pl) != FLUX_OK) continue;
+    out.push_back({cfg, 1});
+    if (op != FLUX_OP_AG) continue;
+    for (int t = 2; t <= 8; t *= 2) {
+      if (S % t != 0 || S / t < pl.bm || p->R * t > MAX_COMM_TILES) break;
+      out.push_back({cfg, t});
+    }
+  }
+  return out;
+}
+
+struct TuneBuffers {
+  const void* A; const void* const* A_chunks; void* A_agg; const void* B;
+  const void* const* peers; void* const* outs; void* C; uint32_t* signals; const int32_t* arrival;
+  void* ws; size_t ws_bytes; void* cs; void* xs;
+};
+
+int tune_call(int op, const flux_problem_t* q, const TuneBuffers& b) {
+  if (op == FLUX_OP_RS) return flux_gemm_rs(q, b.A, b.B, b.peers, b.outs, b.ws, b.ws_bytes, b.cs);
+  return flux_ag_gemm(q, b.A_chunks, b.A_agg, b.B, b.C, b.signals, b.arrival, b.ws, b.ws_bytes, b.cs, b.xs);
+}
+
+// median time per call in ms of `reps` samples, each a batch of back-to-back calls long enough to time
+int tune_time(int op, const flux_problem_t* q, const TuneBuffers& b, int reps, hipEvent_t e0, hipEvent_t e1, float* ms_out) {
+  hipStream_t cs = static_cast<hipStream_t>(b.cs);
+  int st = flux_init_buffers(op, q, b.ws, b.ws_bytes, op == FLUX_OP_AG ? b.signals : nullptr, b.cs);
+  if (st != FLUX_OK) return st;
+  int batch = 1;
+  std::vector<float> samples;
+  for (int r = -2; r < reps; ++r) {          // two warm-up samples; the first also sizes the batch
+    FLUX_HIP(hipEventRecord(e0, cs));
+    for (int i = 0; i < batch; ++i) {
+      st = tune_call(op, q, b);
+      if (st != FLUX_OK) return st;
+    }
+    FLUX_HIP(hipEventRecord(e1, cs));
+    FLUX_HIP(hipEventSynchronize(e1));
+    float ms = 0.f;
+    FLUX_HIP(hipEventElapsedTime(&ms, e0, e1));
+    if (b.ws != nullptr && op == FLUX_OP_AG) {
+      int32_t code = 0, detail = 0;
+      st = flux_query_status(b.ws, &code, &detail);
+      if (st != FLUX_OK) return st;
+      if (code != FLUX_OK) return code;
+    }
+    if (r == -2) batch = std::max(2, std::min(32, (int)(2.0f / std::max(ms, 1e-3f))));   // samples of about 2 ms, calls back to back
+    else if (r >= 0) samples.push_back(ms / (float)batch);
+  }
+  std::sort(samples.begin(), samples.end());
+  *ms_out = samples[samples.size() / 2];
+  return FLUX_OK;
+}
+
+int tune(int op, const flux_problem_t* p, const TuneBuffers& b, int reps, flux_problem_t* tuned, float* ms_best,
+         float* ms_default) {
+  if (p == nullptr || tuned == nullptr) return FLUX_ERR_INVALID_ARG;
+  if (reps <= 0) reps = 5;
+  reps = std::min(reps, 100);
+  Plan pl;
+  int st = make_plan(op, p, &pl);
+  if (st != FLUX_OK) return st;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  FLUX_HIP(hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return FLUX_ERR_HIP; }
+  flux_problem_t base = *p;        // what the library picks by itself
+  base.tile_config = 0; base.split_k = 0; base.comm_tiles_per_chunk = 0;
+  float t_default = 0.f;
+  st = tune_time(op, &base, b, reps, e0, e1, &t_default);
+  flux_problem_t best = base;
+  float t_best = t_default;
+  if (st == FLUX_OK) {
+    for (const Candidate& c : tune_candidates(op, p)) {
+      flux_problem_t q = base;
+      q.tile_config = c.tile_config;
+      q.comm_tiles_per_chunk = c.ctpc;
+      if (flux_workspace_bytes(op, &q) > b.ws_bytes) continue;     // the caller's workspace does not hold this one
+      float t = 0.f;
+      const int sc = tune_time(op, &q, b, reps, e0, e1, &t);
+      if (sc == FLUX_ERR_HIP) { st = sc; break; }
+      if (sc != FLUX_OK) continue;                                  // e.g. timed out: not a candidate
+      if (t < t_best * 0.98f) { t_best = t; best = q; }             // the library's own pick wins ties
+    }
+  }
+  if (st == FLUX_OK) {
+    // the library's pick once more, now that clocks and caches are where the candidates found them
+    float t_again = 0.f;
+    st = tune_time(op, &base, b, reps, e0, e1, &t_again);
+    if (st == FLUX_OK && t_again < t_default) {
+      t_default = t_again;
+      if (best.tile_config == 0 && best.comm_tiles_per_chunk == 0) t_best = t_again;
+      else if (t_best >= t_default * 0.98f) { best = base; t_best = t_default; }
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (st != FLUX_OK) return st;
+  // leave the buffers ready for calls with the tuned problem
+  st = flux_init_buffers(op, &best, b.ws, b.ws_bytes, op == FLUX_OP_AG ? b.signals : nullptr, b.cs);
+  if (st != FLUX_OK) return st;
+  FLUX_HIP(hipStreamSynchronize(static_cast<hipStream_t>(b.cs)));
+  *tuned = best;
+  if (ms_best) *ms_best = t_best;
+  if (ms_default) *ms_default = t_default;
+  return FLUX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t flux_autotune_workspace_bytes(int op, const flux_problem_t* p) {
+  if (p == nullptr) return 0;
+  flux_problem_t base = *p;
+  base.tile_config = 0; base.split_k = 0; base.comm_tiles_per_chunk = 0;
+  size_t need = flux_workspace_bytes(op, &base);
+  for (const Candidate& c : tune_candidates(op, p)) {
+    flux_problem_t q = base;
+    q.tile_config = c.tile_config;
+    q.comm_tiles_per_chunk = c.ctpc;
+    need = std::max(need, flux_workspace_bytes(op, &q));
+  }
+  return need;
+}
+
+int flux_autotune_signal_count(const flux_problem_t* p) {
+  if (p == nullptr || p->R < 1) return 0;
+  int t_max = 1;
+  for (const Candidate& c : tune_candidates(FLUX_OP_AG, p)) t_max = std::max(t_max, (int)c.ctpc);
+  return p->R * t_max;
+}
+
+int flux_autotune_rs(const flux_problem_t* p, const void* A, const void* B, const void* const* peer_partials,
+                     void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream, int32_t reps,
+                     flux_problem_t* tuned, float* ms_best, float* ms_default) {
+  TuneBuffers b{};
+  b.A = A; b.B = B; b.peers = peer_partials; b.outs = out_slices; b.ws = workspace; b.ws_bytes = workspace_bytes; b.cs = stream;
+  return tune(FLUX_OP_RS, p, b, reps, tuned, ms_best, ms_default);
+}
+
+int flux_autotune_ag(const flux_problem_t* p, const void* const* A_chunks, void* A_agg, const void* B, void* C,
+                     uint32_t* signals, int32_t signal_count, const int32_t* arrival_order, void* workspace,
+                     size_t workspace_bytes, void* compute_stream, void* copy_stream, int32_t reps,
+                     flux_problem_t* tuned, float* ms_best, float* ms_default) {
+  if (p == nullptr || signals == nullptr || signal_count < flux_autotune_signal_count(p)) return FLUX_ERR_INVALID_ARG;
+  TuneBuffers b{};
+  b.A_chunks = A_chunks; b.A_agg = A_agg; b.B = B; b.C = C; b.signals = signals; b.arrival = arrival_order;
+  b.ws = workspace; b.ws_bytes = workspace_bytes; b.cs = compute_stream; b.xs = copy_stream;
+  return tune(FLUX_OP_AG, p, b, reps, tuned, ms_best, ms_default);
+}
+
+}  // extern "C"

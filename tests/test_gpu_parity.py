@@ -591,3 +591,58 @@ def test_rs_write_only_then_slice_reduce(cfg, dt):
         gh.assert_close(out, total, dt, "slice reduce")
         if ints:
             gh.assert_bits_equal(out, fo.reduce_slice(staged_ref, dt, dt)[1], "slice reduce, integers")
+
+
+@pytest.mark.parametrize("shape", [dict(M=1024, N=1024, K=512), dict(M=64, N=1024, K=2048)])
+def test_autotune_returns_a_problem_that_still_matches_the_oracle(shape):
+    """The tuner times every tile configuration (and, for the AllGather, the communication tile sizes)
+    on the caller's buffers; whatever it returns must give the oracle's result, be no slower than the
+    library's own pick by its own measurement, and leave workspace and signals ready for use."""
+    # GEMM-ReduceScatter
+    w = fi.scaled(W["c3_rs"], **shape)
+    rank = 4
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    s64, _ = gh.oracle_rs(w, rank, A, B, peers)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype)
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
+    outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
+    n = fb.flux_autotune_workspace_bytes(fb.FLUX_OP_RS, p)
+    ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=gh.DEV) if n else None
+    _say("autotune rs", shape)
+    tuned, best, default = fb.flux_autotune_rs(p, dA, dB, dpeers, outs, ws, reps=3)
+    assert 0 < best <= default
+    assert 0 <= tuned.tile_config <= fb.lib().flux_tile_config_count()
+    for o in outs:
+        o.fill_(float("nan"))
+    fb.flux_gemm_rs(tuned, dA, dB, dpeers, outs, ws)
+    torch.cuda.synchronize()
+    for r in range(w.R):
+        gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+    # AllGather-GEMM
+    wa = fi.scaled(W["c2_ag"], **shape)
+    chunks, Ba, arrival = fi.make_ag_inputs(wa, rank)
+    C64, _ = gh.oracle_ag(wa, chunks, Ba)
+    pa = fb.problem(wa.M, wa.N, wa.K, wa.R, rank, "bf16", wa.out_dtype, spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS)
+    dchunks = [c.to(gh.DEV) for c in chunks]
+    dBa = Ba.to(gh.DEV)
+    A_agg = torch.full((wa.M, wa.K), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    Cout = torch.full((wa.M, wa.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    signals = torch.zeros(fb.flux_autotune_signal_count(pa), dtype=torch.int32, device=gh.DEV)
+    wsa = torch.zeros(fb.flux_autotune_workspace_bytes(fb.FLUX_OP_AG, pa) // 4 + 1, dtype=torch.int32, device=gh.DEV)
+    copy = torch.cuda.Stream()
+    _say("autotune ag", shape)
+    tuned_a, best_a, default_a = fb.flux_autotune_ag(pa, dchunks, A_agg, dBa, Cout, signals, arrival, wsa,
+                                                     torch.cuda.current_stream(), copy, reps=3)
+    assert 0 < best_a <= default_a
+    ctpc = max(1, tuned_a.comm_tiles_per_chunk)
+    assert signals.cpu().tolist()[:wa.R * ctpc] == [1 if i // ctpc == rank else 0 for i in range(wa.R * ctpc)]
+    A_agg.fill_(float("nan"))
+    Cout.fill_(float("nan"))
+    fb.flux_ag_gemm(tuned_a, dchunks, A_agg, dBa, Cout, signals, arrival, wsa, torch.cuda.current_stream(), copy)
+    torch.cuda.synchronize()
+    assert fb.flux_query_status(wsa) == (fb.FLUX_OK, 0)
+    gh.assert_close(Cout, C64, wa.out_dtype)
+    with pytest.raises(fb.FluxError):       # too few signal words for the finest communication tile
+        fb.flux_autotune_ag(pa, dchunks, A_agg, dBa, Cout, signals[:wa.R - 1], arrival, wsa,
+                            torch.cuda.current_stream(), copy, reps=1)

@@ -183,3 +183,22 @@ def test_tile_choice_follows_how_well_the_grid_fills_the_chip():
     assert tile(1024, 8192, 3584) == (256, 128)      # 128 tiles of 256x256: half the chip
     assert tile(2048, 8192, 3584) == (256, 256)      # exactly one round
     assert tile(512, 6144, 12288)[0] in (128, 256) and tile(512, 6144, 12288) != (256, 256)
+
+
+def test_autotune_sizes_cover_every_candidate():
+    """Host side of the tuner: the workspace it asks for holds every candidate's, the signal count
+    covers the finest communication tile (chunk height halved down to the tile height, at most 8)."""
+    p = fb.problem(8192, 4608, 12288, 8, 2)
+    need = fb.flux_autotune_workspace_bytes(fb.FLUX_OP_AG, p)
+    for cfg in range(1, fb.lib().flux_tile_config_count() + 1):
+        for ctpc in (1, 2, 4):
+            q = fb.problem(8192, 4608, 12288, 8, 2, tile_config=cfg, comm_tiles_per_chunk=ctpc)
+            if q.M // q.R // ctpc < fb.flux_tile_shape(fb.FLUX_OP_AG, q).tile_m:
+                continue
+            assert fb.flux_workspace_bytes(fb.FLUX_OP_AG, q) <= need
+    # chunk = 1024 rows; 32-row tiles allow 8 communication tiles per chunk, the cap
+    assert fb.flux_autotune_signal_count(p) == 8 * 8
+    # decode: the chunk (8 rows) is below every tile height, one signal per chunk
+    assert fb.flux_autotune_signal_count(fb.problem(64, 3584, 8192, 8, 2)) == 8
+    assert fb.flux_autotune_workspace_bytes(fb.FLUX_OP_RS, fb.problem(64, 8192, 3584, 8, 2)) >= \
+        fb.flux_workspace_bytes(fb.FLUX_OP_RS, fb.problem(64, 8192, 3584, 8, 2))
