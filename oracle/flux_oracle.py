@@ -286,6 +286,24 @@ def gemm_scatter(A, B, R: int, out_dtype: str, ab_dtype: str = BF16):
     return slices64, [round_to(s, out_dtype) for s in slices64]
 
 
+def gemm_reduce_into(A, B, held, R: int, ab_dtype: str = BF16):
+    """GEMM with the Reduce branch of Alg. 1 carried out by additions on the destination (Sec. 4.2,
+    "Reduce", first form): `held[r]` is what slice r, an fp32 array [M/R, N], holds before the call
+    (the other ranks' contributions so far, or zeros); afterwards it holds that plus the rows of
+    this rank's A.B that the slice owns.  Returns (slices64, slices_f32)."""
+    full = gemm_f64(A, B, ab_dtype)
+    S = slice_rows(full.shape[0], R)
+    if len(held) != R:
+        raise ValueError("need one held slice per rank")
+    slices64 = []
+    for r in range(R):
+        h = to_f64(held[r], F32)
+        if h.shape != (S, full.shape[1]):
+            raise ValueError("held slice has the wrong shape")
+        slices64.append(h + full[r * S:(r + 1) * S, :])
+    return slices64, [round_to(s, F32) for s in slices64]
+
+
 def reduce_slice(staged, staged_dtype: str, out_dtype: str):
     """The local reduction that follows the AlltoAll (Sec. 3.1): `staged` holds, for one slice, the
     R partial results [M/R, N] the R ranks wrote for it (in `staged_dtype`); the slice is their sum,

@@ -242,3 +242,43 @@ def test_reduce_slice_rounds_once():
     total, rounded = fo.reduce_slice(vals, "bf16", "bf16")
     assert total[0, 0] == 259.0
     assert fo.to_f64(rounded, "bf16")[0, 0] == 260.0      # 259 = 258 + 1 is a tie of (258, 260): even significand wins
+
+
+def test_reduce_by_additions_on_the_destination():
+    """Reduce branch carried out on the destination (Sec. 4.2, "Reduce", first form): every rank adds
+    its partial product into the slices, starting from zeros.  On integer inputs, after all R ranks
+    (in any order) the slices are exactly the unsharded GEMM over the concatenated K; after one rank
+    they are its Write-branch scatter; and adding onto the sum of the peers' partials gives what the
+    pull form of the Reduce branch gives.  A dropped term, a wrong slice or a wrong row range fails."""
+    rng = np.random.default_rng(33)
+    M, N, Kr, R = 12, 5, 7, 3
+    S = M // R
+    As = [rand_int(rng, (M, Kr), 2) for _ in range(R)]
+    Bs = [rand_int(rng, (Kr, N), 2) for _ in range(R)]
+    unsharded = np.concatenate(As, axis=1).astype(np.int64) @ np.concatenate(Bs, axis=0).astype(np.int64)
+    zeros = [np.zeros((S, N), dtype=np.float32) for _ in range(R)]
+    # one rank onto zeros = its scatter; brute force for one element
+    _, after0 = fo.gemm_reduce_into(bf16(As[0]), bf16(Bs[0]), zeros, R)
+    _, scat0 = fo.gemm_scatter(bf16(As[0]), bf16(Bs[0]), R, "f32")
+    for r in range(R):
+        assert np.array_equal(after0[r], scat0[r])
+    assert float(after0[2][1, 3]) == float(sum(int(As[0][2 * S + 1, k]) * int(Bs[0][k, 3]) for k in range(Kr)))
+    # all ranks, two different orders
+    for order in ((0, 1, 2), (2, 0, 1)):
+        held = zeros
+        for j in order:
+            _, held = fo.gemm_reduce_into(bf16(As[j]), bf16(Bs[j]), held, R)
+        for r in range(R):
+            assert np.array_equal(held[r].astype(np.int64), unsharded[r * S:(r + 1) * S])
+    # onto the peers' sum = the pull form seen from rank 1
+    partials = [fo.partial_of(bf16(a), bf16(b), "f32") for a, b in zip(As, Bs)]
+    peers_sum = [sum(fo.to_f64(partials[j], "f32")[r * S:(r + 1) * S] for j in range(R) if j != 1).astype(np.float32)
+                 for r in range(R)]
+    s64_add, _ = fo.gemm_reduce_into(bf16(As[1]), bf16(Bs[1]), peers_sum, R)
+    s64_pull, _ = fo.gemm_rs(bf16(As[1]), bf16(Bs[1]), [None if j == 1 else partials[j] for j in range(R)], R, 1, "f32", "f32")
+    for r in range(R):
+        assert np.array_equal(s64_add[r], s64_pull[r])
+    with pytest.raises(ValueError):
+        fo.gemm_reduce_into(bf16(As[0]), bf16(Bs[0]), zeros[:2], R)
+    with pytest.raises(ValueError):
+        fo.gemm_reduce_into(bf16(As[0]), bf16(Bs[0]), [z[:1] for z in zeros], R)
