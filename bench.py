@@ -148,6 +148,18 @@ def main() -> int:
             fb.flux_gemm_rs(self.p_wo, self.A, self.B, None, self.outs, self.ws, compute)
             fb.flux_rs_reduce_slice(self.p_wo, self.staged, self.own, compute)
 
+        def atomic_flavour(self):
+            # Reduce by fp32 atomic additions into the owners' slices (Sec. 4.2, first form of Reduce)
+            if not hasattr(self, "p_at"):
+                w = self.w
+                self.p_at = fb.problem(w.M, w.N, w.K, w.R, self.rank, "f32", "f32", flags=fb.FLUX_FLAG_RS_ATOMIC)
+                self.outs_f32 = [torch.zeros((w.S, w.N), dtype=torch.float32, device=dev) for _ in range(w.R)]
+                n = fb.flux_workspace_bytes(fb.FLUX_OP_RS, self.p_at)
+                self.ws_at = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev) if n else None
+                if self.ws_at is not None:
+                    fb.flux_init_buffers(fb.FLUX_OP_RS, self.p_at, self.ws_at)
+            fb.flux_gemm_rs(self.p_at, self.A, self.B, None, self.outs_f32, self.ws_at, compute)
+
         def alg_bytes(self):
             w = self.w
             ps = 2 if w.partial_dtype == "bf16" else 4
@@ -195,6 +207,7 @@ def main() -> int:
             ks.append(k0.elapsed_ms(k1))
         t_k = statistics.median(ks)
         t_a2a = time_calls(op.alltoall_flavour, reps, warm) if hasattr(op, "alltoall_flavour") else None
+        t_atomic = time_calls(op.atomic_flavour, reps, warm) if hasattr(op, "atomic_flavour") else None
         # the same fused call recorded once in a HIP graph (8 calls per graph) and replayed: what a
         # serving loop that cannot afford per-call launch work would run
         t_graph = None
@@ -214,6 +227,8 @@ def main() -> int:
         more = {} if t_a2a is None else {"ms_write_only_plus_slice_reduce": round(t_a2a, 4)}
         if t_graph is not None:
             more["ms_fused_graph_replay"] = round(t_graph, 4)
+        if t_atomic is not None:
+            more["ms_atomic_reduce_f32"] = round(t_atomic, 4)
         return {**more, "ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
                 "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4), "ms_chunked": round(t_chk, 4),
                 "overlap_efficiency_chunked": None if ect_no <= 0 else round(1.0 - (t_chk - t_gemm) / ect_no, 4),

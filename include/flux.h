@@ -76,6 +76,12 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
                                         A.B is converted and stored into its owner's slice (the AlltoAll
                                         flavour of Sec. 3.1; flux_rs_reduce_slice is the reduction after it) */
 
+#define FLUX_FLAG_RS_ATOMIC 0x80u     /* flux_gemm_rs: Reduce by atomic additions (Sec. 4.2, "Reduce", first form): no
+                                        peers are read; each element of A.B is added, with one fp32 atomic
+                                        addition, to its owner's slice, which holds what the other ranks have
+                                        added so far (or zeros).  out_dtype must be FLUX_F32 (the paper, too,
+                                        applies this form to selected data types only). */
+
 #define FLUX_FLAG_AG_ABSENT_OWNERS 0x40u /* flux_ag_gemm without a copy kernel: share the pieces out over twice as
                                         many workgroups as the grid has, so that every second piece has an
                                         owner that never runs and is taken over by a workgroup that waits for
@@ -110,10 +116,10 @@ typedef struct flux_problem {
 /*
  * GEMM-ReduceScatter, fused (Alg. 1 with the Reduce branch).
  *   A, B            device, bf16, [M,K] and [K,N].
- *   peer_partials   (NULL allowed with FLUX_FLAG_RS_WRITE_ONLY) host array [R] of device pointers to [M,N] matrices of partial_dtype;
+ *   peer_partials   (NULL allowed with FLUX_FLAG_RS_WRITE_ONLY / FLUX_FLAG_RS_ATOMIC) host array [R] of device pointers to [M,N] matrices of partial_dtype;
  *                   entry [rank] is ignored (may be NULL).
  *   out_slices      host array [R] of device pointers to [M/R,N] matrices of out_dtype, all
- *                   written (every element exactly once).
+ *                   written (every element exactly once; with FLUX_FLAG_RS_ATOMIC: added to).
  *   workspace       device, >= flux_workspace_bytes(FLUX_OP_RS, p) bytes (may be NULL if 0),
  *                   initialised once with flux_init_buffers.
  */

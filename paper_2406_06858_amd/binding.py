@@ -24,6 +24,7 @@ FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY = 0x1, 0x2, 
 FLUX_FLAG_NO_TAIL_SPLIT = 0x10
 FLUX_FLAG_RS_WRITE_ONLY = 0x20
 FLUX_FLAG_AG_ABSENT_OWNERS = 0x40
+FLUX_FLAG_RS_ATOMIC = 0x80
 FLUX_PHASE_GEMM, FLUX_PHASE_COMM = 0x1, 0x2
 FLUX_MAX_RANKS = 16
 

@@ -659,7 +659,9 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   Plan pl;
   int st = make_plan(FLUX_OP_RS, p, &pl);
   if (st != FLUX_OK) return st;
-  const bool write_only = p->flags & FLUX_FLAG_RS_WRITE_ONLY;
+  const bool atomic = p->flags & FLUX_FLAG_RS_ATOMIC;
+  if (atomic && ((p->flags & FLUX_FLAG_RS_WRITE_ONLY) || p->out_dtype != FLUX_F32)) return FLUX_ERR_UNSUPPORTED;
+  const bool write_only = (p->flags & FLUX_FLAG_RS_WRITE_ONLY) || atomic;   // neither form reads peers
   if (!A || !B || (!peer_partials && !write_only) || !out_slices || !aligned16(A) || !aligned16(B)) return FLUX_ERR_INVALID_ARG;
   for (int r = 0; r < p->R; ++r) {
     if (!out_slices[r] || !aligned16(out_slices[r])) return FLUX_ERR_INVALID_ARG;
@@ -673,7 +675,7 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   a.A = static_cast<const __bf16*>(A);
   a.B = static_cast<const __bf16*>(B);
   // the kernel wants the R-1 peers packed, ascending rank
-  a.write_only = write_only;
+  a.write_only = atomic ? 2 : (write_only ? 1 : 0);
   for (int r = 0, j = 0; r < p->R; ++r) {
     a.outs[r] = out_slices[r];
     if (!write_only && r != p->rank) a.peers[j++] = peer_partials[r];

@@ -75,7 +75,8 @@ struct GemmArgs {
   const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
   void* outs[FLUX_MAX_RANKS];
   int32_t R, rank, S;        // S = M / R
-  int32_t write_only;        // reduce-scatter epilogue without the reduction (Write branch of Alg. 1)
+  int32_t write_only;        // 1: reduce-scatter epilogue without the reduction (Write branch of Alg. 1);
+                             // 2: no peers are read, the tile is added to the slice with atomic additions
   int32_t partial_f32, out_f32;
   // all-gather prologue
   uint32_t* signals;
@@ -643,6 +644,42 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   return ok;
 }
 
+// Reduce by atomic additions on device memory (Sec. 4.2, "Reduce", first form): the owner's fp32 slice
+// already holds what the other ranks have added; every element of the tile is added to it with one
+// hardware addition that returns nothing.  The lanes of an instruction take consecutive columns of a
+// row, so that an instruction touches two whole cache lines and not sixteen partial ones (with the
+// eight-columns-per-lane layout of the other epilogues this form took five times as long).
+template <class C, bool EDGE>
+__device__ __forceinline__ void epilogue_all_atomic(const GemmArgs& a, void* const* lds_outs, float* ep, f32x16 (&acc)[C::MI][C::NI],
+                                                    int m0, int n0, int lane, int wm, int wn) {
+  constexpr int W = C::WTN < 64 ? C::WTN : 64;   // columns per instruction
+  constexpr int RPI = 64 / W;                    // rows per instruction
+  const int c_in = lane % W, r_in = lane / W;
+#pragma unroll
+  for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        ep[r * C::EP_STRIDE + ni * 32 + (lane & 31)] = acc[mi][ni][e];
+      }
+    __builtin_amdgcn_wave_barrier();
+    for (int r0 = 0; r0 < 32; r0 += RPI) {
+      const int r = r0 + r_in;
+      const int gm = m0 + wm * C::WTM + mi * 32 + r;
+      const int owner = gm / a.S;
+      float* row = static_cast<float*>(lds_outs[owner]) + (size_t)(gm - owner * a.S) * a.N + n0 + wn * C::WTN;
+#pragma unroll
+      for (int c0 = 0; c0 < C::WTN; c0 += W) {
+        const int c = c0 + c_in;
+        if (!EDGE || (gm < a.M && n0 + wn * C::WTN + c < a.N)) unsafeAtomicAdd(row + c, ep[r * C::EP_STRIDE + c]);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 // Everything after the main loop: the split-K hand-over (all but the last-arriving workgroup of
 // a tile park their partial sums, the last one adds them up) and the epilogue, in which the
 // accumulators pass through LDS once (per wave, 32 rows at a time) so that every lane ends up
@@ -719,7 +756,9 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
   // would no longer be kept in registers.  Up to 8 ranks, 7 peer loads per piece are issued, else 15:
   // loads from absent peers return zeros but still cost an issue slot and four registers each.)
   constexpr int NP_ALL = FLUX_MAX_RANKS - 1, NP_8 = 7;
-  if (EPI != EPI_RS || a.write_only) {
+  if (EPI == EPI_RS && a.write_only == 2) {
+    epilogue_all_atomic<C, EDGE>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  } else if (EPI != EPI_RS || a.write_only) {
     epilogue_all<C, EPI, EDGE, false, 2, 0>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
   } else if (a.R <= NP_8 + 1) {
     if (a.partial_f32) epilogue_all<C, EPI, EDGE, true, 1, NP_8>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);

@@ -646,3 +646,58 @@ def test_autotune_returns_a_problem_that_still_matches_the_oracle(shape):
     with pytest.raises(fb.FluxError):       # too few signal words for the finest communication tile
         fb.flux_autotune_ag(pa, dchunks, A_agg, dBa, Cout, signals[:wa.R - 1], arrival, wsa,
                             torch.cuda.current_stream(), copy, reps=1)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 4, 7])
+def test_rs_reduce_by_atomic_additions(cfg):
+    """FLUX_FLAG_RS_ATOMIC: the tile is added to the owner's fp32 slice with atomic additions (Sec. 4.2,
+    "Reduce", first form).  Integer inputs: bit-exact against the oracle, starting from slices that
+    hold other ranks' contributions; a second call adds the product once more; bf16 output is refused."""
+    w = fi.Workload("int_rs_atomic", "rs", 1024 if cfg else 64, 512, 320, 8, a_dist=("int", 2), b_dist=("int", 2),
+                    peer_dist=("int", 4), partial_dtype="f32", out_dtype="f32", seed=91)
+    rank = 6
+    _say("atomic reduce cfg", cfg, "M", w.M)
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    # what the slices hold before the call: the sum of the peers' partials (small integers: exact)
+    held = [sum(fi.to_numpy(peers[j])[r * w.S:(r + 1) * w.S] for j in range(w.R) if j != rank).astype(np.float32)
+            for r in range(w.R)]
+    _, want1 = fo.gemm_reduce_into(fi.to_numpy(A), fi.to_numpy(B), held, w.R)
+    _, want2 = fo.gemm_reduce_into(fi.to_numpy(A), fi.to_numpy(B), want1, w.R)
+    # the pull form of the Reduce branch gives the same slices
+    _, pull = gh.oracle_rs(w, rank, A, B, peers)
+    for r in range(w.R):
+        assert np.array_equal(want1[r], pull[r])
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, "f32", "f32", tile_config=cfg, flags=fb.FLUX_FLAG_RS_ATOMIC)
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    outs = [torch.from_numpy(h.copy()).to(gh.DEV) for h in held]
+    ws = gh.workspace_for(fb.FLUX_OP_RS, p)
+    if ws is not None:
+        fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+    fb.flux_gemm_rs(p, dA, dB, None, outs, ws)
+    torch.cuda.synchronize()
+    for r in range(w.R):
+        gh.assert_bits_equal(outs[r], want1[r], f"first call, slice {r}")
+    fb.flux_gemm_rs(p, dA, dB, None, outs, ws)
+    torch.cuda.synchronize()
+    for r in range(w.R):
+        gh.assert_bits_equal(outs[r], want2[r], f"second call, slice {r}")
+    with pytest.raises(fb.FluxError):
+        fb.flux_gemm_rs(fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", "bf16", flags=fb.FLUX_FLAG_RS_ATOMIC), dA, dB, None,
+                        [o.bfloat16() for o in outs], None)
+
+
+def test_rs_reduce_by_atomic_additions_random_data():
+    w = fi.scaled(W["c3_rs"], M=1024, N=1024, K=768)
+    w = fi.Workload(w.name, "rs", w.M, w.N, w.K, w.R, a_dist=w.a_dist, b_dist=w.b_dist, peer_dist=w.peer_dist,
+                    partial_dtype="f32", out_dtype="f32", seed=w.seed)
+    rank = 3
+    A, B, _ = fi.make_rs_inputs(w, rank)
+    rng = np.random.default_rng(5)
+    held = [rng.standard_normal((w.S, w.N)).astype(np.float32) for _ in range(w.R)]
+    s64, _ = fo.gemm_reduce_into(fi.to_numpy(A), fi.to_numpy(B), held, w.R)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, "f32", "f32", flags=fb.FLUX_FLAG_RS_ATOMIC)
+    outs = [torch.from_numpy(h.copy()).to(gh.DEV) for h in held]
+    fb.flux_gemm_rs(p, A.to(gh.DEV), B.to(gh.DEV), None, outs, gh.workspace_for(fb.FLUX_OP_RS, p))
+    torch.cuda.synchronize()
+    for r in range(w.R):
+        gh.assert_close(outs[r], s64[r], "f32", f"slice {r}")
