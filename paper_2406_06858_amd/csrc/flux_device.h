@@ -1024,10 +1024,11 @@ __device__ __forceinline__ void mma_stage_dma_opaque(const unsigned char* cur_p,
   constexpr int L = DmaLoader<C>::N_INSTR;
   constexpr int GS = (G * 3 + 3) / 4;
   const uint32_t cur = lds_address(cur_p);
-  if constexpr (C::MI * C::NI == 1) {
-    // One MFMA per k-step (the 32x32 wave tiles of the decode configurations): nothing to
-    // hide fragment reads behind, and the tile is bound by memory anyway.  Request the next slab
-    // first, fetch all fragments of this one in one go, wait once.
+  if constexpr (C::MI * C::NI <= 2) {
+    // One or two MFMAs per k-step (the 32x32 and 32x64 wave tiles of the few-row configurations):
+    // too little to hide a k-step's fragment reads behind, so reading step by step pays the LDS
+    // latency four times per slab.  Request the next slab first, fetch all fragments of this one in
+    // one go (48 registers at most), wait once.
     ld.issue(a, nxt, k_next, wave);
     bf16x8 af[KS * C::MI], bfr[KS * C::NI];
 #pragma unroll
@@ -1172,7 +1173,7 @@ __device__ __forceinline__ void barrier_keeping_loads_in_flight() {
 template <class C, int EPI, bool WAIT, bool MASK>
 __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const GemmArgs a) {
   constexpr int NS = C::NSTAGE;
-  static_assert(NS >= 3 && NS <= 6, "3 to 6 stages");
+  static_assert(NS >= 3 && NS <= 9, "3 to 9 stages");
   constexpr int L = DmaLoader<C>::N_INSTR;                  // loads per slab and wave
   static_assert((NS - 2) * L < 64, "outstanding loads must fit the counter");
   // One pool: the stages, and over them (once the main loop is done) the epilogue's staging area.
@@ -1180,8 +1181,9 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
   __shared__ __attribute__((aligned(1024))) unsigned char pool[POOL_BYTES];
   __shared__ int lds_misc[4];
   __shared__ void* lds_outs[FLUX_MAX_RANKS];
-  unsigned char* const st[6] = {pool, pool + C::STAGE_BYTES, pool + 2 * C::STAGE_BYTES, pool + (NS > 3 ? 3 : 0) * C::STAGE_BYTES,
-                                pool + (NS > 4 ? 4 : 0) * C::STAGE_BYTES, pool + (NS > 5 ? 5 : 0) * C::STAGE_BYTES};
+  unsigned char* st[NS];
+#pragma unroll
+  for (int j = 0; j < NS; ++j) st[j] = pool + j * C::STAGE_BYTES;
   unsigned char* const ep_stage = pool;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
