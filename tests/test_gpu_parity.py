@@ -379,10 +379,10 @@ def test_ag_tile_waiting_for_many_signals():
     rank = 1
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
     _, want = gh.oracle_ag(w, chunks, B)
-    for delay in (20_000_000, 0):
-        _say("many signals, delay", delay)
+    for delay, cw in ((20_000_000, 256), (0, 256), (0, 0)):     # copy_workgroups 0: no copy kernel, 64 pieces per owner
+        _say("many signals, delay", delay, "copy_workgroups", cw)
         Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, tile_config=1, comm_tiles_per_chunk=16,
-                                               copy_workgroups=256, delay_copy_cycles=delay, repeat=2)
+                                               copy_workgroups=cw, delay_copy_cycles=delay, repeat=2)
         assert status == (fb.FLUX_OK, 0)
         gh.assert_bits_equal(Cg, want, "C")
         gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
