@@ -39,6 +39,9 @@ def main() -> int:
                     help="counter-collection mode: run N rounds of [chunk copy, AllGather-GEMM kernel on the gathered "
                          "matrix, fused GEMM-ReduceScatter, fused AllGather-GEMM call] and exit (rocprofv3 --pmc runs "
                          "kernels one at a time)")
+    ap.add_argument("--serial-decode", type=int, default=0, metavar="N",
+                    help="counter-collection mode for the few-row shapes: N plain GEMMs (no communication) of each of "
+                         "c5_ag_m8 / _m64 / _m256 over rotating copies of the weight matrix, then exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-config / overlap-efficiency section")
     args = ap.parse_args()
@@ -254,6 +257,17 @@ def main() -> int:
                 "fused_frac_mfma_peak": round(w.flops / t_fus / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
                 "fused_alg_GBs": round(op.alg_bytes() / t_fus / 1e6, 1),
                 "fused_frac_hbm_peak": round(op.alg_bytes() / t_fus / 1e6 / HBM_PEAK_GBS, 4)}
+
+    if args.serial_decode > 0:
+        for name in ("c5_ag_m8", "c5_ag_m64", "c5_ag_m256"):
+            op = AG(W[name], 2)
+            op.rotate_weights(9)
+            for _ in range(args.serial_decode):
+                op.unfused(fb.FLUX_PHASE_GEMM)
+            torch.cuda.synchronize()
+            del op
+        print(json.dumps({"mode": "serial-decode", "launches_per_shape": args.serial_decode}))
+        return 0
 
     # ---- the timed workload: MLP up-projection (AG-GEMM) + down-projection (GEMM-RS) ----
     ag = AG(W["c2_ag"], rank=2, flags=args.ag_flags)
