@@ -379,6 +379,13 @@ def main() -> int:
                         "ms_zero_operands": round(t_zero, 4), "tflops_zero_operands": round(fl / t_zero / 1e9, 1)}
             del Az, Bz, out_
         extra["library_gemm_context"] = lib
+        # Eq. 1-2 once more with GEMM_non-split := the faster of this library's plain kernel and the
+        # vendor library's GEMM on the same operands (the paper takes the fastest GEMM known)
+        for key in ("c2_ag", "c3_rs"):
+            tg = min(extra[key]["ms_gemm_only"], lib[key]["ms_workload_operands"])
+            ect_no = extra[key]["ms_unfused"] - tg
+            extra[key]["overlap_efficiency_vs_fastest_gemm"] = (
+                None if ect_no <= 0 else round(1.0 - (extra[key]["ms_fused"] - tg) / ect_no, 4))
         del ag, rs
         torch.cuda.empty_cache()
         for name in ("c4_ag", "c4_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):
