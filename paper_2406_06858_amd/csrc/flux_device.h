@@ -84,19 +84,19 @@ struct GemmArgs {
   int32_t n_signals, sig_local_lo, sig_local_hi;   // local communication tiles: [lo, hi)
   uint32_t* done_counter;
   uint32_t* started_counter;
-  // cooperative copy: a workgroup that has to wait moves unclaimed pieces of the tile it waits for
-  // (outs[] then holds the chunk sources, A is the gathered matrix); copy_pieces = 0: no copy kernel
+  // the transfer: pieces of communication tiles are claimed and moved by this grid's workgroups
+  // and/or a copy kernel (outs[] then holds the chunk sources, A is the gathered matrix);
+  // copy_pieces = 0: the grid moves nothing and only waits (hipMemcpyAsync driver, or R = 1)
   uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
   uint32_t* copy_counters;   // [n_signals] pieces finished
   uint32_t copy_call_id;     // 0: take the id from copy_call_seq (calls without a copy kernel)
   uint32_t* copy_call_seq;
   int32_t copy_pieces;       // pieces per communication tile
-  int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none, the
-                             // waiting workgroups move everything)
+  int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none)
   int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
   // No driver at all (copy_owner_wgs > 0): piece g (counted over the remote communication tiles in
-  // transfer order, tile j lying in the chunk at position j / ctpc of copy_order4) belongs to workgroup g % copy_owner_wgs of
-  // this grid, which moves it before it looks at its own signals.
+  // transfer order, tile j lying in the chunk at position j / ctpc of copy_order4) belongs to
+  // workgroup g % copy_owner_wgs of this grid, which moves it before it looks at its own signals.
   int32_t copy_owner_wgs;
   int32_t copy_n_tiles;
   unsigned long long copy_order4;   // chunk of position i in bits [4i, 4i+4)
