@@ -885,12 +885,15 @@ struct DmaLoader {
     }
   }
 
-  // all loads of one K-slab for this wave; `stage` is the base of the LDS stage being filled
-  __device__ __forceinline__ void issue(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
+  // this wave's loads of the A part / the B part of one K-slab; `stage` is the base of the LDS stage being filled
+  __device__ __forceinline__ void issue_a(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
 #pragma unroll
     for (int p = 0; p < A_INSTR; ++p)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (p * NW + wave) * 1024), 16, voff_a,
                                                (k0 + p * A_RPI * NW * a.K) * 2, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __device__ __forceinline__ void issue_b(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
 #pragma unroll
     for (int p = 0; p < B_INSTR; ++p)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
@@ -898,6 +901,11 @@ struct DmaLoader {
     // keep the loads where they are written: scheduled late they would be issued just before
     // the wait for them, and nothing would overlap
     __builtin_amdgcn_sched_barrier(0);
+  }
+  // all loads of one K-slab for this wave
+  __device__ __forceinline__ void issue(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
+    issue_a(a, stage, k0, wave);
+    issue_b(a, stage, k0, wave);
   }
 };
 
@@ -1170,6 +1178,20 @@ __device__ __forceinline__ void barrier_keeping_loads_in_flight() {
 
 // MASK: M is not a multiple of the tile height.  Rows past M are read as zeros (they lie outside
 // the buffer resource of A) and the epilogue leaves them out.
+// Counter wait of the first pass of the deep pipeline when the weights' part of the first slabs
+// was issued ahead of everything else: before slab j is read, at most the A parts of the slabs
+// after it (up to slab NS-2) and the j whole slabs issued since may be outstanding.  `j` is a
+// constant after unrolling; the wait instruction needs its count as an immediate.
+template <int NS, int LA, int L, int J = 0>
+struct FirstPassWait {
+  static __device__ __forceinline__ void run(int j) {
+    if constexpr (J < NS - 1) {
+      if (j == J) wait_vm_at_most<(NS - 2 - J) * LA + J * L>();
+      else FirstPassWait<NS, LA, L, J + 1>::run(j);
+    }
+  }
+};
+
 template <class C, int EPI, bool WAIT, bool MASK>
 __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const GemmArgs a) {
   constexpr int NS = C::NSTAGE;
@@ -1201,14 +1223,35 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
     for (int j = 0; j < FLUX_MAX_RANKS; ++j)
       if (tid == j) lds_outs[j] = a.outs[j];
   }
-  if (WAIT) {
-    const int m1 = (!MASK || m0 + C::BM < a.M) ? m0 + C::BM : a.M;
-    if (!wait_signals(a, m0, m1, lds_misc, lds_outs)) return;
-  }
-
   const int k_begin = is_split ? split * a.k_per_split : 0;
   const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
   const int KT = (k_end - k_begin) / C::BK;
+
+  DmaLoader<C> ld;
+  ld.init(a, m0, n0, wave, lane);
+  // Slabs past the end are replaced by the last one: every step issues the same number of loads,
+  // which keeps the counter wait a constant and the loop one shape.  Such a repeat lands in a
+  // stage whose slab has been consumed, never in the one the last slab is read from.
+  const int last = KT - 1;
+  constexpr int LA = DmaLoader<C>::A_INSTR;
+  if (WAIT) {
+    // The weights do not depend on the gathered rows: their part of the first slabs is on its way
+    // while this workgroup moves its share of the chunks and waits for the signals.  In the first
+    // pass of the loop the order of issue is then [B of slabs 0..NS-2][A of slabs 0..NS-2][slab NS-1]...,
+    // and "slab j has landed" means that at most the A parts after it and j whole slabs are out.
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j) ld.issue_b(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
+    const int m1 = (!MASK || m0 + C::BM < a.M) ? m0 + C::BM : a.M;
+    if (!wait_signals(a, m0, m1, lds_misc, lds_outs)) {
+      wait_vm_at_most<0>();        // nothing of this workgroup is left in flight towards its LDS
+      return;
+    }
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j) ld.issue_a(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
+  } else {
+#pragma unroll
+    for (int j = 0; j < NS - 1; ++j) ld.issue(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
+  }
 
   f32x16 acc[C::MI][C::NI];
 #pragma unroll
@@ -1218,20 +1261,14 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
 
-  DmaLoader<C> ld;
-  ld.init(a, m0, n0, wave, lane);
-  // Slabs past the end are replaced by the last one: every step issues the same number of loads,
-  // which keeps the counter wait a constant and the loop one shape.  Such a repeat lands in a
-  // stage whose slab has been consumed, never in the one the last slab is read from.
-  const int last = KT - 1;
-#pragma unroll
-  for (int j = 0; j < NS - 1; ++j) ld.issue(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
   for (int kt0 = 0; kt0 < KT; kt0 += NS) {
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
       const int kt = kt0 + j;
       if (kt < KT) {
-        wait_vm_at_most<(NS - 2) * L>();     // slab kt has landed (this wave's part of it)
+        // slab kt has landed (this wave's part of it)
+        if (WAIT && j < NS - 1 && kt0 == 0) FirstPassWait<NS, LA, L>::run(j);
+        else wait_vm_at_most<(NS - 2) * L>();
         barrier_keeping_loads_in_flight();   // ... everyone's part; and slab kt-1 has been read by all
         const int kn = kt + NS - 1 < last ? kt + NS - 1 : last;
         mma_stage_dma_opaque<C>(st[j], st[(j + NS - 1) % NS], ld, a, k_begin + kn * C::BK, wave, wm, wn, lane, acc);
