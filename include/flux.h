@@ -169,6 +169,10 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  *   compute_stream  the GEMM kernel's stream; on return of the call it is ordered after the
  *                   GEMM, the copy driver and the signal reset.
  *   copy_stream     the copy driver's stream; must differ from compute_stream.
+ *                   HIP maps streams onto a few hardware queues (GPU_MAX_HW_QUEUES, 4 by default)
+ *                   and a queue hands out its packets in order: if both streams land on one queue
+ *                   the driver and the GEMM run one after the other, correctly but without overlap.
+ *                   Successively created streams go to different queues.
  */
 int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_agg,
                  const void* B, void* C, uint32_t* signals, const int32_t* arrival_order,

@@ -22,8 +22,10 @@ typedef TileCfg<64, 64, 64, 2, 2, 6, 1> Cfg;     // decode, M <= 64: six LDS sta
 typedef TileCfg<32, 128, 64, 1, 4, 6, 1> Cfg;    // decode, M <= 32: six LDS stages
 #elif FLUX_CFG_ID == 9
 typedef TileCfg<64, 128, 64, 2, 2, 4, 1> Cfg;    // M <= 256: four LDS stages
+#elif FLUX_CFG_ID == 10
+typedef TileCfg<64, 128, 64, 2, 2, 3, 2> Cfg;    // EXPERIMENT: 64x128, three stages, two workgroups per CU
 #else
-#error "FLUX_CFG_ID must be 1..9"
+#error "FLUX_CFG_ID must be 1..10"
 #endif
 
 // Shapes the tile divides take a direct-to-LDS kernel (two stages, or the deep pipeline for

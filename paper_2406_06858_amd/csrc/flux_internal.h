@@ -14,7 +14,7 @@ struct CfgInfo {
   hipError_t (*launch)(int epi, int wait, int edge, const GemmArgs& a, int grid, hipStream_t s);
 };
 
-constexpr int NUM_CFGS = 9;
+constexpr int NUM_CFGS = 10;
 extern CfgInfo g_cfgs[NUM_CFGS];
 
 #define FLUX_DECLARE_CFG(ID) \
@@ -29,5 +29,6 @@ FLUX_DECLARE_CFG(6)
 FLUX_DECLARE_CFG(7)
 FLUX_DECLARE_CFG(8)
 FLUX_DECLARE_CFG(9)
+FLUX_DECLARE_CFG(10)
 
 }  // namespace flux

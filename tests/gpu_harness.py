@@ -67,7 +67,7 @@ def run_rs(w: fi.Workload, rank: int, A, B, peers, tile_config=0, split_k=0, fla
 
 def run_ag(w: fi.Workload, rank: int, chunks, B, arrival, tile_config=0, split_k=0, flags=0,
            comm_tiles_per_chunk=0, copy_workgroups=0, local_in_place=False, delay_copy_cycles=0,
-           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1, link_gbps=0):
+           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1, link_gbps=0, copy_stream=None):
     """Fused AllGather-GEMM through the C ABI.  A_agg starts NaN-poisoned so a tile that reads
     rows before their signal shows up in C.  Returns (C, A_agg, signals, status)."""
     p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, tile_config, split_k, flags,
@@ -85,7 +85,7 @@ def run_ag(w: fi.Workload, rank: int, chunks, B, arrival, tile_config=0, split_k
     ws.fill_(-1)
     fb.flux_init_buffers(fb.FLUX_OP_AG, p, ws, signals)
     compute = torch.cuda.current_stream()
-    copy = torch.cuda.Stream()
+    copy = copy_stream if copy_stream is not None else torch.cuda.Stream()
     torch.cuda.synchronize()
     if delay_copy_cycles:
         with torch.cuda.stream(copy):

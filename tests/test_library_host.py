@@ -183,6 +183,12 @@ def test_tile_choice_follows_how_well_the_grid_fills_the_chip():
     assert tile(1024, 8192, 3584) == (256, 128)      # 128 tiles of 256x256: half the chip
     assert tile(2048, 8192, 3584) == (256, 256)      # exactly one round
     assert tile(512, 6144, 12288)[0] in (128, 256) and tile(512, 6144, 12288) != (256, 256)
+    # a few hundred rows over a long K, at most 256 tiles of 64x128: those, two per CU, K cut
+    assert tile(512, 3584, 8192) == (64, 128)
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(512, 3584, 8192, 8, 0)) == (0, 224, 2)
+    assert tile(256, 3584, 8192) == (64, 128)
+    assert tile(512, 8192, 3584)[0] >= 128           # short K: no
+    assert tile(1024, 3584, 8192)[0] >= 128          # 448 tiles: no
 
 
 def test_autotune_sizes_cover_every_candidate():
