@@ -385,6 +385,14 @@ static int check_arrival(const flux_problem_t* p, const int32_t* arrival, int* o
 // (key, index).  ReduceScatter: key = position of the owner of the tile's first row in the
 // ring that starts after the local rank and ends on it.  AllGather: key = latest position, in
 // [local chunk, arrival order...], among the chunks the tile's rows touch.
+static void pack_order(TileMap* tm) {
+  tm->packed = tm->tiles_m <= 16;
+  tm->pad_ = 0;
+  tm->order4 = 0;
+  if (tm->packed)
+    for (int t = 0; t < tm->tiles_m; ++t) tm->order4 |= (uint64_t)tm->m_order[t] << (4 * t);
+}
+
 static void build_tile_map(int op, const flux_problem_t* p, const Plan& pl, const int* arrival, TileMap* tm) {
   tm->tiles_m = pl.tiles_m;
   tm->tiles_n = pl.tiles_n;
@@ -393,6 +401,7 @@ static void build_tile_map(int op, const flux_problem_t* p, const Plan& pl, cons
   if (p->flags & FLUX_FLAG_NO_SWIZZLE) {
     tm->band_h = 1;
     for (int t = 0; t < pl.tiles_m; ++t) tm->m_order[t] = (uint16_t)t;
+    pack_order(tm);
     return;
   }
   tm->band_h = (S % pl.bm == 0) ? S / pl.bm : 1;
@@ -419,6 +428,7 @@ static void build_tile_map(int op, const flux_problem_t* p, const Plan& pl, cons
   }
   std::sort(keyed.begin(), keyed.end());
   for (int t = 0; t < pl.tiles_m; ++t) tm->m_order[t] = (uint16_t)keyed[t].second;
+  pack_order(tm);
 }
 
 static size_t workspace_need(const Plan& pl) {
@@ -721,6 +731,9 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   a.n_signals = p->R * pl.ctpc;
   a.sig_local_lo = p->rank * pl.ctpc;
   a.sig_local_hi = (p->rank + 1) * pl.ctpc;
+  // rows that do not start and end on cache line boundaries may share a line with a row of another
+  // communication tile
+  a.acquire_l2 = (reinterpret_cast<uintptr_t>(A_agg) % 128 != 0) || (((size_t)p->K * 2) % 128 != 0);
   const uint32_t call_id = next_call_id();
   if (pl.copy_help && p->R > 1) {
     a.copy_pieces = pl.copy_pieces;

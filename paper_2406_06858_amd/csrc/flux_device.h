@@ -37,7 +37,14 @@ constexpr size_t WS_COUNTER_OFF = 256;     // uint32 per communication tile (cop
 constexpr int MAX_COMM_TILES = 1024;
 constexpr size_t WS_TILECNT_OFF = WS_COUNTER_OFF + 4 * MAX_COMM_TILES;   // split-K arrival counters
 constexpr int MAX_SPLITK_TILES = 4096;
-constexpr size_t WS_HEADER_BYTES = WS_TILECNT_OFF + 4 * MAX_SPLITK_TILES;
+// Workgroups past their signal wait are counted in two levels: workgroup b adds to leaf b mod
+// DONE_LEAVES, whoever completes a leaf adds to the root (WS_DONE_OFF).  Hundreds of additions to one
+// address queue up behind each other (tens of nanoseconds each), and every workgroup waits for its
+// own to come back.  The leaves lie in different memory channels.
+constexpr int DONE_LEAVES = 32;
+constexpr size_t DONE_LEAF_STRIDE = 256;
+constexpr size_t WS_DONELEAF_OFF = WS_TILECNT_OFF + 4 * MAX_SPLITK_TILES;
+constexpr size_t WS_HEADER_BYTES = WS_DONELEAF_OFF + DONE_LEAVES * DONE_LEAF_STRIDE;
 // After the header: AllGather piece claims (uint32 per communication tile and piece), then the
 // split-K partials.
 constexpr int MAX_COPY_PIECES = 256;       // pieces per communication tile = copy-driver workgroups
@@ -48,8 +55,13 @@ constexpr int MAX_COPY_PIECES = 256;       // pieces per communication tile = co
 // workgroup ids walk that order in bands of `band_h` m-tiles times all n-tiles, m fastest.
 // Workgroups are dealt round-robin to the accelerator dies, so with n_xcd > 1 the in-band index
 // is regrouped to give every die a contiguous run of the band (shared panels stay in its L2).
+// With at most 16 m-tiles the order also sits in `order4`, four bits per position: a kernel then
+// has its tile after the first fetch of its arguments, not after a second, dependent one into the
+// table (about a microsecond at the start of every workgroup).
 struct TileMap {
   int32_t tiles_m, tiles_n, band_h, n_xcd;
+  int32_t packed, pad_;
+  uint64_t order4;
   uint16_t m_order[FLUX_MAX_M_TILES];
 };
 
@@ -60,7 +72,7 @@ __host__ __device__ inline void tile_coord(const TileMap& tm, int block, int& mt
   if (tm.n_xcd > 1 && band_sz % tm.n_xcd == 0) q = (q % tm.n_xcd) * (band_sz / tm.n_xcd) + q / tm.n_xcd;
   const int i = band * tm.band_h + q % tm.band_h;
   nt = q / tm.band_h;
-  mt = tm.m_order[i];
+  mt = tm.packed ? (int)((tm.order4 >> (4 * i)) & 15) : (int)tm.m_order[i];
 }
 
 enum : int { EPI_PLAIN = 0, EPI_RS = 1 };
@@ -94,6 +106,7 @@ struct GemmArgs {
   int32_t copy_pieces;       // pieces per communication tile
   int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none)
   int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
+  int32_t acquire_l2;        // the gathered rows may share cache lines across communication tiles: full acquire after the wait
   // No driver at all (copy_owner_wgs > 0): piece g (counted over the remote communication tiles in
   // transfer order, tile j lying in the chunk at position j / ctpc of copy_order4) belongs to
   // workgroup g % copy_owner_wgs of this grid, which moves it before it looks at its own signals.
@@ -627,9 +640,27 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
     __syncthreads();                    // lds[1], lds[2] are rewritten in the next round
   }
   if (tid == 0) {
-    __atomic_thread_fence(__ATOMIC_ACQUIRE);   // system scope: covers copy kernels and DMA writers
-    const uint32_t prev = atomicAdd(a.done_counter, 1u);
-    if (prev == gridDim.x - 1) {
+    // Acquire.  The rows were written through to memory (write-through stores of a workgroup or of
+    // the copy kernel, or a DMA engine) and acknowledged before their signal was set, and the poll
+    // that saw the signal has returned, so loads issued from here on come after them.  What is
+    // left to rule out is a stale copy in this die's L2 or this unit's L1.  Both are emptied when
+    // a kernel starts, and nobody reads a row of the gathered matrix before its signal, so such a
+    // copy can only exist if a cache line holds rows of two communication tiles.  Only then is
+    // the die's L2 invalidated here: doing that costs one to two microseconds per workgroup and
+    // throws out the operand panels the die's other workgroups are sharing.
+    if (a.acquire_l2) __atomic_thread_fence(__ATOMIC_ACQUIRE);   // system scope
+    else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // count this workgroup in: its leaf first, the root if that completed the leaf
+    const uint32_t leaf = blockIdx.x % DONE_LEAVES;
+    const uint32_t quota = (gridDim.x - leaf + DONE_LEAVES - 1) / DONE_LEAVES;
+    const uint32_t leaves = gridDim.x < (uint32_t)DONE_LEAVES ? gridDim.x : (uint32_t)DONE_LEAVES;
+    uint32_t* leaf_counter = a.done_counter + (WS_DONELEAF_OFF - WS_DONE_OFF + leaf * DONE_LEAF_STRIDE) / 4;
+    bool last = false;
+    if (__hip_atomic_fetch_add(leaf_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == quota - 1) {
+      __hip_atomic_store(leaf_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+      last = __hip_atomic_fetch_add(a.done_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == leaves - 1;
+    }
+    if (last) {
       for (int i = 0; i < a.n_signals; ++i)
         __hip_atomic_store(a.signals + i, (i >= a.sig_local_lo && i < a.sig_local_hi) ? 1u : 0u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_SYSTEM);
