@@ -77,56 +77,76 @@ __host__ __device__ inline void tile_coord(const TileMap& tm, int block, int& mt
 
 enum : int { EPI_PLAIN = 0, EPI_RS = 1 };
 
+// Kernel arguments.  A workgroup's first fetches from the argument block miss the scalar cache one
+// 64-byte line after the other, a quarter of a microsecond each, before its first load can be
+// issued: the scalars sit together at the front, grouped by who needs them (every kernel; the signal
+// wait; the transfer; split-K and the reduce-scatter epilogue), and the arrays come last.
 struct GemmArgs {
+  // ---- every kernel ----
   const __bf16* A;           // [M,K]
   const __bf16* B;           // [K,N]
+  void* C;                   // [M,N] of out dtype (plain epilogue)
   int32_t M, N, K;
-  // plain epilogue
-  void* C;                   // [M,N] of out dtype
-  // reduce-scatter epilogue
-  const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
-  void* outs[FLUX_MAX_RANKS];
   int32_t R, rank, S;        // S = M / R
-  int32_t write_only;        // 1: reduce-scatter epilogue without the reduction (Write branch of Alg. 1);
-                             // 2: no peers are read, the tile is added to the slice with atomic additions
-  int32_t partial_f32, out_f32;
-  // all-gather prologue
-  uint32_t* signals;
-  int32_t rows_per_signal;
-  int32_t n_signals, sig_local_lo, sig_local_hi;   // local communication tiles: [lo, hi)
-  uint32_t* done_counter;
-  uint32_t* started_counter;
-  // the transfer: pieces of communication tiles are claimed and moved by this grid's workgroups
-  // and/or a copy kernel (outs[] then holds the chunk sources, A is the gathered matrix);
-  // copy_pieces = 0: the grid moves nothing and only waits (hipMemcpyAsync driver, or R = 1)
-  uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
-  uint32_t* copy_counters;   // [n_signals] pieces finished
-  uint32_t copy_call_id;     // 0: take the id from copy_call_seq (calls without a copy kernel)
-  uint32_t* copy_call_seq;
-  int32_t copy_pieces;       // pieces per communication tile
-  int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none)
-  int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
-  int32_t acquire_l2;        // the gathered rows may share cache lines across communication tiles: full acquire after the wait
-  // No driver at all (copy_owner_wgs > 0): piece g (counted over the remote communication tiles in
-  // transfer order, tile j lying in the chunk at position j / ctpc of copy_order4) belongs to
-  // workgroup g % copy_owner_wgs of this grid, which moves it before it looks at its own signals.
-  int32_t copy_owner_wgs;
-  int32_t copy_n_tiles;
-  unsigned long long copy_order4;   // chunk of position i in bits [4i, 4i+4)
-  unsigned long long copy_tile_vec;   // 16-byte vectors per communication tile
-  uint32_t* status;
-  unsigned long long timeout_ticks;
-  // split-K
   // K split: the first `full_tiles` tiles (in TileCoord order) are computed by one workgroup
   // each; every one of the remaining `split_tiles` tiles by `split_k` workgroups that each take
   // `k_per_split` of K.  A uniform split has full_tiles = 0; splitting only the tiles of the last,
   // partly filled round of the grid keeps all CUs busy to the end.
   int32_t full_tiles, split_tiles;
   int32_t split_k, k_per_split;   // k_per_split is a multiple of BK
+  // ---- all-gather prologue: the signal wait ----
+  uint32_t* signals;
+  uint32_t* done_counter;
+  uint32_t* status;
+  unsigned long long timeout_ticks;
+  int32_t rows_per_signal;
+  int32_t n_signals, sig_local_lo, sig_local_hi;   // local communication tiles: [lo, hi)
+  // the transfer: pieces of communication tiles are claimed and moved by this grid's workgroups
+  // and/or a copy kernel (outs[] then holds the chunk sources, A is the gathered matrix);
+  // copy_pieces = 0: the grid moves nothing and only waits (hipMemcpyAsync driver, or R = 1)
+  int32_t copy_pieces;       // pieces per communication tile
+  // No driver at all (copy_owner_wgs > 0): piece g (counted over the remote communication tiles in
+  // transfer order, tile j lying in the chunk at position j / ctpc of copy_order4) belongs to
+  // workgroup g % copy_owner_wgs of this grid, which moves it before it looks at its own signals.
+  int32_t copy_owner_wgs;
+  int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
+  int32_t acquire_l2;        // the gathered rows may share cache lines across communication tiles: full acquire after the wait
+  // ---- the transfer ----
+  uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
+  uint32_t* copy_counters;   // [n_signals] pieces finished
+  uint32_t* copy_call_seq;
+  uint32_t* started_counter;
+  unsigned long long copy_order4;   // chunk of position i in bits [4i, 4i+4)
+  unsigned long long copy_tile_vec;   // 16-byte vectors per communication tile
+  uint32_t copy_call_id;     // 0: take the id from copy_call_seq (calls without a copy kernel)
+  int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none)
+  int32_t copy_n_tiles;
+  // ---- split-K hand-over, reduce-scatter epilogue ----
+  int32_t write_only;        // 1: reduce-scatter epilogue without the reduction (Write branch of Alg. 1);
+                             // 2: no peers are read, the tile is added to the slice with atomic additions
   float* sk_partials;             // [split_k][split_tiles][BM*BN] fp32
   uint32_t* sk_counters;          // [tiles]
+  int32_t partial_f32, out_f32;
+  // ---- arrays ----
+  void* outs[FLUX_MAX_RANKS];
+  const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
   TileMap tm;
 };
+
+// The rank-indexed pointers (output slices, or chunk sources) go to LDS for dynamic indexing.  The
+// second half of the array lies in another line of the argument block and is only touched when
+// there are that many ranks.  Made visible to the other threads by the next workgroup barrier.
+__device__ __forceinline__ void fill_lds_outs(const GemmArgs& a, void** lds_outs, int tid) {
+  static_assert(FLUX_MAX_RANKS == 16, "two halves of eight");
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (tid == j) lds_outs[j] = a.outs[j];
+  if (a.R > 8) {
+#pragma unroll
+    for (int j = 8; j < 16; ++j)
+      if (tid == j) lds_outs[j] = a.outs[j];
+  }
+}
 
 // workgroup id -> (tile in TileCoord order, K split index, is this tile split)
 __device__ __forceinline__ void map_block(const GemmArgs& a, int b, int& tile, int& split, bool& is_split) {
@@ -445,6 +465,29 @@ __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4*
   }
 }
 
+// A piece of at most COPY_DEPTH * 256 vectors in two halves: the loads, and, once the piece is known
+// to be the caller's, the stores.  The loads touch only the source, so they can be on their way
+// while the claim is.
+constexpr int COPY_DEPTH = 16;
+__device__ __forceinline__ void load_piece(const uint4* __restrict__ src, unsigned long long tile_vec, int piece, int pieces,
+                                           int tid, u32x4 (&v)[COPY_DEPTH]) {
+  const unsigned long long stride = (unsigned long long)pieces * 256;
+  const unsigned long long i = (unsigned long long)piece * 256 + tid;
+#pragma unroll
+  for (int u = 0; u < COPY_DEPTH; ++u) {
+    v[u] = u32x4{0, 0, 0, 0};
+    if (i + u * stride < tile_vec) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i + u * stride));
+  }
+}
+__device__ __forceinline__ void store_piece(uint4* __restrict__ dst, unsigned long long tile_vec, int piece, int pieces,
+                                            int tid, const u32x4 (&v)[COPY_DEPTH]) {
+  const unsigned long long stride = (unsigned long long)pieces * 256;
+  const unsigned long long i = (unsigned long long)piece * 256 + tid;
+#pragma unroll
+  for (int u = 0; u < COPY_DEPTH; ++u)
+    if (i + u * stride < tile_vec) store_through(dst + i + u * stride, v[u]);
+}
+
 // true if the caller now owns the piece.  One exchange, one round trip: whoever swaps the call's id
 // in first sees something else come back; anyone later swaps the id for itself.
 __device__ __forceinline__ bool claim_piece(uint32_t* claim, uint32_t call_id) {
@@ -483,10 +526,96 @@ __device__ __forceinline__ bool driver_fully_started(const uint32_t* started, in
   return total - base >= (uint32_t)workgroups;
 }
 
-// WaitSignal (Alg. 2), preceded by this workgroup's share of the data transfer where no copy kernel
-// runs beside the grid.  The first wave polls the signals covering rows [m0, m1) with coherent
-// loads, one lane per signal; when all are set, an acquire fence makes the copied rows visible and
-// the workgroup barrier hands that to the other waves.  A workgroup that finds a signal missing
+// The id that marks a piece as taken in this call.  With a copy kernel beside the grid the host
+// hands out a fresh one per call.  Without, it is the number of such calls that have completed on
+// this workspace (the last workgroup past its wait counts the call in, when every workgroup has
+// read the old value: a workgroup only reads it before it is past its own wait), so a call
+// recorded in a graph gets a new id on every replay.
+__device__ __forceinline__ uint32_t transfer_call_id(const GemmArgs& a) {
+  if (a.copy_call_id != 0u) return a.copy_call_id;
+  return 0x80000000u | __hip_atomic_load(a.copy_call_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// No driver: the first copy_owner_wgs workgroups of the grid share the transfer out among
+// themselves by index, each moving its pieces in transfer order before it looks at its own
+// signals, whatever its own tile needs.  A piece still goes through the claim table (one word per
+// piece, so nobody contends), which lets any waiting workgroup take over the piece of an owner
+// that has not been given a compute unit yet.  The first wave claims up to 64 pieces in one round
+// trip and, when they have been moved, counts them in in another.  `lds` is 4 ints shared by the
+// workgroup; `lds_srcs` holds the chunk sources by rank (written before, not yet synchronised).
+__device__ __forceinline__ void transfer_own_pieces(const GemmArgs& a, int* lds, void* const* lds_srcs) {
+  if ((int)blockIdx.x >= a.copy_owner_wgs) return;
+  const int tid = threadIdx.x;
+  const int ctpc = a.n_signals / a.R;
+  const int total = a.copy_n_tiles * a.copy_pieces;
+  const int G = a.copy_owner_wgs;
+  if (total <= G && a.copy_tile_vec <= (unsigned long long)a.copy_pieces * 256 * COPY_DEPTH) {
+    // A small transfer (decode): at most one piece per owner, moved in one pass.  Then the whole
+    // call waits for a chain of memory round trips, so they overlap where they can: the piece is
+    // loaded while the call's id and then the claim are on their way.
+    const int g = (int)blockIdx.x;
+    if (g >= total) return;
+    __syncthreads();                       // lds_srcs
+    const uint32_t call_id = transfer_call_id(a);
+    const int j = g / a.copy_pieces, piece = g - j * a.copy_pieces;
+    const int chunk = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15), t = j % ctpc;
+    const int f = chunk * ctpc + t;
+    const uint4* src = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)t * a.copy_tile_vec;
+    uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
+    u32x4 v[COPY_DEPTH];
+    load_piece(src, a.copy_tile_vec, piece, a.copy_pieces, tid, v);
+    if (tid == 0) lds[2] = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + piece, call_id) ? 1 : 0;
+    __syncthreads();
+    if (lds[2]) {
+      store_piece(dst, a.copy_tile_vec, piece, a.copy_pieces, tid, v);
+      finish_pieces(a.copy_counters + f, a.signals + f, a.copy_pieces, 1);
+    }
+    return;
+  }
+  const uint32_t call_id = transfer_call_id(a);
+  for (int base = (int)blockIdx.x; base < total; base += 64 * G) {
+    if (tid < 64) {
+      const int g = base + tid * G;
+      bool mine = false;
+      if (g < total) {
+        const int j = g / a.copy_pieces;
+        const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
+        mine = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + (g - j * a.copy_pieces), call_id);
+      }
+      const unsigned long long won = __ballot(mine);
+      if (tid == 0) { lds[1] = (int)(uint32_t)won; lds[2] = (int)(uint32_t)(won >> 32); }
+    }
+    __syncthreads();
+    const unsigned long long won = (unsigned long long)(uint32_t)lds[1] | ((unsigned long long)(uint32_t)lds[2] << 32);
+    for (unsigned long long rest = won; rest != 0; rest &= rest - 1) {
+      const int g = base + __builtin_ctzll(rest) * G;
+      const int j = g / a.copy_pieces, piece = g - j * a.copy_pieces;
+      const int chunk = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15), t = j % ctpc;
+      const int f = chunk * ctpc + t;
+      const uint4* src = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)t * a.copy_tile_vec;
+      uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
+      copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
+    }
+    // count the pieces in, all at once: lane l of the first wave for the piece it claimed
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
+    __syncthreads();
+    if (tid < 64 && ((won >> tid) & 1)) {
+      const int g = base + tid * G;
+      const int j = g / a.copy_pieces;
+      const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
+      const uint32_t prev = __hip_atomic_fetch_add(a.copy_counters + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (prev + 1u == (uint32_t)a.copy_pieces) {
+        __hip_atomic_store(a.copy_counters + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        __hip_atomic_store(a.signals + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// WaitSignal (Alg. 2).  The first wave polls the signals covering rows [m0, m1) with coherent
+// loads, one lane per signal; when all are set, the workgroup barrier hands that to the other waves.
+// A workgroup that finds a signal missing
 // and unclaimed pieces among the tiles it waits for claims and moves such pieces itself (at once;
 // beside a paced driver only while part of that driver has not been given a compute unit), picking
 // them by a hash that depends on its index so that the workgroups of a grid spread over the pieces
@@ -509,62 +638,8 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   uint32_t salt = (uint32_t)blockIdx.x * 0x9E3779B9u;      // varies per workgroup and per attempt
   int dead_w0 = -1;                                        // window start at which a search found nothing left to take
   bool ok = true;
-  // The id that marks a piece as taken in this call.  With a copy kernel beside the grid the host
-  // hands out a fresh one per call.  Without, it is the number of such calls that have completed on
-  // this workspace (the last workgroup past its wait counts the call in, when every workgroup has
-  // long read the old value), so a call recorded in a graph gets a new id on every replay.
-  uint32_t call_id = a.copy_call_id;
-  if (a.copy_pieces > 0 && call_id == 0u)
-    call_id = 0x80000000u | __hip_atomic_load(a.copy_call_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if ((int)blockIdx.x < a.copy_owner_wgs) {
-    // No driver: the first copy_owner_wgs workgroups of the grid share the transfer out among
-    // themselves by index, each moving its pieces in transfer order before it looks at its own
-    // signals, whatever its own tile needs.  A piece still goes through the claim table (one
-    // word per piece, so nobody contends), which lets any waiting workgroup take over the piece of
-    // an owner that has not been given a compute unit yet.  The first wave claims up to 64 pieces
-    // in one round trip and, when they have been moved, counts them in in another.
-    const int ctpc = a.n_signals / a.R;
-    const int total = a.copy_n_tiles * a.copy_pieces;
-    const int G = a.copy_owner_wgs;
-    for (int base = (int)blockIdx.x; base < total; base += 64 * G) {
-      if (tid < 64) {
-        const int g = base + tid * G;
-        bool mine = false;
-        if (g < total) {
-          const int j = g / a.copy_pieces;
-          const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
-          mine = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + (g - j * a.copy_pieces), call_id);
-        }
-        const unsigned long long won = __ballot(mine);
-        if (tid == 0) { lds[1] = (int)(uint32_t)won; lds[2] = (int)(uint32_t)(won >> 32); }
-      }
-      __syncthreads();
-      const unsigned long long won = (unsigned long long)(uint32_t)lds[1] | ((unsigned long long)(uint32_t)lds[2] << 32);
-      for (unsigned long long rest = won; rest != 0; rest &= rest - 1) {
-        const int g = base + __builtin_ctzll(rest) * G;
-        const int j = g / a.copy_pieces, piece = g - j * a.copy_pieces;
-        const int chunk = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15), t = j % ctpc;
-        const int f = chunk * ctpc + t;
-        const uint4* src = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)t * a.copy_tile_vec;
-        uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
-        copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
-      }
-      // count the pieces in, all at once: lane l of the first wave for the piece it claimed
-      __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
-      __syncthreads();
-      if (tid < 64 && ((won >> tid) & 1)) {
-        const int g = base + tid * G;
-        const int j = g / a.copy_pieces;
-        const int f = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15) * ctpc + j % ctpc;
-        const uint32_t prev = __hip_atomic_fetch_add(a.copy_counters + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev + 1u == (uint32_t)a.copy_pieces) {
-          __hip_atomic_store(a.copy_counters + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-          __hip_atomic_store(a.signals + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        }
-      }
-      __syncthreads();
-    }
-  }
+  uint32_t call_id = 0u;                                   // fetched when a piece is first looked for
+  bool have_call_id = false;
   for (;;) {
     if (tid < 64) {
       // the first wave polls, one signal per lane: one memory round trip per 64 signals, however
@@ -608,6 +683,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
     // workgroup and attempt: workgroups that wait for the same tiles then rarely go for the same
     // piece (taking "the first free one" would make them queue up behind each other).  The local
     // chunk's tiles are never copied by anyone, their signals are preset.
+    if (!have_call_id) { call_id = transfer_call_id(a); have_call_id = true; }
     const int wt = f1 - w0 + 1 < window_tiles ? f1 - w0 + 1 : window_tiles;
     const int total = wt * a.copy_pieces;
     salt = salt * 1664525u + 1013904223u;
@@ -817,12 +893,11 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
   // output slices by rank (reduce-scatter) or chunk sources by rank (all-gather)
   void** lds_outs = reinterpret_cast<void**>(smem + C::PTRS_OFF);
   if (EPI == EPI_RS || WAIT) {
-#pragma unroll
-    for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-      if (tid == j) lds_outs[j] = a.outs[j];     // made visible by the main loop's barriers
+    fill_lds_outs(a, lds_outs, tid);
   }
 
   if (WAIT) {
+    transfer_own_pieces(a, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs);
     if (!wait_signals(a, m0, m1, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs)) return;
   }
 
@@ -1142,11 +1217,10 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   const int m0 = mt * C::BM, n0 = nt * C::BN;
 
   if (EPI == EPI_RS || WAIT) {      // output slices (reduce-scatter) or chunk sources (all-gather), by rank
-#pragma unroll
-    for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-      if (tid == j) lds_outs[j] = a.outs[j];
+    fill_lds_outs(a, lds_outs, tid);
   }
   if (WAIT) {
+    transfer_own_pieces(a, lds_misc, lds_outs);
     if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) return;
   }
 
@@ -1250,9 +1324,7 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
   const int m0 = mt * C::BM, n0 = nt * C::BN;
 
   if (EPI == EPI_RS || WAIT) {
-#pragma unroll
-    for (int j = 0; j < FLUX_MAX_RANKS; ++j)
-      if (tid == j) lds_outs[j] = a.outs[j];
+    fill_lds_outs(a, lds_outs, tid);
   }
   const int k_begin = is_split ? split * a.k_per_split : 0;
   const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
@@ -1266,10 +1338,12 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
   const int last = KT - 1;
   constexpr int LA = DmaLoader<C>::A_INSTR;
   if (WAIT) {
-    // The weights do not depend on the gathered rows: their part of the first slabs is on its way
-    // while this workgroup moves its share of the chunks and waits for the signals.  In the first
-    // pass of the loop the order of issue is then [B of slabs 0..NS-2][A of slabs 0..NS-2][slab NS-1]...,
-    // and "slab j has landed" means that at most the A parts after it and j whole slabs are out.
+    // First this workgroup's own pieces of the chunks: the whole grid waits for them.  Then the
+    // weights, which do not depend on the gathered rows: their part of the first slabs is on its
+    // way while the workgroup waits for its signals.  In the first pass of the loop the order of
+    // issue is then [B of slabs 0..NS-2][A of slabs 0..NS-2][slab NS-1]..., and "slab j has landed"
+    // means that at most the A parts after it and j whole slabs are out.
+    transfer_own_pieces(a, lds_misc, lds_outs);
 #pragma unroll
     for (int j = 0; j < NS - 1; ++j) ld.issue_b(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
     const int m1 = (!MASK || m0 + C::BM < a.M) ? m0 + C::BM : a.M;
