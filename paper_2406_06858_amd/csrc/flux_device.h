@@ -803,10 +803,15 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
     // an L2 write-back nor an L2 invalidate, only "my stores are acknowledged" before counting in.
     constexpr int SC1 = 16;                               // cache-policy bit: device scope
     constexpr int BLOCK_BYTES = C::BM * C::BN * 4;
-    constexpr int NV = C::MI * C::NI * 4;                 // 16-byte vectors per thread
     float* mine = a.sk_partials + ((size_t)split * a.split_tiles + st) * (C::BM * C::BN);
     __amdgpu_buffer_rsrc_t rm = __builtin_amdgcn_make_buffer_rsrc(mine, 0, BLOCK_BYTES, 0x00027000);
-    // layout inside a tile's partial block: [vector index][thread] -> coalesced 16-byte columns
+    // layout inside a tile's partial block: [vector index][thread] -> coalesced 16-byte columns.
+    // A vector holds four of eight consecutive rows; with a ragged M (a decode tile of 8 rows in a
+    // 32-row tile) the vectors that lie wholly past the last row are neither parked nor read back:
+    // their offset is moved past the end of the block, where the range check of the buffer drops a
+    // store and answers a load with zeros (a branch around them would make every load wait for
+    // the one before).
+    const int rows_valid = EDGE ? a.M - m0 - wm * C::WTM : C::BM;
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
@@ -815,7 +820,8 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
         for (int q = 0; q < 4; ++q) {
           const u32x4 v = {__float_as_uint(acc[mi][ni][4 * q]), __float_as_uint(acc[mi][ni][4 * q + 1]),
                            __float_as_uint(acc[mi][ni][4 * q + 2]), __float_as_uint(acc[mi][ni][4 * q + 3])};
-          __builtin_amdgcn_raw_buffer_store_b128(v, rm, (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
+          const bool past = EDGE && mi * 32 + 8 * q >= rows_valid;
+          __builtin_amdgcn_raw_buffer_store_b128(v, rm, past ? BLOCK_BYTES : (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
         }
     __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0): stores acknowledged
     __syncthreads();
@@ -828,9 +834,10 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
     }
     __syncthreads();
     if (!*lds_last) return;
-    (void)NV;
-    // the sum always runs over the parked partials in split order, whichever workgroup happens
-    // to be last, so results do not depend on arrival timing
+    // The sum always runs over the parked partials in split order, whichever workgroup happens
+    // to be last, so results do not depend on arrival timing.  (Keeping the own part in registers
+    // and skipping its load was tried: no gain for 64x64 tiles, a loss for 64x128.  So was issuing
+    // the loads of several parts ahead of the additions.)
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
@@ -847,7 +854,8 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
         for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ro, (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
+            const bool past = EDGE && mi * 32 + 8 * q >= rows_valid;
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ro, past ? BLOCK_BYTES : (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
             acc[mi][ni][4 * q] += __uint_as_float(v[0]);
             acc[mi][ni][4 * q + 1] += __uint_as_float(v[1]);
             acc[mi][ni][4 * q + 2] += __uint_as_float(v[2]);
