@@ -67,13 +67,16 @@ def run_rs(w: fi.Workload, rank: int, A, B, peers, tile_config=0, split_k=0, fla
 
 def run_ag(w: fi.Workload, rank: int, chunks, B, arrival, tile_config=0, split_k=0, flags=0,
            comm_tiles_per_chunk=0, copy_workgroups=0, local_in_place=False, delay_copy_cycles=0,
-           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1, link_gbps=0, copy_stream=None):
+           timeout_ticks=TEST_TIMEOUT_TICKS, repeat=1, link_gbps=0, copy_stream=None, agg_offset_elems=0):
     """Fused AllGather-GEMM through the C ABI.  A_agg starts NaN-poisoned so a tile that reads
     rows before their signal shows up in C.  Returns (C, A_agg, signals, status)."""
     p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, tile_config, split_k, flags,
                    comm_tiles_per_chunk, copy_workgroups, timeout_ticks, link_gbps)
     dB = B.to(DEV)
-    A_agg = torch.full((w.M, w.K), float("nan"), dtype=torch.bfloat16, device=DEV)
+    # (agg_offset_elems: start the gathered matrix that many elements into its allocation, e.g. 8
+    # for a base that is 16-byte but not cache-line aligned)
+    agg_store = torch.full((w.M * w.K + agg_offset_elems,), float("nan"), dtype=torch.bfloat16, device=DEV)
+    A_agg = agg_store[agg_offset_elems:].view(w.M, w.K)
     dchunks = [c.to(DEV) for c in chunks]
     if local_in_place:
         A_agg[rank * w.S:(rank + 1) * w.S].copy_(dchunks[rank])

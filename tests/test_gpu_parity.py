@@ -424,6 +424,28 @@ def test_ag_r1_needs_no_copy():
     assert signals.cpu().tolist() == [1]
 
 
+@pytest.mark.parametrize("cw", [0, 16])
+def test_ag_gathered_matrix_not_line_aligned(cw):
+    """A gathered matrix whose rows do not start on cache line boundaries (base 16 bytes into a
+    line): rows of two communication tiles can then share a line, and the wait ends with the
+    acquire that also drops stale lines from the die's L2 (the cheaper one is only taken when
+    every row starts and ends on a line boundary).  Two calls on the same buffers, the remote
+    rows poisoned in between."""
+    w = fi.scaled(W["c2_ag"], M=1024, N=512, K=448)
+    rank = 5
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    C64, _ = gh.oracle_ag(w, chunks, B)
+    for ctpc in (1, 2):
+        _say("unaligned gathered matrix, copy workgroups", cw, "ctpc", ctpc)
+        Cg, A_agg, _, status = gh.run_ag(w, rank, chunks, B, arrival, copy_workgroups=cw, comm_tiles_per_chunk=ctpc,
+                                         repeat=2, agg_offset_elems=8)
+        assert status == (fb.FLUX_OK, 0)
+        assert A_agg.data_ptr() % 128 == 16
+        gh.assert_close(Cg, C64, w.out_dtype)
+        want = torch.cat(chunks).view(torch.int16)
+        assert torch.equal(A_agg.cpu().view(torch.int16), want)
+
+
 def test_ag_signal_wait_times_out_cleanly():
     """Failure handling, forced from the host: the copy stream is held back and the spin limit
     is one tick, so waiting tiles give up, the kernel still exits, and the status block says
