@@ -154,7 +154,10 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  * driver take a fresh claim id from the host on every call and are not meant to be replayed.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
- *                   at A_agg + rank*(M/R)*K the local chunk is not copied.
+ *                   at A_agg + rank*(M/R)*K the local chunk is not copied.  16-byte alignment is
+ *                   required; with 128-byte alignment and K a multiple of 64 no cache line holds
+ *                   rows of two communication tiles, and a workgroup leaves its signal wait without
+ *                   invalidating its die's L2 (one to two microseconds per workgroup otherwise).
  *   B, C            device, [K,N] bf16 and [M,N] out_dtype.
  *   signals         device uint32[R * comm_tiles_per_chunk] ("signal_list").  Must be in the preset
  *                   state on entry (local communication tiles 1, the others 0): preset once
