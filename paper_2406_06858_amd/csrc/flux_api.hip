@@ -282,6 +282,18 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     if (p->M <= 32) cfg = (deep_ok && p->N % 128 == 0) ? 7 : 5;          // 32x128
     else if (p->M <= 64) cfg = (deep_ok && p->N % 64 == 0 && p->M == 64) ? 6 : 4;   // 64x64 deep, else 64x128
     else if ((long long)p->M * p->N <= 256ll * 1024) cfg = 3;            // 64x64, small problems
+    else if (p->M == 128 && deep_ok && p->N % 128 == 0 && p->K > 8192 && 2ll * (p->N / 128) <= N_CU / 2) {
+      // Two m-tiles, a long K and few columns: the two-per-CU 64x128 tile, whose finer K cut fills
+      // its 512 slots (6144x12288: 55 against 66 us for 64x128 on four stages, weights from HBM).
+      // (64x64 tiles on six stages are 11-19 % ahead on 3584x8192 and 8192x3584 while the weights
+      // are still in the Infinity Cache and 3-4 % behind when they come from HBM: not taken.)
+      cfg = 9;
+    }
+    else if (p->M == 256 && deep_ok && p->N % 128 == 0 && p->N / 128 >= 96 && p->K / 64 >= 64) {
+      // One m-tile of 256 rows over many columns: 256x128 tiles with K cut in two read the weights
+      // once and fill three quarters of the chip (12288x6144: 64-73 against 93-96 us for 64x128).
+      cfg = 1;
+    }
     else if (p->M >= 256 && p->M <= 512 && p->M % 64 == 0 && deep_ok && p->N % 128 == 0 && p->K >= 8192 &&
              (long long)(p->M / 64) * (p->N / 128) <= N_CU) {
       // a few hundred rows over a long K: 64x128 tiles, two workgroups per CU, K cut in two or more

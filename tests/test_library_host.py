@@ -189,6 +189,12 @@ def test_tile_choice_follows_how_well_the_grid_fills_the_chip():
     assert tile(256, 3584, 8192) == (64, 128)
     assert tile(512, 8192, 3584)[0] >= 128           # short K: no
     assert tile(1024, 3584, 8192)[0] >= 128          # 448 tiles: no
+    # two m-tiles, long K, few columns: the same two-per-CU tile with a finer K cut
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(128, 6144, 12288, 8, 0)) == (0, 96, 5)
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(128, 3584, 8192, 8, 0)) == (0, 56, 4)     # 64x128 on four stages, one per CU
+    # one m-tile of 256 rows over many columns: 256x128 with K cut in two
+    assert tile(256, 12288, 6144) == (256, 128)
+    assert tile(256, 8192, 3584) == (64, 128)
 
 
 def test_autotune_sizes_cover_every_candidate():
