@@ -836,31 +836,52 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
     if (!*lds_last) return;
     // The sum always runs over the parked partials in split order, whichever workgroup happens
     // to be last, so results do not depend on arrival timing.  (Keeping the own part in registers
-    // and skipping its load was tried: no gain for 64x64 tiles, a loss for 64x128.  So was issuing
-    // the loads of several parts ahead of the additions.)
+    // and skipping its load was tried: no gain for 64x64 tiles, a loss for 64x128.)
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
       for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
-#pragma unroll 4
-    for (int s = 0; s < a.split_k; ++s) {
-      float* other = a.sk_partials + ((size_t)s * a.split_tiles + st) * (C::BM * C::BN);
-      __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(other, 0, BLOCK_BYTES, 0x00027000);
+    // Sixteen loads are issued before the first is used.  Left to itself the compiler waits for
+    // every vector before it requests the next (a memory round trip each: 17 us for the 256 KB of
+    // two parts of a 256x128 tile); a branch around a load has the same effect, so parts past the
+    // end are read as zeros through the buffer's range check instead.  A large tile takes its
+    // vectors sixteen at a time, part by part; a small one takes all vectors of several parts.
+    constexpr int NVEC = C::MI * C::NI * 4;                 // 16-byte vectors per thread and part
+    constexpr int VB = NVEC < 16 ? NVEC : 16;               // vectors per batch within a part
+    constexpr int PB = 16 / VB;                             // parts per batch
+    static_assert(NVEC % VB == 0 && 16 % VB == 0, "batches divide the tile");
+    for (int s0 = 0; s0 < a.split_k; s0 += PB) {
 #pragma unroll
-      for (int mi = 0; mi < C::MI; ++mi)
+      for (int b0 = 0; b0 < NVEC; b0 += VB) {
+        u32x4 v[PB][VB];
 #pragma unroll
-        for (int ni = 0; ni < C::NI; ++ni)
+        for (int g = 0; g < PB; ++g) {
+          const int s = s0 + g;
+          const bool none = s >= a.split_k;                 // only with PB > 1
+          float* other = a.sk_partials + ((size_t)(none ? 0 : s) * a.split_tiles + st) * (C::BM * C::BN);
+          __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(other, 0, BLOCK_BYTES, 0x00027000);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const bool past = EDGE && mi * 32 + 8 * q >= rows_valid;
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ro, past ? BLOCK_BYTES : (((mi * C::NI + ni) * 4 + q) * C::NT + tid) * 16, 0, SC1);
-            acc[mi][ni][4 * q] += __uint_as_float(v[0]);
-            acc[mi][ni][4 * q + 1] += __uint_as_float(v[1]);
-            acc[mi][ni][4 * q + 2] += __uint_as_float(v[2]);
-            acc[mi][ni][4 * q + 3] += __uint_as_float(v[3]);
+          for (int i = 0; i < VB; ++i) {
+            const int idx = b0 + i, mi = idx / (C::NI * 4), q = idx % 4;
+            const bool past = none || (EDGE && mi * 32 + 8 * q >= rows_valid);
+            v[g][i] = __builtin_amdgcn_raw_buffer_load_b128(ro, past ? BLOCK_BYTES : (idx * C::NT + tid) * 16, 0, SC1);
           }
+        }
+        __builtin_amdgcn_sched_barrier(0);                  // all of the batch's loads first
+#pragma unroll
+        for (int g = 0; g < PB; ++g)
+#pragma unroll
+          for (int i = 0; i < VB; ++i) {
+            const int idx = b0 + i, mi = idx / (C::NI * 4), ni = (idx / 4) % C::NI, q = idx % 4;
+            acc[mi][ni][4 * q] += __uint_as_float(v[g][i][0]);
+            acc[mi][ni][4 * q + 1] += __uint_as_float(v[g][i][1]);
+            acc[mi][ni][4 * q + 2] += __uint_as_float(v[g][i][2]);
+            acc[mi][ni][4 * q + 3] += __uint_as_float(v[g][i][3]);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     __syncthreads();
   }
