@@ -843,15 +843,16 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
       for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
-    // Sixteen loads are issued before the first is used.  Left to itself the compiler waits for
+    // Sixteen or thirty-two loads are issued before the first is used.  Left to itself the compiler waits for
     // every vector before it requests the next (a memory round trip each: 17 us for the 256 KB of
     // two parts of a 256x128 tile); a branch around a load has the same effect, so parts past the
     // end are read as zeros through the buffer's range check instead.  A large tile takes its
-    // vectors sixteen at a time, part by part; a small one takes all vectors of several parts.
+    // vectors a batch at a time, part by part; a small one takes all vectors of several parts.
     constexpr int NVEC = C::MI * C::NI * 4;                 // 16-byte vectors per thread and part
-    constexpr int VB = NVEC < 16 ? NVEC : 16;               // vectors per batch within a part
-    constexpr int PB = 16 / VB;                             // parts per batch
-    static_assert(NVEC % VB == 0 && 16 % VB == 0, "batches divide the tile");
+    constexpr int IN_FLIGHT = NVEC >= 32 ? 32 : 16;         // (32 is ahead for the large tiles, 16 for the small)
+    constexpr int VB = NVEC < IN_FLIGHT ? NVEC : IN_FLIGHT; // vectors per batch within a part
+    constexpr int PB = IN_FLIGHT / VB;                      // parts per batch
+    static_assert(NVEC % VB == 0 && IN_FLIGHT % VB == 0, "batches divide the tile");
     for (int s0 = 0; s0 < a.split_k; s0 += PB) {
 #pragma unroll
       for (int b0 = 0; b0 < NVEC; b0 += VB) {
