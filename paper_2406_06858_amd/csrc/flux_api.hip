@@ -289,16 +289,18 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
       // are still in the Infinity Cache and 3-4 % behind when they come from HBM: not taken.)
       cfg = 9;
     }
-    else if (p->M == 256 && deep_ok && p->N % 128 == 0 && p->N / 128 >= 96 && p->K / 64 >= 64) {
-      // One m-tile of 256 rows over many columns: 256x128 tiles with K cut in two read the weights
-      // once and fill three quarters of the chip (12288x6144: 64-73 against 93-96 us for 64x128).
+    else if (p->M == 256 && deep_ok && p->N % 128 == 0 && p->K >= 6144 &&
+             std::min<long long>(N_CU / (p->N / 128), p->K / 64 / 8) <= 5) {
+      // One m-tile of 256 rows: 256x128 tiles read the weights once; they pay where filling the
+      // chip takes at most five K parts (the workgroup that arrives last at a tile reads all parts
+      // back, at what one CU can pull): 12288x6144 64-70 us against 93-96 us for 64x128, 6144x12288
+      // 68-72 against 88-91 us.
       cfg = 1;
     }
-    else if (p->M >= 256 && p->M <= 512 && p->M % 64 == 0 && deep_ok && p->N % 128 == 0 && p->K >= 8192 &&
-             (long long)(p->M / 64) * (p->N / 128) <= N_CU) {
-      // a few hundred rows over a long K: 64x128 tiles, two workgroups per CU, K cut in two or more
-      // so that every slot has a part of at least 64 slabs; measured 9-17 % ahead of the larger
-      // tiles there, which leave half of the chip idle, and behind them on every other shape
+    else if (p->M == 256 && deep_ok && p->N % 128 == 0 && p->K >= 8192 && 4ll * (p->N / 128) <= N_CU) {
+      // ... and where that takes more parts, over a long K: 64x128 tiles, two workgroups per CU, K
+      // cut so that every slot has a part (3584x8192, weights from HBM: 36-41 us against 40-44 us
+      // for the same tile on four stages, one per CU).
       cfg = 9;
     }
     else if (p->M <= 256 && p->M % 64 == 0 && deep_ok && p->N % 128 == 0) cfg = 8;   // 64x128 deep

@@ -183,18 +183,18 @@ def test_tile_choice_follows_how_well_the_grid_fills_the_chip():
     assert tile(1024, 8192, 3584) == (256, 128)      # 128 tiles of 256x256: half the chip
     assert tile(2048, 8192, 3584) == (256, 256)      # exactly one round
     assert tile(512, 6144, 12288)[0] in (128, 256) and tile(512, 6144, 12288) != (256, 256)
-    # a few hundred rows over a long K, at most 256 tiles of 64x128: those, two per CU, K cut
-    assert tile(512, 3584, 8192) == (64, 128)
-    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(512, 3584, 8192, 8, 0)) == (0, 224, 2)
+    # one m-tile of 256 rows over a long K whose 256x128 tiles would need more than five K parts to
+    # fill the chip: 64x128 tiles, two workgroups per CU, K cut so that every slot has a part
     assert tile(256, 3584, 8192) == (64, 128)
-    assert tile(512, 8192, 3584)[0] >= 128           # short K: no
-    assert tile(1024, 3584, 8192)[0] >= 128          # 448 tiles: no
-    # two m-tiles, long K, few columns: the same two-per-CU tile with a finer K cut
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(256, 3584, 8192, 8, 0)) == (0, 112, 4)
+    # ... five parts or fewer: 256x128, the weights read once
+    assert tile(256, 12288, 6144) == (256, 128)
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(256, 6144, 12288, 8, 0)) == (0, 48, 5)
+    assert tile(256, 8192, 3584) == (64, 128)          # short K: no
+    assert tile(512, 3584, 8192) == (256, 128)         # more rows: the estimate decides
+    # two m-tiles, long K, few columns: the two-per-CU tile with a finer K cut
     assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(128, 6144, 12288, 8, 0)) == (0, 96, 5)
     assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(128, 3584, 8192, 8, 0)) == (0, 56, 4)     # 64x128 on four stages, one per CU
-    # one m-tile of 256 rows over many columns: 256x128 with K cut in two
-    assert tile(256, 12288, 6144) == (256, 128)
-    assert tile(256, 8192, 3584) == (64, 128)
 
 
 def test_autotune_sizes_cover_every_candidate():
