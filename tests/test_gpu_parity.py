@@ -249,6 +249,25 @@ def test_split_k_bitwise_on_integers(split):
                 gh.assert_bits_equal(outs[r], want[r], f"rep {rep} slice {r}")
 
 
+@pytest.mark.parametrize("cfg", ALL_CFGS)
+@pytest.mark.parametrize("M", [256, 40])
+def test_split_k_hand_over_every_config(cfg, M):
+    """The workgroup that arrives last at a K-cut tile reads the parked parts back in batches (several
+    parts at once for a small tile, a part in several batches for a large one) and, with a ragged M,
+    leaves out the vectors past the last row: every configuration, part counts that are and are
+    not multiples of a batch, whole and ragged tiles, bitwise on integer-valued inputs."""
+    w = fi.Workload("int_rs_parts", "rs", M, 512, 1152, 8, a_dist=("int", 2), b_dist=("int", 2),
+                    peer_dist=("int", 8), seed=81)
+    rank = 3
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    _, want = gh.oracle_rs(w, rank, A, B, peers)
+    for split in (2, 5, 9):
+        _say("hand-over cfg", cfg, "M", M, "parts", split)
+        outs = gh.run_rs(w, rank, A, B, peers, tile_config=cfg, split_k=split)
+        for r in range(w.R):
+            gh.assert_bits_equal(outs[r], want[r], f"cfg {cfg} parts {split} slice {r}")
+
+
 @pytest.mark.parametrize("cfg,M,N,K", [(4, 1536, 1536, 1024), (1, 8192, 4608, 512), (3, 4608, 2048, 576)])
 def test_tail_split_bitwise_on_integers(cfg, M, N, K):
     """Only the tiles of the partly filled last round are cut along K; the rest are computed whole."""
