@@ -280,6 +280,13 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     // direct-to-LDS loads (whole tiles along N and K; M may be ragged), else the two-stage twin
     const bool deep_ok = p->K % 64 == 0;
     if (p->M <= 32) cfg = (deep_ok && p->N % 128 == 0) ? 7 : 5;          // 32x128
+    else if (p->M == 64 && deep_ok && p->N % 128 == 0 && p->N / 128 <= N_CU &&
+             std::min<long long>(N_CU / (p->N / 128), p->K / 64 / 8) <= 5) {
+      // 64 rows over a large weight matrix: 64x128 tiles on four stages where at most five K parts
+      // fill the chip (12288x6144: 37 against 45 us, 6144x12288: 36 against 47 us for 64x64 tiles,
+      // whose grid leaves a quarter of the chip idle there; no difference on 8192x3584 and 8192x8192)
+      cfg = 8;
+    }
     else if (p->M <= 64) cfg = (deep_ok && p->N % 64 == 0 && p->M == 64) ? 6 : 4;   // 64x64 deep, else 64x128
     else if ((long long)p->M * p->N <= 256ll * 1024) cfg = 3;            // 64x64, small problems
     else if (p->M == 128 && deep_ok && p->N % 128 == 0 && p->K > 8192 && 2ll * (p->N / 128) <= N_CU / 2) {

@@ -192,6 +192,10 @@ def test_tile_choice_follows_how_well_the_grid_fills_the_chip():
     assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(256, 6144, 12288, 8, 0)) == (0, 48, 5)
     assert tile(256, 8192, 3584) == (64, 128)          # short K: no
     assert tile(512, 3584, 8192) == (256, 128)         # more rows: the estimate decides
+    # 64 rows: 64x64 tiles on six stages, or 64x128 on four where at most five K parts fill the chip
+    assert tile(64, 3584, 8192) == (64, 64)
+    assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(64, 6144, 12288, 8, 0)) == (0, 48, 5)
+    assert tile(64, 12288, 6144) == (64, 128)
     # two m-tiles, long K, few columns: the two-per-CU tile with a finer K cut
     assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(128, 6144, 12288, 8, 0)) == (0, 96, 5)
     assert fb.flux_split_plan(fb.FLUX_OP_AG, fb.problem(128, 3584, 8192, 8, 0)) == (0, 56, 4)     # 64x128 on four stages, one per CU
