@@ -65,9 +65,10 @@ WORKLOADS = {
     # decode
     **{w.name: w for w in (_decode(m, op) for m in (8, 64, 256) for op in ("ag", "rs"))},
     # the op-level sweep of the paper's evaluation (Sec. 5.1): GPT-3-175B MLP at TP=8, local (n, k) =
-    # (6144, 12288) for AllGather-GEMM and (12288, 6144) for GEMM-ReduceScatter, m tokens
-    **{f"op_ag_m{m}": Workload(f"op_ag_m{m}", "ag", m, 6144, 12288, 8, seed=BASE_SEED + 5) for m in (512, 2048, 8192)},
-    **{f"op_rs_m{m}": Workload(f"op_rs_m{m}", "rs", m, 12288, 6144, 8, seed=BASE_SEED + 6) for m in (512, 2048, 8192)},
+    # (6144, 12288) for AllGather-GEMM and (12288, 6144) for GEMM-ReduceScatter, m tokens (m = 8 and 64:
+    # the same weight shards at decode batch sizes)
+    **{f"op_ag_m{m}": Workload(f"op_ag_m{m}", "ag", m, 6144, 12288, 8, seed=BASE_SEED + 5) for m in (8, 64, 512, 2048, 8192)},
+    **{f"op_rs_m{m}": Workload(f"op_rs_m{m}", "rs", m, 12288, 6144, 8, seed=BASE_SEED + 6) for m in (8, 64, 512, 2048, 8192)},
 }
 
 

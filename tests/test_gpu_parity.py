@@ -168,7 +168,7 @@ def _sample_rows(M, S, n_per_slice, seed):
     return rows
 
 
-@pytest.mark.parametrize("name", ["c3_rs", "c4_rs", "op_rs_m2048", "op_rs_m8192"])
+@pytest.mark.parametrize("name", ["c3_rs", "c4_rs", "op_rs_m64", "op_rs_m2048", "op_rs_m8192"])
 def test_rs_full_size_sampled_rows(name):
     """Full benchmark shape in the launch configuration the benchmark uses; the oracle
     evaluates a seeded sample of complete rows in every slice (first and last row included)."""
@@ -189,7 +189,7 @@ def test_rs_full_size_sampled_rows(name):
         assert not torch.isnan(outs[r]).any()
 
 
-@pytest.mark.parametrize("name", ["c2_ag", "c4_ag", "op_ag_m2048", "op_ag_m8192"])
+@pytest.mark.parametrize("name", ["c2_ag", "c4_ag", "op_ag_m64", "op_ag_m2048", "op_ag_m8192"])
 def test_ag_full_size_sampled_rows(name):
     w = W[name]
     rank = 2
