@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the fused tensor-parallel GEMMs on one MI355X.
 
-A step is one pass of the whole hot path on one batch: the fused AllGather-GEMM of the
-Llama-2-70B-like MLP up-projection (4096 tokens, TP=8; chunks released by the copy driver in a
-seeded random order) followed by the fused GEMM-ReduceScatter of the matching down-projection
-(7 peer partials added in the epilogue, 8 row slices written).  Inputs are seeded synthetic
-tensors, already resident in HBM when the timed region starts.
+A step is one pass of the whole hot path on one batch of the largest configuration that fits one
+GPU, the GPT-3-175B-like layer at TP=8 with 8192 tokens: the fused AllGather-GEMM of the QKV
+projection (8 chunks of [1024,12288] gathered in a seeded random arrival order, times [12288,4608])
+followed by the fused GEMM-ReduceScatter of the attention output projection ([8192,1536] times
+[1536,12288], 7 peer partials added in the epilogue, 8 row slices written).  Inputs are seeded
+synthetic tensors, already resident in HBM when the timed region starts.
 
 Prints ONE JSON line (see README for the fields).
 """
@@ -23,6 +24,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+# bytes per launch behind the L2 of the two kernels of the timed step (rocprofv3 FETCH_SIZE + WRITE_SIZE)
+TRAFFIC_BYTES = {"rs": None, "ag": None}
 HBM_PEAK_GBS = 8000.0
 TIMEOUT_TICKS = 500_000_000        # 5 s: a lost signal ends the run with an error, not a hang
 
@@ -271,14 +274,14 @@ def main() -> int:
         print(json.dumps({"mode": "serial-decode", "launches_per_shape": args.serial_decode}))
         return 0
 
-    # ---- the timed workload: MLP up-projection (AG-GEMM) + down-projection (GEMM-RS) ----
-    ag = AG(W["c2_ag"], rank=2, flags=args.ag_flags)
-    rs = RS(W["c3_rs"], rank=2)
+    # ---- the timed workload: QKV projection (AG-GEMM) + attention output projection (GEMM-RS) ----
+    ag = AG(W["c4_ag"], rank=2, flags=args.ag_flags)
+    rs = RS(W["c4_rs"], rank=2)
     flops_step = ag.w.flops + rs.w.flops
 
     if args.serial_kernels > 0:
         for _ in range(args.serial_kernels):
-            ag.unfused(fb.FLUX_PHASE_COMM)      # plain copy of 7 chunks: 58.7 MB read + 58.7 MB written
+            ag.unfused(fb.FLUX_PHASE_COMM)      # plain copy of 7 chunks: 176.2 MB read + 176.2 MB written
             ag.unfused(fb.FLUX_PHASE_GEMM)      # same tile configuration as the fused kernel, no signal wait
             rs.fused()
             # the fused AllGather call also completes when its two kernels cannot overlap: whichever
@@ -329,7 +332,7 @@ def main() -> int:
 
     # spot check against the oracle on a few rows (outside the timed region)
     from oracle import flux_oracle as fo
-    rows = [0, 511, 512, 2047, 4095]
+    rows = [0, 1023, 1024, 4095, 8191]
     ref = fo.ag_gemm_rows([fi.to_numpy(c) for c in ag.chunks_cpu], fi.to_numpy(ag.B_cpu), rows)
     got = ag.C[rows].float().cpu().double().numpy()
     ok_ag = bool(np.all(np.abs(got - ref) <= 1e-2 * np.maximum(1.0, np.abs(ref))))
@@ -343,39 +346,47 @@ def main() -> int:
         return 1
 
     # Traffic behind the L2 per launch, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
-    # `bench.py --serial-kernels 10`, each scaled by what the same counter reads for the 58.7 MB chunk
-    # copy (1.9964 and 1.0000 KiB per count); profiles/bench_c2ag_c3rs_pmc_traffic.txt.
-    traffic = {"rs": 821.4e6 + 67.1e6, "ag": 563.5e6 + 88.2e6}
+    # `bench.py --serial-kernels 5`, each scaled by what the same counter reads for the 176.2 MB chunk
+    # copy of the same run; profiles/bench_c4_pmc_traffic.txt.  None: not measured for this build.
+    traffic = TRAFFIC_BYTES
     alg = {"rs": rs.alg_bytes(), "ag": ag.alg_bytes()}
 
-    def kernel_line(name, which, w, ms):
+    def kernel_line(name, which, w, ms, bound):
         tf = w.flops / (ms * 1e-3) / 1e12
-        return {"kernel": name, "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic[which],
-                "traffic_note": "bytes per launch requested by the L2s from Infinity Cache/HBM; algorithmic %.1fe6"
-                                % (alg[which] / 1e6),
-                "avg_kernel_ms": round(ms, 4),
-                "alg_GBs": round(alg[which] / ms / 1e6, 1), "frac_hbm": round(alg[which] / ms / 1e6 / HBM_PEAK_GBS, 4)}
+        gbs = alg[which] / ms / 1e6
+        line = {"kernel": name, "bound": bound}
+        if bound == "mfma":
+            line.update({"achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)})
+        else:
+            line.update({"achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)})
+        line.update({"traffic": traffic[which],
+                     "traffic_note": "bytes per launch requested by the L2s from Infinity Cache/HBM; algorithmic %.1fe6"
+                                     % (alg[which] / 1e6),
+                     "avg_kernel_ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "alg_GBs": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
+        return line
 
-    # Both kernels of the step are the same bf16 MFMA GEMM (256x256x64 tiles); the roofline line is
-    # for the one that takes longer, the other follows as "second_kernel".  Both are bound by the
-    # MFMA pipes at these shapes (c3_rs: 96 us of MFMA work against 78 us of HBM traffic at peak).
-    lines = [kernel_line("gemm_kernel_dma<ReduceScatter epilogue> on c3_rs", "rs", rs.w, rs_ms),
-             kernel_line("gemm_kernel_dma<AllGather prologue> on c2_ag", "ag", ag.w, ag_ms)]
+    # The roofline line is for the kernel of the step that takes longer, each against the roof that
+    # binds it: the AllGather-GEMM (927.7 GFLOP over 390 MB + 352 MB gathered: MFMA), the
+    # GEMM-ReduceScatter of this shape (309 GFLOP over 1673.5 MB: 123 us of MFMA work against
+    # 209 us of memory traffic at peak: HBM).  The other one follows as "second_kernel".
+    lines = [kernel_line("GEMM kernel <ReduceScatter epilogue> on c4_rs", "rs", rs.w, rs_ms, "hbm"),
+             kernel_line("GEMM kernel <AllGather prologue> on c4_ag", "ag", ag.w, ag_ms, "mfma")]
     lines.sort(key=lambda d: -d["avg_kernel_ms"])
     roofline = dict(lines[0])
     roofline["second_kernel"] = lines[1]
 
     extra = {}
     if not args.no_extra:
-        extra["c2_ag"] = overlap_block(ag)
-        extra["c3_rs"] = overlap_block(rs)
+        extra["c4_ag"] = overlap_block(ag)
+        extra["c4_rs"] = overlap_block(rs)
         # Context, not a target and not part of the path: the vendor library's plain GEMM (hipBLASLt
         # behind torch.matmul) on the same operands, and on zeros.  With normally distributed operands
         # the chip runs into its power limit and every GEMM, this one included, slows down by a
         # fifth or so; the MFMA peak is not reachable on such data by any kernel.
         lib = {}
-        for key, A_, B_ in (("c2_ag", ag.A_agg, ag.B), ("c3_rs", rs.A, rs.B)):
+        for key, A_, B_ in (("c4_ag", ag.A_agg, ag.B), ("c4_rs", rs.A, rs.B)):
             out_ = torch.empty((A_.shape[0], B_.shape[1]), dtype=torch.bfloat16, device=dev)
             fl = 2.0 * A_.shape[0] * A_.shape[1] * B_.shape[1]
             t_data = time_calls(lambda: torch.matmul(A_, B_, out=out_), 20, 5)
@@ -387,18 +398,18 @@ def main() -> int:
         extra["library_gemm_context"] = lib
         # Eq. 1-2 once more with GEMM_non-split := the faster of this library's plain kernel and the
         # vendor library's GEMM on the same operands (the paper takes the fastest GEMM known)
-        for key in ("c2_ag", "c3_rs"):
+        for key in ("c4_ag", "c4_rs"):
             tg = min(extra[key]["ms_gemm_only"], lib[key]["ms_workload_operands"])
             ect_no = extra[key]["ms_unfused"] - tg
             extra[key]["overlap_efficiency_vs_fastest_gemm"] = (
                 None if ect_no <= 0 else round(1.0 - (extra[key]["ms_fused"] - tg) / ect_no, 4))
         del ag, rs
         torch.cuda.empty_cache()
-        for name in ("c4_ag", "c4_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):
+        for name in ("c2_ag", "c3_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):
             op = AG(W[name], 2) if W[name].op == "ag" else RS(W[name], 2)
             if name.startswith("c5"):
                 op.rotate_weights(9)        # 9 x 58.7 MB = 528 MB, twice the Infinity Cache
-            extra[name] = overlap_block(op, reps=20 if name.startswith("c4") else 50, graph=name.startswith("c5"))
+            extra[name] = overlap_block(op, reps=20 if not name.startswith("c5") else 50, graph=name.startswith("c5"))
             del op
             torch.cuda.empty_cache()
         # The tuner (Sec. 4.4) on three shapes: what it picks and what that gains over the library's own choice
@@ -444,6 +455,15 @@ def main() -> int:
                 del op
                 torch.cuda.empty_cache()
         extra["link_paced_1071GBps"] = link
+        # The SDMA-style driver of Alg. 3: hipMemcpyAsync per communication tile plus a stream write of its
+        # signal on the copy stream, the GEMM grid only waits (no workgroup moves data)
+        mc = {}
+        for name in ("c2_ag", "c4_ag"):
+            op = AG(W[name], 2, flags=fb.FLUX_FLAG_COPY_MEMCPY)
+            mc[name] = {"ms_fused": round(time_calls(op.fused, 20, 5), 4)}
+            del op
+            torch.cuda.empty_cache()
+        extra["copy_memcpy_driver"] = mc
     cpu_baseline = None
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host cores: full AllGather-GEMM of the timed shape
@@ -452,9 +472,9 @@ def main() -> int:
             cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
         except Exception:
             cores = len(os.sched_getaffinity(0))
-        # one step of the same workload (c2_ag AllGather-GEMM, then c3_rs GEMM-ReduceScatter with its
+        # one step of the same workload (c4_ag AllGather-GEMM, then c4_rs GEMM-ReduceScatter with its
         # 7 peer partials), whole matrices, repeated until about 10 s of CPU time have gone by
-        wa, wr = W["c2_ag"], W["c3_rs"]
+        wa, wr = W["c4_ag"], W["c4_rs"]
         chunks, Ba, _ = fi.make_ag_inputs(wa, 2)
         cn, Ban = [fi.to_numpy(c) for c in chunks], fi.to_numpy(Ba)
         Ar, Br, peers = fi.make_rs_inputs(wr, 2)
@@ -470,7 +490,7 @@ def main() -> int:
                 break
         cpu_baseline = {"value": round(reps * (wa.flops + wr.flops) / dt / 1e12, 4), "unit": "TFLOP/s",
                         "cores": cores, "kind": "oracle",
-                        "sample": f"{reps} whole steps of the timed workload (oracle ag_gemm on c2_ag + gemm_rs on c3_rs, "
+                        "sample": f"{reps} whole steps of the timed workload (oracle ag_gemm on c4_ag + gemm_rs on c4_rs, "
                                   f"fp64 numpy) in {dt:.1f} s"}
 
     out = {
@@ -478,8 +498,8 @@ def main() -> int:
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "c2_ag + c3_rs: Llama-2-70B-like MLP at TP=8, 4096 tokens - fused AllGather-GEMM "
-                               "[8x512,8192]x[8192,3584] then fused GEMM-ReduceScatter [4096,3584]x[3584,8192] + 7 peers",
+        "config": {"workload": "c4_ag + c4_rs: GPT-3-175B-like layer at TP=8, 8192 tokens - fused AllGather-GEMM "
+                               "[8x1024,12288]x[12288,4608] then fused GEMM-ReduceScatter [8192,1536]x[1536,12288] + 7 peers",
                    "virtual_ranks": 8, "rank": 2, "frac_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4)},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

@@ -49,11 +49,13 @@ extern "C" {
 
 #define FLUX_MAX_RANKS 16
 #define FLUX_MAX_M_TILES 1024      /* ceil(M / tile height) must not exceed this */
+#define FLUX_MAX_N (1 << 21)       /* N must stay below this */
 
 typedef enum {
   FLUX_OK = 0,
   FLUX_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, misaligned base */
-  FLUX_ERR_SHAPE = 2,         /* M % R != 0, N or K not a multiple of 8, sizes <= 0, or a matrix of 2^31 elements or more */
+  FLUX_ERR_SHAPE = 2,         /* M % R != 0, N or K not a multiple of 8, sizes <= 0, a matrix of 2^31 elements or
+                                 more, or N >= FLUX_MAX_N */
   FLUX_ERR_UNSUPPORTED = 3,   /* valid request the library has no kernel for */
   FLUX_ERR_WORKSPACE = 4,     /* workspace missing or smaller than flux_workspace_bytes */
   FLUX_ERR_HIP = 5,           /* a HIP runtime call failed (flux_last_hip_error has the code) */
@@ -151,7 +153,8 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
  * Stream capture: in the default form the call is kernel launches on compute_stream only (one, or
  * two if the local chunk has to be copied into place) and everything that changes from call to
  * call lives in the workspace, so it may be recorded in a HIP graph and replayed.  The forms with a
- * driver take a fresh claim id from the host on every call and are not meant to be replayed.
+ * driver take a fresh claim id from the host on every call: under stream capture they return
+ * FLUX_ERR_UNSUPPORTED.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
  *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
  *                   at A_agg + rank*(M/R)*K the local chunk is not copied.  16-byte alignment is
@@ -307,6 +310,34 @@ int flux_default_order(int32_t rank, int32_t R, int32_t* order);
  * the two is the kernel's duration including any in-kernel signal waits.
  */
 int flux_profile_next_gemm(void* start_event, void* stop_event);
+
+/*
+ * Tile trace (Sec. 4.1: which workgroup computes which tile, and in what order they are dispatched;
+ * Sec. 3.2: how long a tile waits for its signals).  The next flux_gemm_rs / flux_ag_gemm /
+ * flux_gemm_ref_unfused call made by this thread has every workgroup of its GEMM kernel write one
+ * record, indexed by workgroup id, into `records` (device memory, 16-byte aligned, at least
+ * 64 bytes times the grid size full_tiles + split_tiles * split_k of flux_split_plan; a call whose
+ * grid does not fit returns FLUX_ERR_WORKSPACE and enqueues nothing).  The request is consumed by
+ * that call; NULL cancels a pending one.  Clocks are the GPU's 100 MHz wall clock, comparable
+ * between workgroups of one launch.  Tracing costs a few stores per workgroup and makes the last
+ * stamp wait for the workgroup's stores; results are unchanged.
+ */
+typedef struct flux_trace_record {
+  uint32_t block;       /* workgroup id                                                          */
+  uint32_t m_tile;      /* TileCoord of Alg. 1 / Alg. 2 as the kernel computed it                */
+  uint32_t n_tile;
+  uint32_t k_part;      /* bits [15:0]: index of the K part; bit 16: the tile is cut along K     */
+  uint32_t die;         /* accelerator die (XCC) the workgroup ran on                            */
+  uint32_t hw_id;       /* raw hardware id register: wave [3:0], SIMD [5:4], CU [11:8], shader
+                           array [12], shader engine [15:13]                                     */
+  uint32_t tile;        /* index of the tile in TileCoord order                                  */
+  uint32_t reserved;
+  uint64_t t_start;     /* kernel entry                                                          */
+  uint64_t t_ready;     /* past the signal wait (AllGather; equals t_start otherwise)            */
+  uint64_t t_main_end;  /* main loop done                                                        */
+  uint64_t t_end;       /* epilogue (or K-part hand-over) done, stores acknowledged              */
+} flux_trace_record_t;
+int flux_trace_next_call(void* records, size_t bytes);
 
 const char* flux_status_string(int status);
 int flux_last_hip_error(void);       /* hipError_t of the most recent FLUX_ERR_HIP on this thread */

@@ -35,6 +35,7 @@ EXPORTS = [
     "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan", "flux_gemm_ref_chunked",
     "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
     "flux_autotune_rs", "flux_autotune_ag", "flux_autotune_workspace_bytes", "flux_autotune_signal_count",
+    "flux_trace_next_call",
 ]
 
 
@@ -93,6 +94,8 @@ def lib():
         L.flux_tile_config_info.argtypes = [C.c_int32, pi32, pi32, pi32]
         L.flux_default_order.argtypes = [C.c_int32, C.c_int32, pi32]
         L.flux_profile_next_gemm.argtypes = [vp, vp]
+        L.flux_trace_next_call.argtypes = [vp, C.c_size_t]
+        L.flux_trace_next_call.restype = C.c_int
         L.flux_status_string.argtypes = [C.c_int]
         L.flux_status_string.restype = C.c_char_p
         for name in ("flux_gemm_rs", "flux_ag_gemm", "flux_gemm_ref_unfused", "flux_query_status",
@@ -334,3 +337,14 @@ class HipEvent:
 def flux_profile_next_gemm(start: HipEvent | None, stop: HipEvent | None):
     _check(lib().flux_profile_next_gemm(None if start is None else start.handle,
                                         None if stop is None else stop.handle), "flux_profile_next_gemm")
+
+
+TRACE_RECORD_BYTES = 64
+
+
+def flux_trace_next_call(records):
+    """`records`: a device tensor of at least 64 bytes per workgroup of the next call's grid (an int64
+    tensor [grid, 8] reads as: word 0 = block | m_tile << 32, word 1 = n_tile | k_part << 32,
+    word 2 = die | hw_id << 32, word 3 = tile, words 4..7 = the four clocks), or None to cancel."""
+    n = 0 if records is None else records.numel() * records.element_size()
+    _check(lib().flux_trace_next_call(_ptr(records), n), "flux_trace_next_call")

@@ -4,7 +4,6 @@
 #include <atomic>
 #include <cstdio>
 #include <cstring>
-#include <mutex>
 #include <vector>
 
 #include "flux_internal.h"
@@ -25,6 +24,8 @@ constexpr unsigned long long DEFAULT_TIMEOUT_TICKS = 1000000000ull;   // 10 s at
 
 static thread_local int g_last_hip_error = 0;
 static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+static thread_local flux_trace_record_t* g_trace_buf = nullptr;
+static thread_local size_t g_trace_bytes = 0;
 
 #define FLUX_HIP(expr)                                  \
   do {                                                  \
@@ -199,6 +200,9 @@ static int validate_problem(int op, const flux_problem_t* p) {
   // every matrix stays below 2^31 elements: the kernels address operands through 32-bit buffer offsets
   if ((long long)p->M * p->N >= (1ll << 31) || (long long)p->M * p->K >= (1ll << 31) ||
       (long long)p->K * p->N >= (1ll << 31)) return FLUX_ERR_SHAPE;
+  // the reduce-scatter epilogue addresses a tile of fp32 partials (up to 256 rows) through a signed
+  // 31-bit offset from the tile's origin: 256 rows of 4-byte elements must stay below 2^31 bytes
+  if (p->N >= FLUX_MAX_N) return FLUX_ERR_SHAPE;
   if (p->out_dtype != FLUX_BF16 && p->out_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
   if (op == FLUX_OP_RS && p->partial_dtype != FLUX_BF16 && p->partial_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
   if (p->tile_config < 0 || p->tile_config > NUM_CFGS) return FLUX_ERR_INVALID_ARG;
@@ -491,6 +495,18 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
   }
 }
 
+// A pending tile-trace request of this thread: checked (and consumed) before anything is enqueued.
+static int take_trace(const Plan& pl, flux_trace_record_t** out) {
+  *out = g_trace_buf;
+  const size_t bytes = g_trace_bytes;
+  g_trace_buf = nullptr;
+  g_trace_bytes = 0;
+  if (*out == nullptr) return FLUX_OK;
+  const size_t grid = (size_t)pl.full_tiles + (size_t)pl.split_tiles * pl.split_k;
+  if (bytes < grid * sizeof(flux_trace_record_t)) { *out = nullptr; return FLUX_ERR_WORKSPACE; }
+  return FLUX_OK;
+}
+
 static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hipStream_t s) {
   const int grid = pl.full_tiles + pl.split_tiles * pl.split_k;
   hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
@@ -546,11 +562,12 @@ static uint32_t next_call_id() {
   return id;
 }
 
-static std::mutex g_event_mu;
-static hipEvent_t g_fork = nullptr, g_join = nullptr;
+// Fork/join and per-chunk events belong to the calling host thread: a wait enqueued on an event
+// refers to the record that preceded it on that thread, so calls of one thread may share a set,
+// while two threads recording the same event could order a stream after the wrong fork.
+static thread_local hipEvent_t g_fork = nullptr, g_join = nullptr;
 
 static int get_events(hipEvent_t* fork, hipEvent_t* join) {
-  std::lock_guard<std::mutex> lk(g_event_mu);
   if (g_fork == nullptr) {
     FLUX_HIP(hipEventCreateWithFlags(&g_fork, hipEventDisableTiming));
     FLUX_HIP(hipEventCreateWithFlags(&g_join, hipEventDisableTiming));
@@ -560,10 +577,9 @@ static int get_events(hipEvent_t* fork, hipEvent_t* join) {
   return FLUX_OK;
 }
 
-static hipEvent_t g_chunk_events[FLUX_MAX_RANKS] = {nullptr};
+static thread_local hipEvent_t g_chunk_events[FLUX_MAX_RANKS] = {nullptr};
 
 static int get_chunk_events(hipEvent_t** events) {
-  std::lock_guard<std::mutex> lk(g_event_mu);
   for (int i = 0; i < FLUX_MAX_RANKS; ++i)
     if (g_chunk_events[i] == nullptr) FLUX_HIP(hipEventCreateWithFlags(&g_chunk_events[i], hipEventDisableTiming));
   *events = g_chunk_events;
@@ -583,6 +599,13 @@ extern "C" {
 int flux_version(void) { return 1; }
 
 int flux_last_hip_error(void) { return g_last_hip_error; }
+
+int flux_trace_next_call(void* records, size_t bytes) {
+  if (records != nullptr && (!aligned16(records) || bytes < sizeof(flux_trace_record_t))) return FLUX_ERR_INVALID_ARG;
+  g_trace_buf = static_cast<flux_trace_record_t*>(records);
+  g_trace_bytes = records ? bytes : 0;
+  return FLUX_OK;
+}
 
 int flux_profile_next_gemm(void* start_event, void* stop_event) {
   if ((start_event == nullptr) != (stop_event == nullptr)) return FLUX_ERR_INVALID_ARG;
@@ -708,9 +731,13 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   }
   st = check_workspace(pl, FLUX_OP_RS, workspace, workspace_bytes);
   if (st != FLUX_OK) return st;
+  flux_trace_record_t* trace;
+  st = take_trace(pl, &trace);
+  if (st != FLUX_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);
   GemmArgs a;
   fill_common(&a, p, pl, pl.split_k > 1 ? workspace : nullptr);
+  a.trace = trace;
   a.A = static_cast<const __bf16*>(A);
   a.B = static_cast<const __bf16*>(B);
   // the kernel wants the R-1 peers packed, ascending rank
@@ -740,11 +767,15 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   if (st != FLUX_OK) return st;
   st = check_workspace(pl, FLUX_OP_AG, workspace, workspace_bytes);
   if (st != FLUX_OK) return st;
+  flux_trace_record_t* trace;
+  st = take_trace(pl, &trace);
+  if (st != FLUX_OK) return st;
   hipStream_t cs = static_cast<hipStream_t>(compute_stream);
   hipStream_t xs = static_cast<hipStream_t>(copy_stream);
 
   GemmArgs a;
   fill_common(&a, p, pl, workspace);
+  a.trace = trace;
   a.A = static_cast<const __bf16*>(A_agg);
   a.B = static_cast<const __bf16*>(B);
   a.C = C;
@@ -775,6 +806,18 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   }
   build_tile_map(FLUX_OP_AG, p, pl, order, &a.tm);
 
+  const bool driver_form = !(pl.copy_self || p->R == 1);
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  if (driver_form) {
+    // The forms with a driver beside the grid take a claim id from the host and fork onto a second
+    // stream: recorded in a graph, every replay would find all pieces claimed already.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    FLUX_HIP(hipStreamIsCapturing(cs, &cap));
+    if (cap != hipStreamCaptureStatusNone) return FLUX_ERR_UNSUPPORTED;
+    st = get_events(&ev_fork, &ev_join);
+    if (st != FLUX_OK) return st;
+  }
+
   // local chunk (its signal is preset, so it must be in place before the kernel starts)
   const __bf16* local_dst = static_cast<const __bf16*>(A_agg) + (size_t)p->rank * chunk_elems;
   if (A_chunks[p->rank] != static_cast<const void*>(local_dst)) {
@@ -782,13 +825,10 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
     st = launch_copy(p, pl, A_chunks, A_agg, &self, 1, false, nullptr, nullptr, 0, cs);
     if (st != FLUX_OK) return st;
   }
-  if (pl.copy_self || p->R == 1) {
+  if (!driver_form) {
     // nothing runs beside the GEMM grid: no fork, no join
     return launch_gemm(pl, EPI_PLAIN, 1, a, cs);
   }
-  hipEvent_t ev_fork, ev_join;
-  st = get_events(&ev_fork, &ev_join);
-  if (st != FLUX_OK) return st;
   // fork: the copy driver may start once everything queued so far on compute_stream is done
   FLUX_HIP(hipEventRecord(ev_fork, cs));
   FLUX_HIP(hipStreamWaitEvent(xs, ev_fork, 0));
@@ -832,8 +872,14 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
       if (workspace == nullptr || workspace_bytes < workspace_need(pl)) return FLUX_ERR_WORKSPACE;
     }
   }
+  flux_trace_record_t* trace = nullptr;
+  if (do_gemm) {
+    st = take_trace(pl, &trace);
+    if (st != FLUX_OK) return st;
+  }
   GemmArgs a;
   fill_common(&a, p, pl, pl.split_k > 1 ? workspace : nullptr);
+  a.trace = trace;
   a.B = static_cast<const __bf16*>(B);
   a.C = C;
   // natural tile order for the baseline GEMM, die remap kept

@@ -127,6 +127,7 @@ struct GemmArgs {
   float* sk_partials;             // [split_k][split_tiles][BM*BN] fp32
   uint32_t* sk_counters;          // [tiles]
   int32_t partial_f32, out_f32;
+  flux_trace_record_t* trace;     // tile trace, one record per workgroup; null: none
   // ---- arrays ----
   void* outs[FLUX_MAX_RANKS];
   const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
@@ -158,6 +159,39 @@ __device__ __forceinline__ void map_block(const GemmArgs& a, int b, int& tile, i
     split = r / a.split_tiles;
     is_split = a.split_k > 1;
   }
+}
+
+// ---- tile trace -------------------------------------------------------------------------------
+// With a trace buffer every workgroup leaves one record: which tile and K part it computed, on which
+// die and compute unit, and the 100 MHz wall clock at four points (kernel entry, past the signal
+// wait, main loop done, epilogue stores acknowledged).  Thread 0 writes; without a buffer the cost
+// is one scalar test per point.
+enum : int { TRACE_START = 0, TRACE_READY = 1, TRACE_MAIN_END = 2, TRACE_END = 3 };
+
+__device__ __forceinline__ void trace_begin(const GemmArgs& a, int tile, int mt, int nt, int split, bool is_split) {
+  if (a.trace == nullptr || threadIdx.x != 0) return;
+  flux_trace_record_t* r = a.trace + blockIdx.x;
+  r->block = blockIdx.x;
+  r->m_tile = (uint32_t)mt;
+  r->n_tile = (uint32_t)nt;
+  r->k_part = (uint32_t)split | (is_split ? 0x10000u : 0u);
+  r->die = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) ;       // XCC_ID, bits [3:0]
+  r->hw_id = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));      // HW_ID, all 32 bits
+  r->tile = (uint32_t)tile;
+  r->reserved = 0;
+  const uint64_t t = wall_clock64();
+  r->t_start = t; r->t_ready = t; r->t_main_end = t; r->t_end = t;
+}
+
+__device__ __forceinline__ void trace_stamp(const GemmArgs& a, int point) {
+  if (a.trace == nullptr) return;
+  if (point == TRACE_END) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores are acknowledged
+  if (threadIdx.x != 0) return;
+  flux_trace_record_t* r = a.trace + blockIdx.x;
+  const uint64_t t = wall_clock64();
+  if (point == TRACE_READY) r->t_ready = t;
+  if (point <= TRACE_MAIN_END) r->t_main_end = t;
+  r->t_end = t;
 }
 
 // ---- LDS swizzles ---------------------------------------------------------------------------
@@ -380,7 +414,8 @@ __device__ __forceinline__ void epilogue_block(const GemmArgs& a, void* const* l
       ok[b] = !EDGE || (m0 + row < a.M && n0 + col < a.N);
       if (EPI == EPI_RS) {
         // a lane outside the matrix gets an offset past the records: zeros, no memory access
-        const int voff = ok[b] ? (row * a.N + col) * (PF32 ? 4 : 2) : (int)0x80000000;
+        // (tile-relative: row < BM <= 256 and N < 2^21, so the byte offset stays below 2^31)
+        const int voff = ok[b] ? (int)(((uint32_t)row * (uint32_t)a.N + (uint32_t)col) * (PF32 ? 4u : 2u)) : (int)0x80000000;
 #pragma unroll
         for (int j = 0; j < NP; ++j)
 #pragma unroll
@@ -795,6 +830,7 @@ template <class C, int EPI, bool EDGE>
 __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem, int* lds_misc, void* const* lds_outs,
                                           f32x16 (&acc)[C::MI][C::NI], int tile, int split, bool is_split,
                                           int m0, int n0, int tid, int lane, int wave, int wm, int wn) {
+  trace_stamp(a, TRACE_MAIN_END);
   // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
   if (is_split) {
     const int st = tile - a.full_tiles;            // index among the split tiles
@@ -833,6 +869,7 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
       *lds_last = last;
     }
     __syncthreads();
+    trace_stamp(a, TRACE_END);        // a workgroup that is not the tile's last ends here
     if (!*lds_last) return;
     // The sum always runs over the parked partials in split order, whichever workgroup happens
     // to be last, so results do not depend on arrival timing.  (Keeping the own part in registers
@@ -904,6 +941,7 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
     if (a.partial_f32) epilogue_all<C, EPI, EDGE, true, 1, NP_ALL>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
     else epilogue_all<C, EPI, EDGE, false, 1, NP_ALL>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
   }
+  trace_stamp(a, TRACE_END);
 }
 
 template <class C, int EPI, bool WAIT, bool EDGE>
@@ -919,6 +957,7 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
   tile_coord(a.tm, tile, mt, nt);
   const int m0 = mt * C::BM, n0 = nt * C::BN;
   const int m1 = m0 + C::BM < a.M ? m0 + C::BM : a.M;
+  trace_begin(a, tile, mt, nt, split, is_split);
 
   // output slices by rank (reduce-scatter) or chunk sources by rank (all-gather)
   void** lds_outs = reinterpret_cast<void**>(smem + C::PTRS_OFF);
@@ -928,7 +967,8 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel(const GemmArgs a) {
 
   if (WAIT) {
     transfer_own_pieces(a, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs);
-    if (!wait_signals(a, m0, m1, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs)) return;
+    if (!wait_signals(a, m0, m1, reinterpret_cast<int*>(smem + C::MISC_OFF), lds_outs)) { trace_stamp(a, TRACE_END); return; }
+    trace_stamp(a, TRACE_READY);
   }
 
   const int k_begin = is_split ? split * a.k_per_split : 0;
@@ -993,18 +1033,23 @@ struct DmaLoader {
   static_assert(NW % 2 == 0 && (RPI * NW) % 4 == 0, "swizzle must not depend on the instruction index");
   static_assert(C::BM % (A_RPI * NW) == 0 && C::BK % (RPI * NW) == 0 && 512 % C::BN == 0, "loader shape");
 
+  // Offsets into A and B are unsigned 32-bit byte offsets (a matrix has fewer than 2^31 elements, so
+  // fewer than 2^32 bytes); the hardware adds the vector and the scalar part as unsigned numbers.
   __amdgpu_buffer_rsrc_t ra, rb;
-  int voff_a, voff_b;
+  uint32_t voff_a, voff_b;
+  uint32_t K2, N2;               // row pitches in bytes
 
   __device__ __forceinline__ void init(const GemmArgs& a, int m0, int n0, int wave, int lane) {
     ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.A), 0, (int)((unsigned)a.M * (unsigned)a.K * 2u), 0x00027000);
     rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0, (int)((unsigned)a.K * (unsigned)a.N * 2u), 0x00027000);
     const int r_in = lane / C::A_SLOTS, sp = lane % C::A_SLOTS;
     const int row = A_RPI * wave + r_in;
-    voff_a = ((m0 + row) * a.K + ((sp ^ swz_a<C::A_SLOTS>(row)) << 3)) * 2;
+    K2 = (uint32_t)a.K * 2u;
+    N2 = (uint32_t)a.N * 2u;
+    voff_a = (uint32_t)(m0 + row) * K2 + ((uint32_t)(sp ^ swz_a<C::A_SLOTS>(row)) << 4);
     const int k_in = lane / C::B_SLOTS, spb = lane % C::B_SLOTS;
     const int k = RPI * wave + k_in;
-    voff_b = (k * a.N + n0 + ((spb ^ swz_b<C::B_SLOTS>(k)) << 3)) * 2;
+    voff_b = (uint32_t)k * N2 + (uint32_t)n0 * 2u + ((uint32_t)(spb ^ swz_b<C::B_SLOTS>(k)) << 4);
   }
 
   static constexpr int N_INSTR = A_INSTR + B_INSTR;
@@ -1012,12 +1057,12 @@ struct DmaLoader {
   // same with an index that is constant after loop unrolling
   __device__ __forceinline__ void issue_dyn(int idx, const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
     if (idx < A_INSTR) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (idx * NW + wave) * 1024), 16, voff_a,
-                                               (k0 + idx * A_RPI * NW * a.K) * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (idx * NW + wave) * 1024), 16, (int)voff_a,
+                                               (int)((uint32_t)k0 * 2u + (uint32_t)(idx * A_RPI * NW) * K2), 0, 0);
     } else {
       const int p = idx - A_INSTR;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
-                                               (k0 + p * RPI * NW) * a.N * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, (int)voff_b,
+                                               (int)((uint32_t)(k0 + p * RPI * NW) * N2), 0, 0);
     }
   }
 
@@ -1025,15 +1070,15 @@ struct DmaLoader {
   __device__ __forceinline__ void issue_a(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
 #pragma unroll
     for (int p = 0; p < A_INSTR; ++p)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (p * NW + wave) * 1024), 16, voff_a,
-                                               (k0 + p * A_RPI * NW * a.K) * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t*)(stage + (p * NW + wave) * 1024), 16, (int)voff_a,
+                                               (int)((uint32_t)k0 * 2u + (uint32_t)(p * A_RPI * NW) * K2), 0, 0);
     __builtin_amdgcn_sched_barrier(0);
   }
   __device__ __forceinline__ void issue_b(const GemmArgs& a, unsigned char* stage, int k0, int wave) const {
 #pragma unroll
     for (int p = 0; p < B_INSTR; ++p)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, voff_b,
-                                               (k0 + p * RPI * NW) * a.N * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, (int)voff_b,
+                                               (int)((uint32_t)(k0 + p * RPI * NW) * N2), 0, 0);
     // keep the loads where they are written: scheduled late they would be issued just before
     // the wait for them, and nothing would overlap
     __builtin_amdgcn_sched_barrier(0);
@@ -1245,13 +1290,15 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   int mt, nt;
   tile_coord(a.tm, tile, mt, nt);
   const int m0 = mt * C::BM, n0 = nt * C::BN;
+  trace_begin(a, tile, mt, nt, split, is_split);
 
   if (EPI == EPI_RS || WAIT) {      // output slices (reduce-scatter) or chunk sources (all-gather), by rank
     fill_lds_outs(a, lds_outs, tid);
   }
   if (WAIT) {
     transfer_own_pieces(a, lds_misc, lds_outs);
-    if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) return;
+    if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) { trace_stamp(a, TRACE_END); return; }
+    trace_stamp(a, TRACE_READY);
   }
 
   const int k_begin = is_split ? split * a.k_per_split : 0;
@@ -1352,6 +1399,7 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
   int mt, nt;
   tile_coord(a.tm, tile, mt, nt);
   const int m0 = mt * C::BM, n0 = nt * C::BN;
+  trace_begin(a, tile, mt, nt, split, is_split);
 
   if (EPI == EPI_RS || WAIT) {
     fill_lds_outs(a, lds_outs, tid);
@@ -1379,8 +1427,10 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_deep(const Gemm
     const int m1 = (!MASK || m0 + C::BM < a.M) ? m0 + C::BM : a.M;
     if (!wait_signals(a, m0, m1, lds_misc, lds_outs)) {
       wait_vm_at_most<0>();        // nothing of this workgroup is left in flight towards its LDS
+      trace_stamp(a, TRACE_END);
       return;
     }
+    trace_stamp(a, TRACE_READY);
 #pragma unroll
     for (int j = 0; j < NS - 1; ++j) ld.issue_a(a, st[j], k_begin + (j < last ? j : last) * C::BK, wave);
   } else {

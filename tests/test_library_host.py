@@ -218,3 +218,39 @@ def test_autotune_sizes_cover_every_candidate():
     assert fb.flux_autotune_signal_count(fb.problem(64, 3584, 8192, 8, 2)) == 8
     assert fb.flux_autotune_workspace_bytes(fb.FLUX_OP_RS, fb.problem(64, 8192, 3584, 8, 2)) >= \
         fb.flux_workspace_bytes(fb.FLUX_OP_RS, fb.problem(64, 8192, 3584, 8, 2))
+
+
+def test_offsets_stay_in_32_bits_at_the_edges_of_validation():
+    """The kernels address A and B through unsigned 32-bit byte offsets and a tile of partials through a
+    signed 31-bit one: validation admits only shapes for which that holds."""
+    ok = fb.problem(16384, 65536, 65536, 8, 0)                 # M*K = M*N = 2^30, K*N = 2^32: too many
+    with pytest.raises(fb.FluxError) as e:
+        fb.flux_tile_shape(fb.FLUX_OP_RS, ok)
+    assert e.value.status == fb.FLUX_ERR_SHAPE
+    # largest admitted element counts: 2^31 - 2^15 elements per matrix -> byte offsets below 2^32
+    p = fb.problem(32768, 65528, 65528, 8, 0)
+    assert 32768 * 65528 < 2 ** 31 and 65528 * 65528 >= 2 ** 31
+    with pytest.raises(fb.FluxError):
+        fb.flux_tile_shape(fb.FLUX_OP_RS, p)
+    q = fb.problem(32768, 65528, 32768, 8, 0)
+    assert (q.M * q.K) * 2 < 2 ** 32 and (q.K * q.N) * 2 < 2 ** 32
+    assert fb.flux_tile_shape(fb.FLUX_OP_RS, q).tile_m == 256
+    # a tile of 256 rows of fp32 partials: 256 * N * 4 bytes must stay below 2^31
+    wide = fb.problem(8, 1 << 21, 8, 8, 0)
+    with pytest.raises(fb.FluxError) as e:
+        fb.flux_tile_shape(fb.FLUX_OP_RS, wide)
+    assert e.value.status == fb.FLUX_ERR_SHAPE
+    assert fb.flux_tile_shape(fb.FLUX_OP_RS, fb.problem(8, (1 << 21) - 8, 8, 8, 0)).tile_n > 0
+    assert 256 * ((1 << 21) - 8) * 4 < 2 ** 31
+
+
+def test_trace_request_arguments():
+    import ctypes as C
+    L = fb.lib()
+    assert L.flux_trace_next_call(None, 0) == fb.FLUX_OK                      # cancels
+    assert L.flux_trace_next_call(8, 4096) == fb.FLUX_ERR_INVALID_ARG         # misaligned
+    assert L.flux_trace_next_call(4096, 32) == fb.FLUX_ERR_INVALID_ARG        # not even one record
+    assert fb.TRACE_RECORD_BYTES == 64
+    # a pending request does not survive a call that is rejected for its own reasons ...
+    assert L.flux_trace_next_call(4096, 1 << 20) == fb.FLUX_OK
+    assert L.flux_trace_next_call(None, 0) == fb.FLUX_OK
