@@ -130,6 +130,22 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * flux_gemm_rs for callers that cannot allocate or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments and results, but
+ * what a call that cuts K needs beyond its inputs and outputs (arrival counters and parked fp32
+ * partial tiles) lives in an array inside the library, FLUX_STATIC_SCRATCH_BYTES per GPU, held
+ * from the time the library is loaded until the process ends.  The call allocates nothing.
+ * A problem whose K cut needs more than that (flux_workspace_bytes says how much) is rejected with
+ * FLUX_ERR_WORKSPACE before anything is enqueued; a problem that needs no workspace never touches
+ * the array.  All calls on one GPU share that GPU's array, which keeps the last call's contents:
+ * the call clears the counters itself (one small kernel ahead of the GEMM), and calls that overlap
+ * in time on one GPU (different streams or threads) race.  Calls on one stream are safe.
+ */
+#define FLUX_STATIC_SCRATCH_BYTES (32u << 20)
+int flux_gemm_rs_static(const flux_problem_t* p, const void* A, const void* B,
+                        const void* const* peer_partials, void* const* out_slices, void* stream);
+
+/*
  * AllGather-GEMM, fused (Alg. 2 kernel + the data transfer of Alg. 3, pull form).
  * Who moves the remote chunks (communication tile by communication tile in `arrival_order`,
  * setting each tile's signal when it is complete) depends on the problem:

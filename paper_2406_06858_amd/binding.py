@@ -35,7 +35,7 @@ EXPORTS = [
     "flux_version", "flux_profile_next_gemm", "flux_init_buffers", "flux_split_plan", "flux_gemm_ref_chunked",
     "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
     "flux_autotune_rs", "flux_autotune_ag", "flux_autotune_workspace_bytes", "flux_autotune_signal_count",
-    "flux_trace_next_call",
+    "flux_trace_next_call", "flux_gemm_rs_static",
 ]
 
 
@@ -71,6 +71,8 @@ def lib():
         vp, pvp = C.c_void_p, C.POINTER(C.c_void_p)
         pp, pi32 = C.POINTER(flux_problem_t), C.POINTER(C.c_int32)
         L.flux_gemm_rs.argtypes = [pp, vp, vp, pvp, pvp, vp, C.c_size_t, vp]
+        L.flux_gemm_rs_static.argtypes = [pp, vp, vp, pvp, pvp, vp]
+        L.flux_gemm_rs_static.restype = C.c_int
         L.flux_ag_gemm.argtypes = [pp, pvp, vp, vp, vp, vp, pi32, vp, C.c_size_t, vp, vp]
         L.flux_gemm_ref_unfused.argtypes = [C.c_int, C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, vp, C.c_size_t, vp]
         L.flux_gemm_ref_chunked.argtypes = [C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, pi32, vp, C.c_size_t, vp, vp]
@@ -159,6 +161,15 @@ def flux_gemm_rs(p, A, B, peer_partials, out_slices, workspace=None, stream=None
     _check(lib().flux_gemm_rs(C.byref(p), _ptr(A), _ptr(B),
                               None if peer_partials is None else _ptr_list(peer_partials), _ptr_list(out_slices),
                               _ptr(workspace), ws_bytes, _stream(stream)), "flux_gemm_rs")
+
+
+FLUX_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def flux_gemm_rs_static(p, A, B, peer_partials, out_slices, stream=None):
+    _check(lib().flux_gemm_rs_static(C.byref(p), _ptr(A), _ptr(B),
+                                     None if peer_partials is None else _ptr_list(peer_partials), _ptr_list(out_slices),
+                                     _stream(stream)), "flux_gemm_rs_static")
 
 
 def flux_ag_gemm(p, A_chunks, A_agg, B, Cout, signals, arrival_order, workspace, compute_stream, copy_stream):

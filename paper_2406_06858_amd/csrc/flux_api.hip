@@ -587,6 +587,35 @@ static int get_chunk_events(hipEvent_t** events) {
 }
 
 
+int gemm_rs_planned(const flux_problem_t* p, const Plan& pl, const void* A, const void* B, const void* const* peer_partials,
+                    void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream);
+
+}  // namespace flux
+
+// Scratch memory of flux_gemm_rs_static: one array per GPU the library's code object is loaded on,
+// there until the process ends.  In host code the array's name only stands for the symbol; its
+// address on the current device is looked up once per device and used from then on.
+static __device__ __align__(256) unsigned char flux_static_scratch[FLUX_STATIC_SCRATCH_BYTES];
+
+namespace flux {
+
+constexpr int MAX_DEVICES = 64;
+static std::atomic<void*> g_scratch_ptr[MAX_DEVICES];
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  FLUX_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return FLUX_ERR_UNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    FLUX_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(flux_static_scratch)));   // the current device's copy
+    if (p == nullptr) return FLUX_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);              // (a racing thread stores the same address)
+  }
+  *out = p;
+  return FLUX_OK;
+}
+
 }  // namespace flux
 
 // ------------------------------------------------------------------------------------------
@@ -721,6 +750,37 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   Plan pl;
   int st = make_plan(FLUX_OP_RS, p, &pl);
   if (st != FLUX_OK) return st;
+  return gemm_rs_planned(p, pl, A, B, peer_partials, out_slices, workspace, workspace_bytes, stream);
+}
+
+int flux_gemm_rs_static(const flux_problem_t* p, const void* A, const void* B, const void* const* peer_partials,
+                        void* const* out_slices, void* stream) {
+  Plan pl;
+  int st = make_plan(FLUX_OP_RS, p, &pl);
+  if (st != FLUX_OK) return st;
+  const size_t need = pl.split_k > 1 ? workspace_need(pl) : 0;
+  if (need > (size_t)FLUX_STATIC_SCRATCH_BYTES) return FLUX_ERR_WORKSPACE;
+  if (need == 0) return gemm_rs_planned(p, pl, A, B, peer_partials, out_slices, nullptr, 0, stream);
+  void* scratch = nullptr;
+  st = static_scratch(&scratch);
+  if (st != FLUX_OK) return st;
+  // The array keeps what the last call on this GPU left in it.  The arrival counters of the K-cut
+  // tiles must start at zero (a call that was interrupted may have left some behind); the partials
+  // are written before they are read.  A small kernel, not a memset: callers may be capturing.
+  const int words = (int)(WS_HEADER_BYTES / 4);
+  hipLaunchKernelGGL(preset_kernel, dim3((words + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     (uint32_t*)nullptr, 0, 0, 0, static_cast<uint32_t*>(scratch), words);
+  FLUX_HIP(hipGetLastError());
+  return gemm_rs_planned(p, pl, A, B, peer_partials, out_slices, scratch, (size_t)FLUX_STATIC_SCRATCH_BYTES, stream);
+}
+
+}  // extern "C"
+
+namespace flux {
+
+int gemm_rs_planned(const flux_problem_t* p, const Plan& pl, const void* A, const void* B, const void* const* peer_partials,
+                    void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream) {
+  int st;
   const bool atomic = p->flags & FLUX_FLAG_RS_ATOMIC;
   if (atomic && ((p->flags & FLUX_FLAG_RS_WRITE_ONLY) || p->out_dtype != FLUX_F32)) return FLUX_ERR_UNSUPPORTED;
   const bool write_only = (p->flags & FLUX_FLAG_RS_WRITE_ONLY) || atomic;   // neither form reads peers
@@ -749,6 +809,10 @@ int flux_gemm_rs(const flux_problem_t* p, const void* A, const void* B, const vo
   build_tile_map(FLUX_OP_RS, p, pl, nullptr, &a.tm);
   return launch_gemm(pl, EPI_RS, 0, a, s);
 }
+
+}  // namespace flux
+
+extern "C" {
 
 int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_agg, const void* B, void* C,
                  uint32_t* signals, const int32_t* arrival_order, void* workspace, size_t workspace_bytes,
