@@ -253,6 +253,39 @@ int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_orde
 int flux_rs_reduce_slice(const flux_problem_t* p, const void* const* staged, void* out, void* stream);
 
 /*
+ * Reduce with tile-ready counters (Sec. 4.2, "Reduce", second form: the producers write their tiles
+ * to the destination and raise a flag per tile; a reducer on the destination takes the tiles as
+ * they come up).  Every rank's GEMM scatters its product by owner (the Write branch of Alg. 1) and
+ * counts each tile in; the owner's reducer waits tile by tile and sums the staged partials.
+ *
+ * flux_gemm_rs_notify   producer: flux_gemm_rs with FLUX_FLAG_RS_WRITE_ONLY (implied) whose stores go
+ *                       through to memory and whose workgroups, after their tile's last store is
+ *                       acknowledged, add one to tile_ready[m_tile * tiles_n + n_tile] (the tile grid of
+ *                       the whole [M,N] product under the call's tile configuration; flux_rs_ready_count
+ *                       entries).  A tile cut along K is counted once, by the workgroup that writes it.
+ * flux_rs_reduce_slice_ready
+ *                       consumer for the slice of rank p->rank: `staged` as for flux_rs_reduce_slice; for
+ *                       every tile that overlaps the slice it waits until the counter has reached
+ *                       `producers` (bounded by p->spin_timeout_ticks like a signal wait: a tile that
+ *                       times out is left unwritten and reported through flux_query_status on `workspace`,
+ *                       detail = index of the counter), then writes out = sum of the staged rows in rank
+ *                       order, fp32, converted once.  It must be given the same M, N, K, R and tile_config
+ *                       as the producers (the counters are per producer tile).  `workspace`: device,
+ *                       at least 32 KiB, cleared once with flux_init_buffers(FLUX_OP_RS, ...).
+ * tile_ready            device uint32[flux_rs_ready_count(p)], zero before the first producer starts;
+ *                       neither side resets it (on one GPU the counters of a tile that spans several
+ *                       slices are shared by their owners): clear it between rounds.
+ * The consumer may be enqueued before, beside or after the producers; enqueue it on a stream of its own
+ * AFTER the producers so that it can never sit ahead of one of them in a hardware queue.
+ */
+int flux_gemm_rs_notify(const flux_problem_t* p, const void* A, const void* B, void* const* out_slices,
+                        uint32_t* tile_ready, void* workspace, size_t workspace_bytes, void* stream);
+int flux_rs_reduce_slice_ready(const flux_problem_t* p, const void* const* staged, void* out,
+                               uint32_t* tile_ready, int32_t producers,
+                               void* workspace, size_t workspace_bytes, void* stream);
+int32_t flux_rs_ready_count(const flux_problem_t* p);
+
+/*
  * Medium-grained baseline: the decomposition the paper compares against (Sec. 2.2): the GEMM is
  * cut into R GEMMs of M/R rows, one per slice / chunk, and the communication of one part runs on
  * comm_stream beside the GEMM of the next on compute_stream.

@@ -36,6 +36,7 @@ EXPORTS = [
     "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
     "flux_autotune_rs", "flux_autotune_ag", "flux_autotune_workspace_bytes", "flux_autotune_signal_count",
     "flux_trace_next_call", "flux_gemm_rs_static",
+    "flux_gemm_rs_notify", "flux_rs_reduce_slice_ready", "flux_rs_ready_count",
 ]
 
 
@@ -73,6 +74,12 @@ def lib():
         L.flux_gemm_rs.argtypes = [pp, vp, vp, pvp, pvp, vp, C.c_size_t, vp]
         L.flux_gemm_rs_static.argtypes = [pp, vp, vp, pvp, pvp, vp]
         L.flux_gemm_rs_static.restype = C.c_int
+        L.flux_gemm_rs_notify.argtypes = [pp, vp, vp, pvp, vp, vp, C.c_size_t, vp]
+        L.flux_gemm_rs_notify.restype = C.c_int
+        L.flux_rs_reduce_slice_ready.argtypes = [pp, pvp, vp, vp, C.c_int32, vp, C.c_size_t, vp]
+        L.flux_rs_reduce_slice_ready.restype = C.c_int
+        L.flux_rs_ready_count.argtypes = [pp]
+        L.flux_rs_ready_count.restype = C.c_int32
         L.flux_ag_gemm.argtypes = [pp, pvp, vp, vp, vp, vp, pi32, vp, C.c_size_t, vp, vp]
         L.flux_gemm_ref_unfused.argtypes = [C.c_int, C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, vp, C.c_size_t, vp]
         L.flux_gemm_ref_chunked.argtypes = [C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, pi32, vp, C.c_size_t, vp, vp]
@@ -170,6 +177,22 @@ def flux_gemm_rs_static(p, A, B, peer_partials, out_slices, stream=None):
     _check(lib().flux_gemm_rs_static(C.byref(p), _ptr(A), _ptr(B),
                                      None if peer_partials is None else _ptr_list(peer_partials), _ptr_list(out_slices),
                                      _stream(stream)), "flux_gemm_rs_static")
+
+
+def flux_rs_ready_count(p) -> int:
+    return int(lib().flux_rs_ready_count(C.byref(p)))
+
+
+def flux_gemm_rs_notify(p, A, B, out_slices, tile_ready, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().flux_gemm_rs_notify(C.byref(p), _ptr(A), _ptr(B), _ptr_list(out_slices), _ptr(tile_ready),
+                                     _ptr(workspace), ws_bytes, _stream(stream)), "flux_gemm_rs_notify")
+
+
+def flux_rs_reduce_slice_ready(p, staged, out, tile_ready, producers, workspace, stream=None):
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib().flux_rs_reduce_slice_ready(C.byref(p), _ptr_list(staged), _ptr(out), _ptr(tile_ready), producers,
+                                            _ptr(workspace), ws_bytes, _stream(stream)), "flux_rs_reduce_slice_ready")
 
 
 def flux_ag_gemm(p, A_chunks, A_agg, B, Cout, signals, arrival_order, workspace, compute_stream, copy_stream):

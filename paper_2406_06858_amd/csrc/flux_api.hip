@@ -166,6 +166,90 @@ __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
   }
 }
 
+struct ReadyReduceArgs {
+  const void* staged[FLUX_MAX_RANKS];   // [S,N] partials for this slice, one per producer, in rank order
+  void* out;                            // [S,N]
+  uint32_t* tile_ready;                 // [tiles_m * tiles_n] of the whole [M,N] grid
+  uint32_t* status;                     // status block (code, detail)
+  unsigned long long timeout_ticks;
+  int32_t S, N, R, partial_f32, out_f32;
+  int32_t bm, bn, tiles_n;              // the producers' tile shape
+  int32_t row0;                         // first global row of the slice
+  int32_t mt_lo, n_mt;                  // m-tiles that overlap the slice
+  int32_t producers;                    // counter value that means "every producer has written the tile"
+};
+
+// Consumer side of the tile-ready handshake (Sec. 4.2, "Reduce", second form: a reducer on the
+// destination that takes tiles as they come up).  A few persistent workgroups walk over the tiles
+// that overlap this rank's slice; for each, one lane polls the tile's counter (bounded), then the
+// workgroup sums the producers' staged rows of that tile in rank order, fp32, and writes the slice.
+// Staged data is read at device scope (past this die's L2): the producers wrote it through.
+__global__ void __launch_bounds__(256) rs_ready_reduce_kernel(const ReadyReduceArgs a) {
+  __shared__ int verdict;
+  const int n_tiles = a.n_mt * a.tiles_n;
+  const int elem = a.partial_f32 ? 4 : 2;
+  constexpr int SC1 = 16;                                     // cache-policy bit: device scope
+  for (int t = (int)blockIdx.x; t < n_tiles; t += (int)gridDim.x) {
+    const int mt = a.mt_lo + t / a.tiles_n, nt = t % a.tiles_n;
+    if (threadIdx.x == 0) {
+      const uint32_t* c = a.tile_ready + (size_t)mt * a.tiles_n + nt;
+      const unsigned long long t0 = wall_clock64();
+      int ok = 1;
+      while (__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < (uint32_t)a.producers) {
+        if (wall_clock64() - t0 > a.timeout_ticks) {
+          if (atomicCAS(a.status, 0u, (uint32_t)FLUX_ERR_TIMEOUT) == 0u) a.status[1] = (uint32_t)(mt * a.tiles_n + nt);
+          ok = 0;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(32);
+      }
+      verdict = ok;
+    }
+    __syncthreads();
+    const int ok = verdict;
+    __syncthreads();                    // everyone has read it before thread 0 writes the next one
+    if (!ok) continue;                  // the tile stays unwritten; the status block says which
+    // rows of the tile that belong to this slice, as local rows
+    const int g0 = mt * a.bm > a.row0 ? mt * a.bm : a.row0;
+    const int g1 = (mt + 1) * a.bm < a.row0 + a.S ? (mt + 1) * a.bm : a.row0 + a.S;
+    const int c0 = nt * a.bn, c1 = c0 + a.bn < a.N ? c0 + a.bn : a.N;
+    const int vec_per_row = (c1 - c0) / 8;
+    const int nvec = (g1 - g0) * vec_per_row;
+    // the staged matrices through buffer resources based at the first row of the tile within the
+    // slice (uniform; a lane's offset from there stays below 256 rows * N * 4 bytes < 2^31)
+    const size_t tile_base = (size_t)(g0 - a.row0) * a.N;
+    for (int v = (int)threadIdx.x; v < nvec; v += (int)blockDim.x) {
+      const int tr = v / vec_per_row, col = c0 + (v % vec_per_row) * 8;
+      const size_t o = tile_base + (size_t)tr * a.N + col;
+      const int voff = (int)(((uint32_t)tr * (uint32_t)a.N + (uint32_t)col) * (uint32_t)elem);
+      float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < a.R; ++j) {
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<unsigned char*>(static_cast<const unsigned char*>(a.staged[j])) + tile_base * elem, 0, 0x7fffffff, 0x00027000);
+        if (a.partial_f32) {
+          const u32x4 u = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, 0, SC1), w = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16, 0, SC1);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { x[e] += __uint_as_float(u[e]); x[4 + e] += __uint_as_float(w[e]); }
+        } else {
+          const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, 0, SC1);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { x[2 * e] += bf16_lo(w[e]); x[2 * e + 1] += bf16_hi(w[e]); }
+        }
+      }
+      if (a.out_f32) {
+        float* q = static_cast<float*>(a.out) + o;
+        st_stream16(q, make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])));
+        st_stream16(q + 4, make_uint4(__float_as_uint(x[4]), __float_as_uint(x[5]), __float_as_uint(x[6]), __float_as_uint(x[7])));
+      } else {
+        uint4 w;
+        w.x = pack_bf16x2(x[0], x[1]); w.y = pack_bf16x2(x[2], x[3]);
+        w.z = pack_bf16x2(x[4], x[5]); w.w = pack_bf16x2(x[6], x[7]);
+        st_stream16(static_cast<__bf16*>(a.out) + o, w);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // planning
 // ------------------------------------------------------------------------------------------
@@ -588,7 +672,7 @@ static int get_chunk_events(hipEvent_t** events) {
 
 
 int gemm_rs_planned(const flux_problem_t* p, const Plan& pl, const void* A, const void* B, const void* const* peer_partials,
-                    void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream);
+                    void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream, uint32_t* tile_ready = nullptr);
 
 }  // namespace flux
 
@@ -779,7 +863,7 @@ int flux_gemm_rs_static(const flux_problem_t* p, const void* A, const void* B, c
 namespace flux {
 
 int gemm_rs_planned(const flux_problem_t* p, const Plan& pl, const void* A, const void* B, const void* const* peer_partials,
-                    void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream) {
+                    void* const* out_slices, void* workspace, size_t workspace_bytes, void* stream, uint32_t* tile_ready) {
   int st;
   const bool atomic = p->flags & FLUX_FLAG_RS_ATOMIC;
   if (atomic && ((p->flags & FLUX_FLAG_RS_WRITE_ONLY) || p->out_dtype != FLUX_F32)) return FLUX_ERR_UNSUPPORTED;
@@ -798,6 +882,7 @@ int gemm_rs_planned(const flux_problem_t* p, const Plan& pl, const void* A, cons
   GemmArgs a;
   fill_common(&a, p, pl, pl.split_k > 1 ? workspace : nullptr);
   a.trace = trace;
+  a.tile_ready = tile_ready;
   a.A = static_cast<const __bf16*>(A);
   a.B = static_cast<const __bf16*>(B);
   // the kernel wants the R-1 peers packed, ascending rank
@@ -813,6 +898,58 @@ int gemm_rs_planned(const flux_problem_t* p, const Plan& pl, const void* A, cons
 }  // namespace flux
 
 extern "C" {
+
+int32_t flux_rs_ready_count(const flux_problem_t* p) {
+  Plan pl;
+  if (make_plan(FLUX_OP_RS, p, &pl) != FLUX_OK) return 0;
+  return pl.tiles_m * pl.tiles_n;
+}
+
+int flux_gemm_rs_notify(const flux_problem_t* p, const void* A, const void* B, void* const* out_slices,
+                        uint32_t* tile_ready, void* workspace, size_t workspace_bytes, void* stream) {
+  if (p == nullptr || tile_ready == nullptr) return FLUX_ERR_INVALID_ARG;
+  if (p->flags & FLUX_FLAG_RS_ATOMIC) return FLUX_ERR_UNSUPPORTED;
+  flux_problem_t q = *p;
+  q.flags |= FLUX_FLAG_RS_WRITE_ONLY;
+  Plan pl;
+  int st = make_plan(FLUX_OP_RS, &q, &pl);
+  if (st != FLUX_OK) return st;
+  return gemm_rs_planned(&q, pl, A, B, nullptr, out_slices, workspace, workspace_bytes, stream, tile_ready);
+}
+
+int flux_rs_reduce_slice_ready(const flux_problem_t* p, const void* const* staged, void* out, uint32_t* tile_ready,
+                               int32_t producers, void* workspace, size_t workspace_bytes, void* stream) {
+  Plan pl;
+  int st = make_plan(FLUX_OP_RS, p, &pl);
+  if (st != FLUX_OK) return st;
+  if (!staged || !out || !tile_ready || !aligned16(out) || producers < 1) return FLUX_ERR_INVALID_ARG;
+  if (workspace == nullptr || workspace_bytes < WS_HEADER_BYTES || !aligned16(workspace)) return FLUX_ERR_WORKSPACE;
+  ReadyReduceArgs r;
+  std::memset(&r, 0, sizeof(r));
+  for (int j = 0; j < p->R; ++j) {
+    if (!staged[j] || !aligned16(staged[j])) return FLUX_ERR_INVALID_ARG;
+    r.staged[j] = staged[j];
+  }
+  const int S = p->M / p->R;
+  r.out = out;
+  r.tile_ready = tile_ready;
+  r.status = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + WS_STATUS_OFF);
+  r.timeout_ticks = p->spin_timeout_ticks ? p->spin_timeout_ticks : DEFAULT_TIMEOUT_TICKS;
+  r.S = S; r.N = p->N; r.R = p->R;
+  r.partial_f32 = p->partial_dtype == FLUX_F32;
+  r.out_f32 = p->out_dtype == FLUX_F32;
+  r.bm = pl.bm; r.bn = pl.bn; r.tiles_n = pl.tiles_n;
+  r.row0 = p->rank * S;
+  r.mt_lo = r.row0 / pl.bm;
+  r.n_mt = (r.row0 + S - 1) / pl.bm - r.mt_lo + 1;
+  r.producers = producers;
+  // A small persistent grid: its workgroups wait on compute units that the producers' GEMM
+  // workgroups (which take a whole unit each) then cannot use.
+  const int grid = std::max(1, std::min(r.n_mt * pl.tiles_n, 32));
+  hipLaunchKernelGGL(rs_ready_reduce_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream), r);
+  FLUX_HIP(hipGetLastError());
+  return FLUX_OK;
+}
 
 int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_agg, const void* B, void* C,
                  uint32_t* signals, const int32_t* arrival_order, void* workspace, size_t workspace_bytes,

@@ -128,6 +128,7 @@ struct GemmArgs {
   uint32_t* sk_counters;          // [tiles]
   int32_t partial_f32, out_f32;
   flux_trace_record_t* trace;     // tile trace, one record per workgroup; null: none
+  uint32_t* tile_ready;           // reduce-scatter, Write branch: per output tile, producers that have written it; null: not kept
   // ---- arrays ----
   void* outs[FLUX_MAX_RANKS];
   const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
@@ -227,6 +228,18 @@ __device__ __forceinline__ uint4 ld_stream16(const void* p) {
 __device__ __forceinline__ void st_stream16(void* p, const uint4& v) {
   const u32x4 d = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(d, static_cast<u32x4*>(p));
+}
+
+// 16-byte store at device scope: written through this die's L2, so that a reader on another
+// accelerator die needs no write-back of the whole L2 to see it.
+__device__ __forceinline__ void store_through(uint4* p, const u32x4& d) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
+}
+// Output vectors: streamed, or written through when a consumer may read the tile as soon as its ready
+// counter moves (`through`, uniform).
+__device__ __forceinline__ void st_out16(void* p, const uint4& v, bool through) {
+  if (through) store_through(static_cast<uint4*>(p), u32x4{v.x, v.y, v.z, v.w});
+  else st_stream16(p, v);
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -349,6 +362,7 @@ template <int EPI>
 __device__ __forceinline__ void store_row8(const GemmArgs& a, void* const* lds_outs, int gm, int gn, const float (&v)[8]) {
   void* base;
   size_t o;
+  const bool through = EPI == EPI_RS && a.tile_ready != nullptr;
   if (EPI == EPI_RS) {
     const int r = gm / a.S;
     base = lds_outs[r];
@@ -359,13 +373,13 @@ __device__ __forceinline__ void store_row8(const GemmArgs& a, void* const* lds_o
   }
   if (a.out_f32) {
     float* q = static_cast<float*>(base) + o;
-    st_stream16(q, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
-    st_stream16(q + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
+    st_out16(q, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])), through);
+    st_out16(q + 4, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])), through);
   } else {
     uint4 w;
     w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
     w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
-    st_stream16(static_cast<__bf16*>(base) + o, w);
+    st_out16(static_cast<__bf16*>(base) + o, w, through);
   }
 }
 
@@ -476,12 +490,6 @@ __device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds
 // only wait may take pieces nobody has claimed yet.  Either way the piece is claimed first (a
 // compare-and-swap of the call's id into the piece's claim word), moved, and counted in; whoever
 // counts in last sets the tile's signal (SetSignal of Alg. 3).
-
-// 16-byte store at device scope: written through this die's L2, so that a reader on another
-// accelerator die needs no write-back of the whole L2 to see it.
-__device__ __forceinline__ void store_through(uint4* p, const u32x4& d) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(d) : "memory");
-}
 
 __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
                                            int piece, int pieces, int tid) {
@@ -940,6 +948,15 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
   } else {
     if (a.partial_f32) epilogue_all<C, EPI, EDGE, true, 1, NP_ALL>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
     else epilogue_all<C, EPI, EDGE, false, 1, NP_ALL>(a, lds_outs, ep, acc, m0, n0, lane, wm, wn);
+  }
+  if (EPI == EPI_RS && a.tile_ready != nullptr) {
+    // Producer side of the tile-ready handshake (Sec. 4.2, "Reduce", second form): the tile was written
+    // through to memory; once every wave's stores are acknowledged, count this producer in.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (tid == 0)
+      __hip_atomic_fetch_add(a.tile_ready + (size_t)(m0 / C::BM) * a.tm.tiles_n + n0 / C::BN, 1u, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_SYSTEM);
   }
   trace_stamp(a, TRACE_END);
 }
