@@ -58,6 +58,12 @@ def main() -> int:
     import numpy as np
     import torch
 
+    t_begin = time.perf_counter()
+
+    def say(msg):
+        """Progress on stderr (the JSON line is the only thing on stdout)."""
+        print(f"[bench {time.perf_counter() - t_begin:6.1f}s] {msg}", file=sys.stderr, flush=True)
+
     from paper_2406_06858_amd import binding as fb
     from paper_2406_06858_amd import inputs as fi
 
@@ -275,6 +281,7 @@ def main() -> int:
         return 0
 
     # ---- the timed workload: QKV projection (AG-GEMM) + attention output projection (GEMM-RS) ----
+    say("generating the inputs of c4_ag and c4_rs")
     ag = AG(W["c4_ag"], rank=2, flags=args.ag_flags)
     rs = RS(W["c4_rs"], rank=2)
     flops_step = ag.w.flops + rs.w.flops
@@ -300,6 +307,7 @@ def main() -> int:
             fb.flux_profile_next_gemm(prof[2], prof[3])
         rs.fused()
 
+    say("clock ramp, warm-up and timed steps")
     # clock ramp: the engine clock takes about a second of sustained load to leave its idle
     # state and settle at the power-limited level; the W warm-up steps come after that
     t_ramp = time.perf_counter()
@@ -330,6 +338,7 @@ def main() -> int:
         print(f"bench.py: AllGather-GEMM reported status {status}", file=sys.stderr)
         return 1
 
+    say(f"timed region done: {ms_per_step:.4f} ms per step; spot check against the oracle")
     # spot check against the oracle on a few rows (outside the timed region)
     from oracle import flux_oracle as fo
     rows = [0, 1023, 1024, 4095, 8191]
@@ -379,8 +388,11 @@ def main() -> int:
 
     extra = {}
     if not args.no_extra:
+        say("extra: c4_ag")
         extra["c4_ag"] = overlap_block(ag)
+        say("extra: c4_rs")
         extra["c4_rs"] = overlap_block(rs)
+        say("extra: vendor library GEMM on the same operands")
         # Context, not a target and not part of the path: the vendor library's plain GEMM (hipBLASLt
         # behind torch.matmul) on the same operands, and on zeros.  With normally distributed operands
         # the chip runs into its power limit and every GEMM, this one included, slows down by a
@@ -406,6 +418,7 @@ def main() -> int:
         del ag, rs
         torch.cuda.empty_cache()
         for name in ("c2_ag", "c3_rs", "c5_ag_m64", "c5_rs_m64", "c5_ag_m8", "c5_rs_m8", "c5_ag_m256", "c5_rs_m256"):
+            say(f"extra: {name}")
             op = AG(W[name], 2) if W[name].op == "ag" else RS(W[name], 2)
             if name.startswith("c5"):
                 op.rotate_weights(9)        # 9 x 58.7 MB = 528 MB, twice the Infinity Cache
@@ -416,6 +429,7 @@ def main() -> int:
         tuned = {}
         for name in ("c4_ag", "c4_rs", "op_ag_m2048", "op_rs_m2048", "c5_ag_m64"):
             w = W[name]
+            say(f"extra: tuner on {name}")
             if w.op == "ag":
                 op = AG(w, 2)
                 op.signals = torch.zeros(fb.flux_autotune_signal_count(op.p), dtype=torch.int32, device=dev)
@@ -436,6 +450,7 @@ def main() -> int:
         sweep = {}
         for name in ("op_ag_m8", "op_rs_m8", "op_ag_m64", "op_rs_m64",
                      "op_ag_m512", "op_rs_m512", "op_ag_m2048", "op_rs_m2048", "op_ag_m8192", "op_rs_m8192"):
+            say(f"extra: op-level sweep {name}")
             op = AG(W[name], 2) if W[name].op == "ag" else RS(W[name], 2)
             if W[name].M <= 64:
                 op.rotate_weights(3)        # 3 x 151 MB: a decode step never finds its weights in the Infinity Cache
@@ -449,8 +464,9 @@ def main() -> int:
         link = {}
         for name, variants in (("c4_ag", ((1, 0), (2, 0), (4, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE))), ("c2_ag", ((1, 0), (2, 0)))):
             for ctpc, flags in variants:
-                op = AG(W[name], 2, link_gbps=1071, copy_workgroups=64, comm_tiles_per_chunk=ctpc, flags=flags)
+                op = AG(W[name], 2, link_gbps=1071, comm_tiles_per_chunk=ctpc, flags=flags)
                 key = f"{name}_ctpc{ctpc}" + ("_noswizzle" if flags else "")
+                say(f"extra: link-paced {key}")
                 link[key] = overlap_block(op)
                 del op
                 torch.cuda.empty_cache()
@@ -459,6 +475,7 @@ def main() -> int:
         # signal on the copy stream, the GEMM grid only waits (no workgroup moves data)
         mc = {}
         for name in ("c2_ag", "c4_ag"):
+            say(f"extra: memcpy driver {name}")
             op = AG(W[name], 2, flags=fb.FLUX_FLAG_COPY_MEMCPY)
             mc[name] = {"ms_fused": round(time_calls(op.fused, 20, 5), 4)}
             del op
@@ -466,6 +483,7 @@ def main() -> int:
         extra["copy_memcpy_driver"] = mc
     cpu_baseline = None
     if not args.no_cpu_baseline:
+        say("cpu baseline: the oracle on whole steps of the same workload")
         # the oracle as it stands, on the host cores: full AllGather-GEMM of the timed shape
         try:
             from threadpoolctl import threadpool_info
@@ -505,6 +523,7 @@ def main() -> int:
         "cpu_baseline": cpu_baseline,
         "extra": extra,
     }
+    say("done")
     print(json.dumps(out))
     return 0
 

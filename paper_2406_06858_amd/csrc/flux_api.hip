@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
         __syncthreads();
         if (!take) continue;
       }
-      copy_piece(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x);
+      copy_piece<32>(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x);
       ++moved;
     }
     if (moved == 0) continue;
@@ -446,7 +446,15 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     // Driver: one piece of every communication tile per workgroup.  A small driver: it keeps the
     // later chunks coming in the background while waiting GEMM workgroups pull what they need now;
     // a large one would sit on compute units the GEMM wants.
-    int wgs = p->copy_workgroups > 0 ? p->copy_workgroups : 32;
+    // ... and one that stands for a link needs no more workgroups than move data at the link's rate
+    // (about 40 GB/s each): every one of them holds a compute unit for the whole transfer.
+    // A driver that stands for a link gets as many workgroups as move data at the link's rate and no
+    // more, since each keeps GEMM workgroups off a compute unit for as long as the transfer lasts.  A
+    // unit copies about 20 GB/s beside a running GEMM, with four waves or with sixteen (a driver of 12
+    // workgroups of 1024 threads moved 170 GB/s, one of 28 of 256 threads 870 GB/s), so a 1 TB/s link
+    // costs some fifty units: that is the price of standing in for a link with compute units.
+    int wgs = p->copy_workgroups > 0 ? p->copy_workgroups
+                                     : (p->link_gbps > 0 ? std::max(4, std::min(64, (p->link_gbps + 19) / 20)) : 32);
     wgs = std::min(wgs, MAX_COPY_PIECES);
     const unsigned long long tile_vec = (unsigned long long)(p->M / p->R) * p->K / 8 / pl->ctpc;
     wgs = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(wgs, (tile_vec + 255) / 256));
@@ -617,6 +625,9 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
   c.tiles_per_chunk = fused ? pl.ctpc : 1;
   c.chunk_vec = chunk_vec;
   c.tile_vec = chunk_vec / c.tiles_per_chunk;
+  // bytes / (GB/s) = ns; 10 ns per tick.  The baseline's copy is paced like the fused call's driver:
+  // an emulated link delivers no faster when nothing overlaps with it.
+  c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
   int wgs;
   if (fused) {
     unsigned char* w = static_cast<unsigned char*>(ws);
@@ -625,8 +636,6 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
     c.claims = reinterpret_cast<uint32_t*>(w + WS_HEADER_BYTES);
     c.call_id = call_id;
     c.started = reinterpret_cast<uint32_t*>(w + WS_STARTED_OFF);
-    // bytes / (GB/s) = ns; 10 ns per tick
-    c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
     wgs = pl.copy_wgs;
     c.pieces = pl.copy_pieces;
   } else {
@@ -1005,6 +1014,12 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
       for (int i = 0; i < p->R - 1; ++i) a.copy_order4 |= (unsigned long long)order[i] << (4 * i);
     }
   }
+  if ((p->flags & FLUX_FLAG_COPY_MEMCPY) && p->R > 1) {
+    // the grid moves nothing unless the library copies are starved of compute units: then, after
+    // 100 us without a signal, a workgroup fetches its own rows
+    for (int r = 0; r < p->R; ++r) a.outs[r] = const_cast<void*>(A_chunks[r]);   // chunk sources by rank
+    a.self_serve_ticks = 10000u;
+  }
   build_tile_map(FLUX_OP_AG, p, pl, order, &a.tm);
 
   const bool driver_form = !(pl.copy_self || p->R == 1);
@@ -1054,6 +1069,14 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   // were already put back by the last workgroup past its wait)
   FLUX_HIP(hipEventRecord(ev_join, xs));
   FLUX_HIP(hipStreamWaitEvent(cs, ev_join, 0));
+  if (p->flags & FLUX_FLAG_COPY_MEMCPY) {
+    // a copy that the grid overtook (its workgroups fetched their rows themselves) writes its signal
+    // after the grid's own reset: put the array back once more behind the join (Sec. 4.3: the
+    // reset after the GEMM, with a stream and an event)
+    hipLaunchKernelGGL(preset_kernel, dim3((a.n_signals + 255) / 256), dim3(256), 0, cs, signals, a.n_signals,
+                       a.sig_local_lo, a.sig_local_hi, (uint32_t*)nullptr, 0);
+    FLUX_HIP(hipGetLastError());
+  }
   return FLUX_OK;
 }
 

@@ -111,6 +111,9 @@ struct GemmArgs {
   int32_t copy_owner_wgs;
   int32_t copy_eager;        // waiting workgroups take pieces even while the whole driver is running
   int32_t acquire_l2;        // the gathered rows may share cache lines across communication tiles: full acquire after the wait
+  // The driver is a copy engine or library copy that takes no pieces (copy_pieces = 0): a workgroup
+  // that has waited this long (100 MHz ticks; 0: never) fetches the rows of its own tile itself.
+  uint32_t self_serve_ticks;
   // ---- the transfer ----
   uint32_t* copy_claims;     // [n_signals][copy_pieces], a piece is taken when it holds copy_call_id
   uint32_t* copy_counters;   // [n_signals] pieces finished
@@ -491,11 +494,12 @@ __device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds
 // compare-and-swap of the call's id into the piece's claim word), moved, and counted in; whoever
 // counts in last sets the tile's signal (SetSignal of Alg. 3).
 
+// DEPTH vectors per thread in flight (16 inside the GEMM kernels, whose registers are taken; the
+// copy kernel, whose workgroups each hold a compute unit, takes 32); the last batch is predicated,
+// not walked one vector (one memory round trip) at a time.
+template <int DEPTH = 16>
 __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
                                            int piece, int pieces, int tid) {
-  // 16 vectors per thread in flight; the last batch is predicated, not walked one vector (one
-  // memory round trip) at a time
-  constexpr int DEPTH = 16;
   const unsigned long long stride = (unsigned long long)pieces * 256;
   for (unsigned long long i = (unsigned long long)piece * 256 + tid; i < tile_vec; i += DEPTH * stride) {
     u32x4 v[DEPTH];
@@ -673,7 +677,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   const int tid = threadIdx.x;
   const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
   const unsigned long long t0 = wall_clock64();
-  enum : int { ARRIVED = 1, GIVE_UP = 2, HELP = 3 };
+  enum : int { ARRIVED = 1, GIVE_UP = 2, HELP = 3, SELF_SERVE = 4 };
   const int nf = f1 - f0 + 1;
   // The search for a piece covers a window of at most 4096 pieces (12 index bits in the key below),
   // starting at the first tile whose signal is still missing, so it moves on as tiles complete.
@@ -708,6 +712,10 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
           st = HELP;
           break;
         }
+        if (a.copy_pieces == 0 && a.self_serve_ticks != 0u && wall_clock64() - t0 > (unsigned long long)a.self_serve_ticks) {
+          st = SELF_SERVE;
+          break;
+        }
         __builtin_amdgcn_s_sleep(16);
       }
       if (tid == 0) {
@@ -722,6 +730,38 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
     __syncthreads();                    // everyone has read them before the first wave can write again
     if (st == ARRIVED) break;
     if (st == GIVE_UP) { ok = false; break; }
+    if (st == SELF_SERVE) {
+      // The transfers of a driver that takes no pieces (a library copy per tile with a stream write
+      // of its signal) run as kernels of their own on this chip: when the grid's waiting workgroups
+      // hold every compute unit, those kernels cannot start and the signals never come.  A workgroup
+      // that has waited long enough therefore fetches the rows of its own tile from the chunk
+      // sources itself and goes on without its signals.  The driver may write the same bytes to the
+      // same places at the same time: harmless.  (The host puts the signals back after the join in
+      // this form, since a driver that was overtaken sets some of them after the grid is done.)
+      const unsigned long long vec_per_row = (unsigned long long)a.K / 8;
+      const unsigned long long nvec = (unsigned long long)(m1 - m0) * vec_per_row;
+      for (unsigned long long v = tid; v < nvec; v += 4 * blockDim.x) {
+        u32x4 x[4];
+        const uint4* src[4];
+        uint4* dst[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const unsigned long long vv = v + (unsigned long long)u * blockDim.x;
+          const int row = m0 + (int)((vv < nvec ? vv : 0) / vec_per_row);
+          const unsigned long long col = (vv < nvec ? vv : 0) % vec_per_row;
+          const int chunk = row / a.S;
+          src[u] = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)(row - chunk * a.S) * vec_per_row + col;
+          dst[u] = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)row * vec_per_row + col;
+          if (vv < nvec) x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src[u]));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (v + (unsigned long long)u * blockDim.x < nvec && src[u] != dst[u]) store_through(dst[u], x[u]);
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): the stores are acknowledged
+      __syncthreads();
+      break;
+    }
     // One of the unclaimed pieces among the tiles of the window, picked by a hash that differs per
     // workgroup and attempt: workgroups that wait for the same tiles then rarely go for the same
     // piece (taking "the first free one" would make them queue up behind each other).  The local

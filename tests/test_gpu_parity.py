@@ -319,6 +319,25 @@ def test_ag_arrival_orders_and_copy_engines(order, flags):
         assert signals.cpu().tolist() == [1 if i // n == rank else 0 for i in range(w.R * n)]
 
 
+@pytest.mark.parametrize("ctpc", [1, 2])
+def test_ag_library_copies_starved_of_compute_units(ctpc):
+    """FLUX_FLAG_COPY_MEMCPY on a grid that fills the chip: the first 256 workgroups take every compute
+    unit and most of them wait for signals, so the library copies (kernels of their own on this chip)
+    cannot start.  A workgroup that has waited 100 us fetches its own rows; the call completes without
+    a timeout, with the right result, the gathered matrix complete and the signals preset again."""
+    w = fi.Workload("ag_starved", "ag", 4096, 4608, 512, 8, seed=89, a_dist=("int", 2), b_dist=("int", 2))
+    rank = 6
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    _say("ag memcpy driver, 288 tiles on 256 compute units, ctpc", ctpc)
+    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, flags=fb.FLUX_FLAG_COPY_MEMCPY, tile_config=1,
+                                           comm_tiles_per_chunk=ctpc, repeat=3)
+    assert status == (fb.FLUX_OK, 0)
+    C64, Cbits = gh.oracle_ag(w, chunks, B)
+    gh.assert_bits_equal(Cg, Cbits, "C")
+    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+    assert signals.cpu().tolist() == [1 if i // ctpc == rank else 0 for i in range(w.R * ctpc)]
+
+
 def test_ag_delayed_copy_stream_still_correct():
     """The copy driver starts ~10 ms late (host-forced); every remote tile has to spin."""
     w = AG_SMALL
