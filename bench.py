@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # bytes per launch behind the L2 of the two kernels of the timed step (rocprofv3 FETCH_SIZE + WRITE_SIZE)
-TRAFFIC_BYTES = {"rs": None, "ag": None}
+TRAFFIC_BYTES = {"rs": 1950.0e6 + 201.3e6, "ag": 2637.8e6 + 319.0e6}     # profiles/bench_c4_pmc_traffic.txt
 HBM_PEAK_GBS = 8000.0
 TIMEOUT_TICKS = 500_000_000        # 5 s: a lost signal ends the run with an error, not a hang
 
@@ -43,8 +43,9 @@ def main() -> int:
                          "matrix, fused GEMM-ReduceScatter, fused AllGather-GEMM call] and exit (rocprofv3 --pmc runs "
                          "kernels one at a time)")
     ap.add_argument("--serial-decode", type=int, default=0, metavar="N",
-                    help="counter-collection mode for the few-row shapes: N plain GEMMs (no communication) of each of "
-                         "c5_ag_m8 / _m64 / _m256 over rotating copies of the weight matrix, then exit")
+                    help="counter-collection mode for the few-row shapes (M = 8, 64, 256): N plain GEMMs, N fused "
+                         "AllGather-GEMM calls and N fused GEMM-ReduceScatter calls each, over rotating copies of the "
+                         "weight matrix, then exit")
     ap.add_argument("--event-every", type=int, default=8, metavar="E",
                     help="record the per-kernel HIP events on every E-th timed step (1 = every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -270,14 +271,27 @@ def main() -> int:
                 "fused_frac_hbm_peak": round(op.alg_bytes() / t_fus / 1e6 / HBM_PEAK_GBS, 4)}
 
     if args.serial_decode > 0:
-        for name in ("c5_ag_m8", "c5_ag_m64", "c5_ag_m256"):
-            op = AG(W[name], 2)
-            op.rotate_weights(9)
+        # per few-row shape: N plain GEMMs (no communication), then N fused AllGather-GEMM calls, then N
+        # fused GEMM-ReduceScatter calls, each over rotating copies of the weight matrix; synchronised
+        # between the groups so that a trace shows them apart
+        for m in (8, 64, 256):
+            ag_op = AG(W[f"c5_ag_m{m}"], 2)
+            ag_op.rotate_weights(9)
             for _ in range(args.serial_decode):
-                op.unfused(fb.FLUX_PHASE_GEMM)
+                ag_op.unfused(fb.FLUX_PHASE_GEMM)
             torch.cuda.synchronize()
-            del op
-        print(json.dumps({"mode": "serial-decode", "launches_per_shape": args.serial_decode}))
+            for _ in range(args.serial_decode):
+                ag_op.fused()
+            torch.cuda.synchronize()
+            del ag_op
+            rs_op = RS(W[f"c5_rs_m{m}"], 2)
+            rs_op.rotate_weights(9)
+            for _ in range(args.serial_decode):
+                rs_op.fused()
+            torch.cuda.synchronize()
+            del rs_op
+        print(json.dumps({"mode": "serial-decode", "launches_per_shape_and_kind": args.serial_decode,
+                          "order": "per M in (8, 64, 256): plain GEMM (AllGather shape), fused AllGather-GEMM, fused GEMM-ReduceScatter"}))
         return 0
 
     # ---- the timed workload: QKV projection (AG-GEMM) + attention output projection (GEMM-RS) ----
@@ -356,7 +370,7 @@ def main() -> int:
 
     # Traffic behind the L2 per launch, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
     # `bench.py --serial-kernels 5`, each scaled by what the same counter reads for the 176.2 MB chunk
-    # copy of the same run; profiles/bench_c4_pmc_traffic.txt.  None: not measured for this build.
+    # copy of the same run (1.9977 and 1.0000 KiB per count); profiles/bench_c4_pmc_traffic.txt.
     traffic = TRAFFIC_BYTES
     alg = {"rs": rs.alg_bytes(), "ag": ag.alg_bytes()}
 
@@ -427,7 +441,7 @@ def main() -> int:
             torch.cuda.empty_cache()
         # The tuner (Sec. 4.4) on three shapes: what it picks and what that gains over the library's own choice
         tuned = {}
-        for name in ("c4_ag", "c4_rs", "op_ag_m2048", "op_rs_m2048", "c5_ag_m64"):
+        for name in ("c4_ag", "c4_rs", "op_ag_m2048", "op_rs_m2048", "c5_ag_m64", "c5_rs_m64", "c5_ag_m256"):
             w = W[name]
             say(f"extra: tuner on {name}")
             if w.op == "ag":
@@ -441,7 +455,7 @@ def main() -> int:
                 n = fb.flux_autotune_workspace_bytes(fb.FLUX_OP_RS, op.p)
                 op.ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev) if n else None
                 t, ms_best, ms_def = fb.flux_autotune_rs(op.p, op.A, op.B, op.peers, op.outs, op.ws, compute, reps=5)
-            tuned[name] = {"tile_config": t.tile_config, "comm_tiles_per_chunk": t.comm_tiles_per_chunk,
+            tuned[name] = {"tile_config": t.tile_config, "split_k": t.split_k, "comm_tiles_per_chunk": t.comm_tiles_per_chunk,
                            "ms_tuned": round(ms_best, 4), "ms_library_pick": round(ms_def, 4)}
             del op
             torch.cuda.empty_cache()

@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
         __syncthreads();
         if (!take) continue;
       }
-      copy_piece<32>(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x);
+      copy_piece(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x);
       ++moved;
     }
     if (moved == 0) continue;
@@ -1319,7 +1319,7 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
 // ------------------------------------------------------------------------------------------
 namespace {
 
-struct Candidate { int32_t tile_config, ctpc; };
+struct Candidate { int32_t tile_config, ctpc, split_k; };
 
 // Every tile configuration that accepts the shape; for AllGather each with the communication tile
 // halved from the chunk down to the GEMM tile height (Sec. 4.3), at most 8 tiles per chunk.
@@ -1333,11 +1333,23 @@ std::vector<Candidate> tune_candidates(int op, const flux_problem_t* p) {
     q.comm_tiles_per_chunk = 0;
     Plan pl;
     if (make_plan(op, &q, &pl) != FLUX_OK) continue;
-    out.push_back({cfg, 1});
+    out.push_back({cfg, 1, 0});
+    // few rows: how K is cut decides how well the grid fills the chip and what the hand-over costs;
+    // half and twice the library's number of parts are candidates too
+    if (p->M <= 256 && pl.full_tiles == 0) {
+      const int kt = (p->K + pl.bk - 1) / pl.bk;
+      for (int sk : {pl.split_k / 2, pl.split_k * 2}) {
+        if (sk < 1 || sk == pl.split_k || sk > 64 || sk > kt / 4) continue;
+        flux_problem_t r = q;
+        r.split_k = sk;
+        Plan plr;
+        if (make_plan(op, &r, &plr) == FLUX_OK && plr.split_k == sk) out.push_back({cfg, 1, sk});
+      }
+    }
     if (op != FLUX_OP_AG) continue;
     for (int t = 2; t <= 8; t *= 2) {
       if (S % t != 0 || S / t < pl.bm || p->R * t > MAX_COMM_TILES) break;
-      out.push_back({cfg, t});
+      out.push_back({cfg, t, 0});
     }
   }
   return out;
@@ -1407,6 +1419,7 @@ int tune(int op, const flux_problem_t* p, const TuneBuffers& b, int reps, flux_p
       flux_problem_t q = base;
       q.tile_config = c.tile_config;
       q.comm_tiles_per_chunk = c.ctpc;
+      q.split_k = c.split_k;
       if (flux_workspace_bytes(op, &q) > b.ws_bytes) continue;     // the caller's workspace does not hold this one
       float t = 0.f;
       const int sc = tune_time(op, &q, b, reps, e0, e1, &t);
@@ -1421,7 +1434,7 @@ int tune(int op, const flux_problem_t* p, const TuneBuffers& b, int reps, flux_p
     st = tune_time(op, &base, b, reps, e0, e1, &t_again);
     if (st == FLUX_OK && t_again < t_default) {
       t_default = t_again;
-      if (best.tile_config == 0 && best.comm_tiles_per_chunk == 0) t_best = t_again;
+      if (best.tile_config == 0 && best.comm_tiles_per_chunk == 0 && best.split_k == 0) t_best = t_again;
       else if (t_best >= t_default * 0.98f) { best = base; t_best = t_default; }
     }
   }
@@ -1451,6 +1464,7 @@ size_t flux_autotune_workspace_bytes(int op, const flux_problem_t* p) {
     flux_problem_t q = base;
     q.tile_config = c.tile_config;
     q.comm_tiles_per_chunk = c.ctpc;
+    q.split_k = c.split_k;
     need = std::max(need, flux_workspace_bytes(op, &q));
   }
   return need;

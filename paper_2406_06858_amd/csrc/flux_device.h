@@ -494,9 +494,8 @@ __device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds
 // compare-and-swap of the call's id into the piece's claim word), moved, and counted in; whoever
 // counts in last sets the tile's signal (SetSignal of Alg. 3).
 
-// DEPTH vectors per thread in flight (16 inside the GEMM kernels, whose registers are taken; the
-// copy kernel, whose workgroups each hold a compute unit, takes 32); the last batch is predicated,
-// not walked one vector (one memory round trip) at a time.
+// DEPTH vectors per thread in flight (32 made the plain chunk copy slower: 60 against 24 us for 58.7 MB);
+// the last batch is predicated, not walked one vector (one memory round trip) at a time.
 template <int DEPTH = 16>
 __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
                                            int piece, int pieces, int tid) {
