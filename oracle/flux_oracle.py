@@ -200,15 +200,21 @@ def m_tile_order(op: str, M: int, R: int, rank: int, BM: int, arrival_order=None
     return [t for _, t in keyed]
 
 
-def band_height(M: int, R: int, BM: int) -> int:
-    """Number of consecutive scheduled m-tiles enumerated together with all n-tiles: the
-    m-tiles of one slice/chunk when the slice height is a multiple of BM, else one."""
+def band_height(M: int, R: int, BM: int, comm_tiles_per_chunk: int = 1) -> int:
+    """Number of consecutive scheduled m-tiles enumerated together with all n-tiles: the m-tiles
+    of one communication tile (Sec. 4.3: a chunk, or the given fraction of one; tiles that wait for
+    the same signal are then dispatched together and those of the next communication tile after
+    them) when its height is a multiple of BM; else those of one slice/chunk when that is a
+    multiple of BM; else one."""
     S = slice_rows(M, R)
+    t = max(1, comm_tiles_per_chunk)
+    if S % t == 0 and (S // t) % BM == 0:
+        return S // t // BM
     return S // BM if S % BM == 0 else 1
 
 
 def tile_coord(op: str, block: int, M: int, N: int, R: int, rank: int, BM: int, BN: int,
-               arrival_order=None, n_xcd: int = 1) -> tuple[int, int]:
+               arrival_order=None, n_xcd: int = 1, comm_tiles_per_chunk: int = 1) -> tuple[int, int]:
     """TileCoord of Alg. 1 / Alg. 2: linear workgroup id -> (m_tile, n_tile).
 
     Workgroups are dispatched in id order, so ascending ids must walk the m-tiles in
@@ -223,7 +229,7 @@ def tile_coord(op: str, block: int, M: int, N: int, R: int, rank: int, BM: int, 
     tiles_n = -(-N // BN)
     if not (0 <= block < tiles_m * tiles_n):
         raise ValueError("block out of range")
-    gb = band_height(M, R, BM)
+    gb = band_height(M, R, BM, comm_tiles_per_chunk if op == "ag" else 1)
     band_sz = gb * tiles_n
     band = block // band_sz
     q = block % band_sz

@@ -521,7 +521,10 @@ static void build_tile_map(int op, const flux_problem_t* p, const Plan& pl, cons
     pack_order(tm);
     return;
   }
-  tm->band_h = (S % pl.bm == 0) ? S / pl.bm : 1;
+  // a band = the m-tiles that wait for the same signal (one communication tile, Sec. 4.3), if whole
+  // tiles make up a communication tile; else the m-tiles of one slice / chunk; else one m-tile
+  const int Sc = (op == FLUX_OP_AG && S % pl.ctpc == 0) ? S / pl.ctpc : S;
+  tm->band_h = (Sc % pl.bm == 0) ? Sc / pl.bm : ((S % pl.bm == 0) ? S / pl.bm : 1);
   int pos[FLUX_MAX_RANKS];
   if (op == FLUX_OP_RS) {
     for (int d = 1; d < p->R; ++d) pos[(p->rank + d) % p->R] = d - 1;

@@ -30,7 +30,7 @@ def _records(t: torch.Tensor, grid: int) -> dict:
                 t_end=q[:, 7].astype(np.int64))
 
 
-def _expected_tiles(op, p, w, rank, arrival, n_xcd):
+def _expected_tiles(op, p, w, rank, arrival, n_xcd, ctpc=1):
     """(tile index, K part) of every workgroup from the split plan, and the oracle's coordinates of every tile."""
     opc = fb.FLUX_OP_RS if op == "rs" else fb.FLUX_OP_AG
     full, split_tiles, split_k = fb.flux_split_plan(opc, p)
@@ -39,7 +39,7 @@ def _expected_tiles(op, p, w, rank, arrival, n_xcd):
     blocks = np.arange(grid)
     tile = np.where(blocks < full, blocks, full + (blocks - full) % max(1, split_tiles))
     part = np.where(blocks < full, 0, (blocks - full) // max(1, split_tiles))
-    coords = np.array([fo.tile_coord(op, int(t), w.M, w.N, w.R, rank, sh.tile_m, sh.tile_n, arrival, n_xcd)
+    coords = np.array([fo.tile_coord(op, int(t), w.M, w.N, w.R, rank, sh.tile_m, sh.tile_n, arrival, n_xcd, ctpc)
                        for t in range(full + split_tiles)])
     return grid, tile, part, coords, sh, split_k
 
@@ -113,22 +113,24 @@ def test_rs_trace_matches_oracle_tile_coord(cfg, flags):
     assert (trace == 0).all()
 
 
-@pytest.mark.parametrize("order", ["ring", "random", "no_swizzle"])
+@pytest.mark.parametrize("order", ["ring", "random", "no_swizzle", "random_ctpc2"])
 @pytest.mark.parametrize("cfg", [0, 1])
 def test_ag_trace_matches_oracle_tile_coord(order, cfg):
     w = fi.Workload("ag_trace", "ag", 4096, 5120, 512, 8, seed=92)
     rank = 2
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
     flags = fb.FLUX_FLAG_NO_SWIZZLE if order == "no_swizzle" else 0
+    ctpc = 2 if order == "random_ctpc2" else 1          # two signals per chunk: a band is one communication tile
     if order == "ring":
         arrival = fo.default_order(rank, w.R)
-    p = fb.problem(w.M, w.N, w.K, w.R, rank, tile_config=cfg, flags=flags, spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS)
-    grid, tile, part, coords, sh, split_k = _expected_tiles("ag", p, w, rank, arrival, 1 if flags else 8)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, tile_config=cfg, flags=flags, comm_tiles_per_chunk=ctpc,
+                   spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS)
+    grid, tile, part, coords, sh, split_k = _expected_tiles("ag", p, w, rank, arrival, 1 if flags else 8, ctpc)
     _say("ag trace", order, "cfg", cfg, "tile", sh.tile_m, sh.tile_n, "grid", grid, "split_k", split_k)
     dchunks = [c.to(gh.DEV) for c in chunks]
     A_agg = torch.full((w.M, w.K), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
     Cout = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
-    signals = torch.zeros(w.R, dtype=torch.int32, device=gh.DEV)
+    signals = torch.zeros(w.R * ctpc, dtype=torch.int32, device=gh.DEV)
     ws = gh.workspace_for(fb.FLUX_OP_AG, p)
     fb.flux_init_buffers(fb.FLUX_OP_AG, p, ws, signals)
     trace = torch.zeros((grid, 8), dtype=torch.int64, device=gh.DEV)

@@ -127,6 +127,30 @@ def test_tile_coord_matches_oracle(M, N, R, op):
                     assert got == want, (cfg, rank, flags, b)
 
 
+def test_tile_coord_bands_follow_the_communication_tile():
+    """With several signals per chunk (Sec. 4.3) a band is the set of m-tiles that wait for the same
+    signal: library and oracle agree for every workgroup, and the m-tiles of a band all lie in
+    one communication tile."""
+    M, N, R, rank = 8192, 4608, 8, 2
+    arr = [0, 6, 3, 1, 5, 7, 4]
+    for cfg, ctpc in ((1, 1), (1, 2), (1, 4), (2, 4), (3, 8), (1, 8)):
+        p = fb.problem(M, N, 256, R, rank, tile_config=cfg, comm_tiles_per_chunk=ctpc)
+        sh = fb.flux_tile_shape(fb.FLUX_OP_AG, p)
+        tiles_n = N // sh.tile_n
+        tiles = (M // sh.tile_m) * tiles_n
+        gb = fo.band_height(M, R, sh.tile_m, ctpc)
+        rows_per_signal = M // R // ctpc
+        assert gb == (rows_per_signal // sh.tile_m if rows_per_signal % sh.tile_m == 0 else M // R // sh.tile_m)
+        for b in range(0, tiles, 7):
+            got = fb.flux_tile_coord(fb.FLUX_OP_AG, p, arr, b)
+            assert got == fo.tile_coord("ag", b, M, N, R, rank, sh.tile_m, sh.tile_n, arr, sh.n_xcd, ctpc), (cfg, ctpc, b)
+        if rows_per_signal % sh.tile_m == 0:
+            for band in range(0, tiles // (gb * tiles_n), 3):
+                sig = {fb.flux_tile_coord(fb.FLUX_OP_AG, p, arr, band * gb * tiles_n + q)[0] * sh.tile_m // rows_per_signal
+                       for q in range(gb * tiles_n)}
+                assert len(sig) == 1
+
+
 def test_no_swizzle_flag_gives_natural_order():
     M, N, R, rank = 4096, 3584, 8, 3
     p = fb.problem(M, N, 256, R, rank, tile_config=1, flags=fb.FLUX_FLAG_NO_SWIZZLE)

@@ -160,3 +160,34 @@ def test_protocol_replay_waits_only_when_copy_lags():
     # still correct, because WaitSignal blocks
     with pytest.raises(ValueError):
         fo.visit_order_ag(rank, R, [0, 1])
+
+
+@pytest.mark.parametrize("ctpc", [1, 2, 4, 8])
+@pytest.mark.parametrize("n_xcd", [1, 8])
+def test_ag_bands_follow_the_communication_tile(ctpc, n_xcd):
+    """Sec. 4.3 + 4.1: with several signals per chunk the tiles are still a bijection, ascending
+    workgroup ids never ask for a communication tile that is transferred later than one asked for
+    before, and where whole tiles make up a communication tile a band holds the m-tiles of exactly
+    one of them (they wait for the same signal and are dispatched together)."""
+    M, N, R, rank, BM, BN = 8192, 4608, 8, 2, 256, 256
+    arr = [0, 6, 3, 1, 5, 7, 4]
+    tiles_m, tiles_n = M // BM, N // BN
+    coords = [fo.tile_coord("ag", b, M, N, R, rank, BM, BN, arr, n_xcd, ctpc) for b in range(tiles_m * tiles_n)]
+    assert set(coords) == set(itertools.product(range(tiles_m), range(tiles_n)))
+    S = M // R
+    rows_per_signal = S // ctpc
+    visit = fo.visit_order_ag(rank, R, arr)
+    # transfer position of the communication tile that holds the tile's last row
+    def position(mt):
+        last = (mt + 1) * BM - 1
+        return visit.index(last // S) * ctpc + (last % S) // rows_per_signal
+    pos = [position(mt) for mt, _ in coords]
+    gb = fo.band_height(M, R, BM, ctpc)
+    band_sz = gb * tiles_n
+    per_band = [pos[i:i + band_sz] for i in range(0, len(pos), band_sz)]
+    assert all(max(a) <= min(b) for a, b in zip(per_band, per_band[1:]))
+    if rows_per_signal % BM == 0:
+        assert gb == rows_per_signal // BM
+        assert all(len(set(band)) == 1 for band in per_band)
+    else:
+        assert gb == S // BM           # a tile spans several communication tiles: bands stay per chunk
