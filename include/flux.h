@@ -89,6 +89,13 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
                                         owner that never runs and is taken over by a workgroup that waits for
                                         it.  For tests of that take-over; costs time, never correctness. */
 
+#define FLUX_FLAG_NO_RESIDENT_GRID 0x100u /* flux_gemm_rs: always one workgroup per tile, dispatched by the hardware.
+                                        Without the flag a grid of at least four rounds of 256x256 tiles with
+                                        K <= 3072 runs as one resident workgroup per compute unit that walks
+                                        the same block sequence (Sec. 4.1 order, in time), half of them half
+                                        a tile period late, so that reduce epilogues (Sec. 4.2) and main
+                                        loops of different units overlap.  Same results bit for bit. */
+
 /* flux_gemm_ref_unfused phases */
 #define FLUX_PHASE_GEMM 0x1
 #define FLUX_PHASE_COMM 0x2
@@ -340,6 +347,15 @@ int flux_autotune_signal_count(const flux_problem_t* p);
  */
 int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_t* split_tiles,
                     int32_t* split_k);
+
+/*
+ * Whether flux_gemm_rs would run this problem as a grid of resident workgroups (see
+ * FLUX_FLAG_NO_RESIDENT_GRID): returns the number of resident workgroups (0: one workgroup per block of
+ * flux_split_plan, dispatched by the hardware) and, in *delay_ticks, how late every second group of
+ * eight of them starts (100 MHz ticks).  The blocks and their order (flux_tile_coord, flux_split_plan)
+ * and the tile trace (one record per block) are the same in both forms.  Host function.
+ */
+int32_t flux_rs_resident_grid(const flux_problem_t* p, uint32_t* delay_ticks);
 
 /* Tile configuration a call would use: tile sizes, K split and die count used for the remap. */
 int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* tile_n,

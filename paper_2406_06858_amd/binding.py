@@ -24,6 +24,7 @@ FLUX_FLAG_NO_SWIZZLE, FLUX_FLAG_NO_XCD_REMAP, FLUX_FLAG_COPY_MEMCPY = 0x1, 0x2, 
 FLUX_FLAG_NO_TAIL_SPLIT = 0x10
 FLUX_FLAG_RS_WRITE_ONLY = 0x20
 FLUX_FLAG_AG_ABSENT_OWNERS = 0x40
+FLUX_FLAG_NO_RESIDENT_GRID = 0x100
 FLUX_FLAG_RS_ATOMIC = 0x80
 FLUX_PHASE_GEMM, FLUX_PHASE_COMM = 0x1, 0x2
 FLUX_MAX_RANKS = 16
@@ -36,7 +37,7 @@ EXPORTS = [
     "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
     "flux_autotune_rs", "flux_autotune_ag", "flux_autotune_workspace_bytes", "flux_autotune_signal_count",
     "flux_trace_next_call", "flux_gemm_rs_static",
-    "flux_gemm_rs_notify", "flux_rs_reduce_slice_ready", "flux_rs_ready_count",
+    "flux_gemm_rs_notify", "flux_rs_reduce_slice_ready", "flux_rs_ready_count", "flux_rs_resident_grid",
 ]
 
 
@@ -80,6 +81,8 @@ def lib():
         L.flux_rs_reduce_slice_ready.restype = C.c_int
         L.flux_rs_ready_count.argtypes = [pp]
         L.flux_rs_ready_count.restype = C.c_int32
+        L.flux_rs_resident_grid.argtypes = [pp, C.POINTER(C.c_uint32)]
+        L.flux_rs_resident_grid.restype = C.c_int32
         L.flux_ag_gemm.argtypes = [pp, pvp, vp, vp, vp, vp, pi32, vp, C.c_size_t, vp, vp]
         L.flux_gemm_ref_unfused.argtypes = [C.c_int, C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, vp, C.c_size_t, vp]
         L.flux_gemm_ref_chunked.argtypes = [C.c_int, pp, vp, pvp, vp, vp, pvp, pvp, vp, pi32, vp, C.c_size_t, vp, vp]
@@ -181,6 +184,13 @@ def flux_gemm_rs_static(p, A, B, peer_partials, out_slices, stream=None):
 
 def flux_rs_ready_count(p) -> int:
     return int(lib().flux_rs_ready_count(C.byref(p)))
+
+
+def flux_rs_resident_grid(p) -> tuple[int, int]:
+    """(resident workgroups or 0, start delay of every second group of eight in 100 MHz ticks)."""
+    d = C.c_uint32(0)
+    n = int(lib().flux_rs_resident_grid(C.byref(p), C.byref(d)))
+    return n, int(d.value)
 
 
 def flux_gemm_rs_notify(p, A, B, out_slices, tile_ready, workspace=None, stream=None):

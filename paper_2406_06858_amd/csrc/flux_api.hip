@@ -269,6 +269,8 @@ struct Plan {
   int copy_help;            // waiting GEMM workgroups may take pieces
   int copy_self;            // no copy kernel at all: the GEMM grid moves everything
   int copy_owners;          // ... its first copy_owners workgroups sharing the pieces out by index
+  int resident;             // reduce-scatter: one resident workgroup per compute unit walks the blocks ...
+  uint32_t resident_delay_ticks;   // ... every second group of eight starting this late (100 MHz ticks)
   size_t claim_bytes;       // claim words in the workspace, after the header
 };
 
@@ -440,6 +442,31 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
   else if (p->M % pl->bm != 0) pl->edge = (g_cfgs[cfg].stages > 2 && pl->bm == 32) ? 2 : 1;   // (see below)
   else pl->edge = 0;
   pl->n_xcd = (p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_NO_XCD_REMAP)) ? 1 : N_XCD;
+  // Reduce-scatter grids of many short tiles.  Workgroups that the hardware dispatches one per tile
+  // run in lock step (a freed compute unit gets its next workgroup only when its turn comes in the
+  // dispatch order), so all 256 epilogues pull their peers' tiles at the same time and share what
+  // the memory delivers (44 us per 256x256 tile with 7 peers), and then all main loops run with the
+  // memory idle.  A compute unit alone pulls more than its 1/256 share (32 us per tile).  So: one
+  // resident workgroup per compute unit, walking the block sequence with the grid's stride, and
+  // half of them starting half a period late, which puts one half's epilogues beside the other
+  // half's main loops for the rest of the kernel (8192x12288x1536, 8 ranks: 447 against 500 us).
+  // With a long K the main loops drift apart by themselves within a round or two and nothing is
+  // gained (8192x12288x6144: 1114 us either way), and a grid of fewer than four rounds does not
+  // earn the late start back.
+  pl->resident = 0;
+  pl->resident_delay_ticks = 0;
+  if (op == FLUX_OP_RS && !(p->flags & (FLUX_FLAG_RS_WRITE_ONLY | FLUX_FLAG_RS_ATOMIC | FLUX_FLAG_NO_RESIDENT_GRID)) &&
+      g_cfgs[cfg].stages == 2 && g_cfgs[cfg].occupancy == 1 && pl->edge == 0 &&
+      (long long)pl->full_tiles + (long long)pl->split_tiles * pl->split_k >= 4ll * N_CU && p->K <= 3072) {
+    pl->resident = 1;
+    // half a period: (main loop + epilogue of a tile on a compute unit that shares the memory with
+    // half of the others) / 2; 1.5 us per 64-deep K slab of a 256x256 tile, 33 GB/s per unit
+    const double main_ticks = 150.0 * (double)kt;
+    const double tile_bytes = (double)pl->bm * pl->bn *
+        ((p->R - 1) * (p->partial_dtype == FLUX_F32 ? 4.0 : 2.0) + (p->out_dtype == FLUX_F32 ? 4.0 : 2.0));
+    const double epi_ticks = tile_bytes / 33.0e9 * 1.0e8;
+    pl->resident_delay_ticks = (uint32_t)std::min(20000.0, (main_ticks + epi_ticks) / 2);
+  }
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
   pl->copy_wgs = 0; pl->copy_pieces = 0; pl->copy_help = 0; pl->copy_self = 0; pl->copy_owners = 0; pl->claim_bytes = 0;
   if (op == FLUX_OP_AG) {
@@ -607,7 +634,14 @@ static int launch_gemm(const Plan& pl, int epi, int wait, const GemmArgs& a, hip
   hipEvent_t e0 = g_prof_start, e1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (e0) FLUX_HIP(hipEventRecord(e0, s));
-  FLUX_HIP(g_cfgs[pl.cfg].launch(epi, wait, pl.edge, a, grid, s));
+  if (pl.resident && epi == EPI_RS && !wait && a.write_only == 0) {
+    GemmArgs b = a;
+    b.persist_blocks = grid;
+    b.persist_delay_ticks = pl.resident_delay_ticks;
+    FLUX_HIP(g_cfgs[pl.cfg].launch(epi, wait, pl.edge, b, N_CU, s));
+  } else {
+    FLUX_HIP(g_cfgs[pl.cfg].launch(epi, wait, pl.edge, a, grid, s));
+  }
   if (e1) FLUX_HIP(hipEventRecord(e1, s));
   return FLUX_OK;
 }
@@ -811,6 +845,14 @@ int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_
   if (split_tiles) *split_tiles = pl.split_tiles;
   if (split_k) *split_k = pl.split_k;
   return FLUX_OK;
+}
+
+int32_t flux_rs_resident_grid(const flux_problem_t* p, uint32_t* delay_ticks) {
+  Plan pl;
+  if (delay_ticks) *delay_ticks = 0;
+  if (p == nullptr || make_plan(FLUX_OP_RS, p, &pl) != FLUX_OK || !pl.resident) return 0;
+  if (delay_ticks) *delay_ticks = pl.resident_delay_ticks;
+  return N_CU;
 }
 
 int flux_tile_coord(int op, const flux_problem_t* p, const int32_t* arrival_order, int32_t block,

@@ -132,6 +132,8 @@ struct GemmArgs {
   int32_t partial_f32, out_f32;
   flux_trace_record_t* trace;     // tile trace, one record per workgroup; null: none
   uint32_t* tile_ready;           // reduce-scatter, Write branch: per output tile, producers that have written it; null: not kept
+  int32_t persist_blocks;         // > 0: a grid of resident workgroups, workgroup b takes the blocks b, b + grid, ... below this
+  uint32_t persist_delay_ticks;   // ... and every second group of eight starts this late (100 MHz ticks)
   // ---- arrays ----
   void* outs[FLUX_MAX_RANKS];
   const void* peers[FLUX_MAX_RANKS];   // the R-1 peer partials packed in ascending rank order
@@ -172,10 +174,11 @@ __device__ __forceinline__ void map_block(const GemmArgs& a, int b, int& tile, i
 // is one scalar test per point.
 enum : int { TRACE_START = 0, TRACE_READY = 1, TRACE_MAIN_END = 2, TRACE_END = 3 };
 
-__device__ __forceinline__ void trace_begin(const GemmArgs& a, int tile, int mt, int nt, int split, bool is_split) {
+__device__ __forceinline__ void trace_begin(const GemmArgs& a, int tile, int mt, int nt, int split, bool is_split, int vb = -1) {
   if (a.trace == nullptr || threadIdx.x != 0) return;
-  flux_trace_record_t* r = a.trace + blockIdx.x;
-  r->block = blockIdx.x;
+  const uint32_t b = vb < 0 ? blockIdx.x : (uint32_t)vb;
+  flux_trace_record_t* r = a.trace + b;
+  r->block = b;
   r->m_tile = (uint32_t)mt;
   r->n_tile = (uint32_t)nt;
   r->k_part = (uint32_t)split | (is_split ? 0x10000u : 0u);
@@ -187,11 +190,11 @@ __device__ __forceinline__ void trace_begin(const GemmArgs& a, int tile, int mt,
   r->t_start = t; r->t_ready = t; r->t_main_end = t; r->t_end = t;
 }
 
-__device__ __forceinline__ void trace_stamp(const GemmArgs& a, int point) {
+__device__ __forceinline__ void trace_stamp(const GemmArgs& a, int point, int vb = -1) {
   if (a.trace == nullptr) return;
   if (point == TRACE_END) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's stores are acknowledged
   if (threadIdx.x != 0) return;
-  flux_trace_record_t* r = a.trace + blockIdx.x;
+  flux_trace_record_t* r = a.trace + (vb < 0 ? blockIdx.x : (uint32_t)vb);
   const uint64_t t = wall_clock64();
   if (point == TRACE_READY) r->t_ready = t;
   if (point <= TRACE_MAIN_END) r->t_main_end = t;
@@ -876,8 +879,8 @@ __device__ __forceinline__ void epilogue_all_atomic(const GemmArgs& a, void* con
 template <class C, int EPI, bool EDGE>
 __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem, int* lds_misc, void* const* lds_outs,
                                           f32x16 (&acc)[C::MI][C::NI], int tile, int split, bool is_split,
-                                          int m0, int n0, int tid, int lane, int wave, int wm, int wn) {
-  trace_stamp(a, TRACE_MAIN_END);
+                                          int m0, int n0, int tid, int lane, int wave, int wm, int wn, int vb = -1) {
+  trace_stamp(a, TRACE_MAIN_END, vb);
   // ---- split-K: all but the last-arriving workgroup of a tile park their partial sums ----
   if (is_split) {
     const int st = tile - a.full_tiles;            // index among the split tiles
@@ -916,7 +919,7 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
       *lds_last = last;
     }
     __syncthreads();
-    trace_stamp(a, TRACE_END);        // a workgroup that is not the tile's last ends here
+    trace_stamp(a, TRACE_END, vb);    // a workgroup that is not the tile's last ends here
     if (!*lds_last) return;
     // The sum always runs over the parked partials in split order, whichever workgroup happens
     // to be last, so results do not depend on arrival timing.  (Keeping the own part in registers
@@ -997,7 +1000,7 @@ __device__ __forceinline__ void gemm_tail(const GemmArgs& a, unsigned char* smem
       __hip_atomic_fetch_add(a.tile_ready + (size_t)(m0 / C::BM) * a.tm.tiles_n + n0 / C::BN, 1u, __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_SYSTEM);
   }
-  trace_stamp(a, TRACE_END);
+  trace_stamp(a, TRACE_END, vb);
 }
 
 template <class C, int EPI, bool WAIT, bool EDGE>
@@ -1390,6 +1393,75 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
     wait_vm0_and_barrier();
   }
   gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, is_split, m0, n0, tid, lane, wave, wm, wn);
+}
+
+// The same kernel as a grid of resident workgroups, one per compute unit, each walking the block
+// sequence with the grid's stride (block b, b + grid, ...: the order of Sec. 4.1 is kept, in time
+// instead of in dispatch).
+template <class C, int EPI>
+__global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_resident(const GemmArgs a_) {
+  constexpr int S0_BYTES = C::STAGE_BYTES > C::EP_BYTES ? C::STAGE_BYTES : C::EP_BYTES;
+  __shared__ __attribute__((aligned(1024))) unsigned char stage0[S0_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char stage1[C::STAGE_BYTES];
+  __shared__ int lds_misc[4];
+  __shared__ void* lds_outs[FLUX_MAX_RANKS];
+  if (EPI == EPI_RS) fill_lds_outs(a_, lds_outs, (int)threadIdx.x);
+  if (a_.persist_delay_ticks != 0 && ((blockIdx.x >> 3) & 1)) {
+    const uint64_t t0 = wall_clock64();
+    while (wall_clock64() - t0 < a_.persist_delay_ticks) __builtin_amdgcn_s_sleep(32);
+  }
+  const int n_blocks = a_.persist_blocks;
+  for (int vb = (int)blockIdx.x; vb < n_blocks; vb += (int)gridDim.x) {
+    // The argument block is read afresh for every block (the struct is the kernel's only argument and
+    // lies at the start of the argument segment): fetched once before the loop, its hundred-odd scalars
+    // would be kept in registers across the main loop, which has none to spare.
+    typedef const GemmArgs __attribute__((address_space(4))) * ArgPtr;
+    ArgPtr ap = (ArgPtr)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+    const GemmArgs& a = *(const GemmArgs*)ap;
+    // ... and so is everything a lane derives from its index (fragment addresses, load offsets)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    int tile, split;
+    bool is_split;
+    map_block(a, vb, tile, split, is_split);
+    int mt, nt;
+    tile_coord(a.tm, tile, mt, nt);
+    const int m0 = mt * C::BM, n0 = nt * C::BN;
+    trace_begin(a, tile, mt, nt, split, is_split, vb);
+    const int k_begin = is_split ? split * a.k_per_split : 0;
+    const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
+    const int KT = (k_end - k_begin) / C::BK;
+    f32x16 acc[C::MI][C::NI];
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.f;
+    DmaLoader<C> ld;
+    ld.init(a, m0, n0, wave, lane);
+    ld.issue(a, stage0, k_begin, wave);
+    wait_vm0_and_barrier();
+    const int k_last = k_begin + (KT - 1) * C::BK;
+    int kt = 0;
+    for (; kt + 2 <= KT; kt += 2) {
+      mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
+      wait_vm0_and_barrier();
+      const int k2 = k_begin + (kt + 2) * C::BK;
+      mma_stage_dma<C, true>(stage1, stage0, ld, a, k2 < k_last ? k2 : k_last, wave, wm, wn, lane, acc);
+      wait_vm0_and_barrier();
+    }
+    if (kt < KT) {
+      mma_stage_dma<C, true>(stage0, stage1, ld, a, k_last, wave, wm, wn, lane, acc);
+      wait_vm0_and_barrier();
+    }
+    gemm_tail<C, EPI, false>(a, stage0, lds_misc, lds_outs, acc, tile, split, is_split, m0, n0, tid, lane, wave, wm, wn, vb);
+    __syncthreads();      // the staging area and lds_misc are the next block's
+  }
 }
 
 // ---------------------------------------------------------------------------------------------

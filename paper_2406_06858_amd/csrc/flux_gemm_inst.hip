@@ -36,6 +36,12 @@ enum : int { EDGE_NONE = 0, EDGE_ANY = 1, EDGE_ROWS = 2 };
 template <int EPI, bool WAIT, int EDGE>
 static hipError_t launch_one(const GemmArgs& a, int grid, hipStream_t s) {
   if constexpr (EDGE == EDGE_NONE && Cfg::NSTAGE == 2) {
+    if constexpr (!WAIT && Cfg::OCC == 1) {
+      if (a.persist_blocks > 0) {
+        hipLaunchKernelGGL((gemm_kernel_dma_resident<Cfg, EPI>), dim3(grid), dim3(Cfg::NT), 0, s, a);
+        return hipGetLastError();
+      }
+    }
     hipLaunchKernelGGL((gemm_kernel_dma<Cfg, EPI, WAIT>), dim3(grid), dim3(Cfg::NT), 0, s, a);
     return hipGetLastError();
   } else if constexpr (EDGE != EDGE_ANY && Cfg::NSTAGE >= 3) {

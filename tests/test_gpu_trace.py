@@ -159,6 +159,55 @@ def test_ag_trace_matches_oracle_tile_coord(order, cfg):
     gh.assert_close(Cout, C64, w.out_dtype)
 
 
+def test_rs_resident_grid_walks_the_same_blocks_in_order():
+    """A reduce-scatter grid of many short tiles runs as one resident workgroup per compute unit (256 of
+    them) that walks the block sequence of Sec. 4.1 with the grid's stride, half of them starting late.
+    Every block still leaves one record with the oracle's tile; blocks b and b + 256 ran on the same
+    compute unit one after the other; the late half starts late by what the library says; the result is
+    the one-workgroup-per-tile form's bit for bit, and the oracle's within tolerance."""
+    w = fi.Workload("rs_resident", "rs", 8192, 8192, 256, 8, seed=94)
+    rank = 3
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank)
+    wgs, delay = fb.flux_rs_resident_grid(p)
+    assert wgs == 256 and delay > 0
+    q = fb.problem(w.M, w.N, w.K, w.R, rank, flags=fb.FLUX_FLAG_NO_RESIDENT_GRID)
+    assert fb.flux_rs_resident_grid(q) == (0, 0)
+    grid, tile, part, coords, sh, split_k = _expected_tiles("rs", p, w, rank, None, 8)
+    assert (sh.tile_m, sh.tile_n) == (256, 256) and split_k == 1 and grid == 1024
+    _say("rs resident grid", grid, "blocks on", wgs, "workgroups, delay", delay, "ticks")
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
+    outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
+    outs1 = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(w.R)]
+    trace = torch.zeros((grid, 8), dtype=torch.int64, device=gh.DEV)
+    fb.flux_trace_next_call(trace)
+    fb.flux_gemm_rs(p, dA, dB, dpeers, outs)
+    fb.flux_gemm_rs(q, dA, dB, dpeers, outs1)
+    torch.cuda.synchronize()
+    rec = _records(trace, grid)
+    assert np.array_equal(rec["block"], np.arange(grid))
+    assert np.array_equal(rec["tile"], tile)
+    assert np.array_equal(np.stack([rec["m_tile"], rec["n_tile"]], axis=1), coords[tile])
+    assert (rec["t_start"] <= rec["t_main_end"]).all() and (rec["t_main_end"] <= rec["t_end"]).all()
+    where = rec["die"] * 256 + ((rec["hw_id"].astype(np.int64) >> 8) & 0xff)     # die, shader engine, array, compute unit
+    for b in range(grid - wgs):
+        assert where[b] == where[b + wgs], ("blocks of one workgroup on different units", b)
+        assert rec["t_end"][b] <= rec["t_start"][b + wgs] + JITTER_TICKS, ("a workgroup's blocks overlap", b)
+    assert len(set(where[:wgs].tolist())) == wgs                 # one workgroup per compute unit
+    late = ((np.arange(wgs) >> 3) & 1) == 1
+    t0 = rec["t_start"][:wgs]
+    shift = float(np.median(t0[late]) - np.median(t0[~late]))
+    assert 0.7 * delay <= shift <= 1.3 * delay + 2 * JITTER_TICKS, (shift, delay)
+    # the order of Sec. 4.1, in time: a later round of blocks starts after an earlier one
+    med = [float(np.median(rec["t_start"][i:i + wgs])) for i in range(0, grid, wgs)]
+    assert all(x < y for x, y in zip(med, med[1:])), med
+    s64, _ = gh.oracle_rs(w, rank, A, B, peers)
+    for r in range(w.R):
+        gh.assert_close(outs[r], s64[r], w.out_dtype, f"slice {r}")
+        assert torch.equal(outs[r].view(torch.int16), outs1[r].view(torch.int16)), f"slice {r}: the two grid forms differ"
+
+
 def test_trace_buffer_too_small_is_rejected():
     w = fi.Workload("rs_trace_small", "rs", 1024, 1024, 256, 8, seed=93)
     rank = 0

@@ -278,3 +278,19 @@ def test_trace_request_arguments():
     # a pending request does not survive a call that is rejected for its own reasons ...
     assert L.flux_trace_next_call(4096, 1 << 20) == fb.FLUX_OK
     assert L.flux_trace_next_call(None, 0) == fb.FLUX_OK
+
+
+def test_resident_grid_is_planned_for_many_short_reduce_scatter_tiles():
+    """flux_rs_resident_grid: four rounds or more of 256x256 tiles with K <= 3072 and the Reduce epilogue."""
+    c4 = fb.problem(8192, 12288, 1536, 8, 2)
+    n, d = fb.flux_rs_resident_grid(c4)
+    assert n == 256 and 3000 <= d <= 3800                       # half of (36 us main loop + 32 us epilogue)
+    assert fb.flux_rs_resident_grid(fb.problem(8192, 12288, 1536, 8, 2, flags=fb.FLUX_FLAG_NO_RESIDENT_GRID)) == (0, 0)
+    assert fb.flux_rs_resident_grid(fb.problem(8192, 12288, 1536, 8, 2, flags=fb.FLUX_FLAG_RS_WRITE_ONLY)) == (0, 0)
+    assert fb.flux_rs_resident_grid(fb.problem(4096, 8192, 3584, 8, 2)) == (0, 0)       # two rounds, long K
+    assert fb.flux_rs_resident_grid(fb.problem(8192, 12288, 6144, 8, 2)) == (0, 0)      # long K
+    assert fb.flux_rs_resident_grid(fb.problem(8192, 12288, 1536, 8, 2, tile_config=2)) == (0, 0)
+    assert fb.flux_rs_resident_grid(fb.problem(8192 + 8, 12288, 1536, 8, 2)) == (0, 0)  # ragged: other kernel
+    # the blocks and their order do not depend on the form
+    assert fb.flux_split_plan(fb.FLUX_OP_RS, c4) == fb.flux_split_plan(
+        fb.FLUX_OP_RS, fb.problem(8192, 12288, 1536, 8, 2, flags=fb.FLUX_FLAG_NO_RESIDENT_GRID))
