@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # bytes per launch behind the L2 of the two kernels of the timed step (rocprofv3 FETCH_SIZE + WRITE_SIZE)
-TRAFFIC_BYTES = {"rs": 1950.0e6 + 201.3e6, "ag": 2637.8e6 + 319.0e6}     # profiles/bench_c4_pmc_traffic.txt
+TRAFFIC_BYTES = {"rs": 2168.5e6 + 205.8e6, "ag": 2604.3e6 + 319.0e6}     # profiles/bench_c4_pmc_traffic.txt
 HBM_PEAK_GBS = 8000.0
 TIMEOUT_TICKS = 500_000_000        # 5 s: a lost signal ends the run with an error, not a hang
 
@@ -189,6 +189,14 @@ def main() -> int:
                     fb.flux_init_buffers(fb.FLUX_OP_RS, self.p_at, self.ws_at)
             fb.flux_gemm_rs(self.p_at, self.A, self.next_B(), None, self.outs_f32, self.ws_at, compute)
 
+        def one_workgroup_per_tile(self):
+            # the same fused call without the resident grid (only differs where the library plans one)
+            if not hasattr(self, "p_1pt"):
+                w = self.w
+                self.p_1pt = fb.problem(w.M, w.N, w.K, w.R, self.rank, w.partial_dtype, w.out_dtype,
+                                        flags=fb.FLUX_FLAG_NO_RESIDENT_GRID)
+            fb.flux_gemm_rs(self.p_1pt, self.A, self.next_B(), self.peers, self.outs, self.ws, compute)
+
         def alg_bytes(self):
             w = self.w
             ps = 2 if w.partial_dtype == "bf16" else 4
@@ -258,6 +266,9 @@ def main() -> int:
             more["ms_fused_graph_replay"] = round(t_graph, 4)
         if t_atomic is not None:
             more["ms_atomic_reduce_f32"] = round(t_atomic, 4)
+        if hasattr(op, "one_workgroup_per_tile") and fb.flux_rs_resident_grid(op.p)[0] > 0:
+            more["resident_grid"] = dict(zip(("workgroups", "late_start_ticks_100MHz"), fb.flux_rs_resident_grid(op.p)))
+            more["ms_fused_one_workgroup_per_tile"] = round(time_calls(op.one_workgroup_per_tile, reps, warm), 4)
         return {**more, "ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
                 "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4), "ms_chunked": round(t_chk, 4),
                 "overlap_efficiency_chunked": None if ect_no <= 0 else round(1.0 - (t_chk - t_gemm) / ect_no, 4),

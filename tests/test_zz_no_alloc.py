@@ -72,6 +72,28 @@ def test_static_scratch_fp32_variant_and_problems_without_a_k_cut():
         assert torch.equal(got[r], want[r])
 
 
+def test_static_entry_point_with_a_resident_grid():
+    """Many short tiles run as a grid of resident workgroups (no scratch needed): twice in a row, then a
+    K-cut problem that does use the array."""
+    w = fi.Workload("rs_resident_static", "rs", 8192, 8192, 256, 8, seed=94)
+    p, A, B, peers, want, got = _both(w, 3)
+    assert fb.flux_rs_resident_grid(p)[0] == 256
+    small = fi.Workload("rs_small", "rs", 8, 1024, 2048, 8, seed=95)
+    ps, As, Bs, pes, wants, gots = _both(small, 3)
+    for i in range(2):
+        print("static resident call", i, flush=True)
+        for g in got:
+            g.fill_(float("nan"))
+        fb.flux_gemm_rs_static(p, A, B, peers, got)
+        torch.cuda.synchronize()
+        for r in range(w.R):
+            assert torch.equal(got[r].view(torch.int16), want[r].view(torch.int16)), f"call {i}, slice {r}"
+    fb.flux_gemm_rs_static(ps, As, Bs, pes, gots)
+    torch.cuda.synchronize()
+    for r in range(8):
+        assert torch.equal(gots[r].view(torch.int16), wants[r].view(torch.int16))
+
+
 def test_static_scratch_rejects_what_does_not_fit():
     # 8192 x 4608 x 12288: the 64 tiles of the last round are cut four ways, 64 MB of partials
     p = fb.problem(8192, 4608, 12288, 8, 0)
