@@ -289,6 +289,31 @@ def test_tail_split_bitwise_on_integers(cfg, M, N, K):
     gh.assert_bits_equal(Cn, want, f"cfg {cfg} no tail split")
 
 
+def test_resident_grid_with_a_k_cut_tail_bitwise_on_integers():
+    """Four whole rounds of 256x256 tiles plus 32 tiles cut along K, all walked by 256 resident workgroups:
+    a K part that is not its tile's last ends its block early and the workgroup goes on to the next one."""
+    M, N, K, R, rank = 8192, 8448, 1024, 8, 5
+    w = fi.Workload("int_rs_resident_tail", "rs", M, N, K, R, a_dist=("int", 2), b_dist=("int", 2), peer_dist=("int", 8), seed=83)
+    p = fb.problem(M, N, K, R, rank)
+    full, cut, k = fb.flux_split_plan(fb.FLUX_OP_RS, p)
+    assert (full, cut) == (1024, 32) and k > 1, (full, cut, k)
+    assert fb.flux_rs_resident_grid(p)[0] == 256
+    _say("resident grid with tail", (full, cut, k))
+    A, B, peers = fi.make_rs_inputs(w, rank)
+    _, want = gh.oracle_rs(w, rank, A, B, peers)
+    dA, dB = A.to(gh.DEV), B.to(gh.DEV)
+    dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
+    ws = gh.workspace_for(fb.FLUX_OP_RS, p)
+    ws.fill_(-1)
+    fb.flux_init_buffers(fb.FLUX_OP_RS, p, ws)
+    for rep in range(2):
+        outs = [torch.full((w.S, N), float("nan"), dtype=torch.bfloat16, device=gh.DEV) for _ in range(R)]
+        fb.flux_gemm_rs(p, dA, dB, dpeers, outs, ws)
+        torch.cuda.synchronize()
+        for r in range(R):
+            gh.assert_bits_equal(outs[r], want[r], f"rep {rep} slice {r}")
+
+
 # ---------------------------------------------------------------------------------------------
 # AllGather protocol: orders, signals, copy engines, timing
 # ---------------------------------------------------------------------------------------------
