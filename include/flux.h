@@ -89,6 +89,11 @@ typedef enum { FLUX_OP_RS = 0, FLUX_OP_AG = 1 } flux_op_t;
                                         owner that never runs and is taken over by a workgroup that waits for
                                         it.  For tests of that take-over; costs time, never correctness. */
 
+#define FLUX_FLAG_AG_COPY_UPFRONT 0x200u /* flux_ag_gemm without a copy kernel: move every remote chunk before the
+                                        signal wait.  Without the flag a grid of several rounds moves only
+                                        the chunks its first round needs up front and carries the others
+                                        inside the first round's main loops (see flux_ag_deferred_tiles). */
+
 #define FLUX_FLAG_NO_RESIDENT_GRID 0x100u /* flux_gemm_rs: always one workgroup per tile, dispatched by the hardware.
                                         Without the flag a grid of at least four rounds of 256x256 tiles with
                                         K <= 3072 runs as one resident workgroup per compute unit that walks
@@ -356,6 +361,14 @@ int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_
  * and the tile trace (one record per block) are the same in both forms.  Host function.
  */
 int32_t flux_rs_resident_grid(const flux_problem_t* p, uint32_t* delay_ticks);
+
+/*
+ * How many of the R-1 remote chunks flux_ag_gemm (default form: no copy kernel) would move inside the
+ * main loops of its first round of workgroups instead of before the signal wait (Sec. 3.2: tiles whose
+ * data has arrived compute while the rest is on its way): the last that many chunks of the arrival
+ * order.  0: everything is moved up front.  Host function.
+ */
+int32_t flux_ag_deferred_tiles(const flux_problem_t* p);
 
 /* Tile configuration a call would use: tile sizes, K split and die count used for the remap. */
 int flux_tile_shape(int op, const flux_problem_t* p, int32_t* tile_m, int32_t* tile_n,

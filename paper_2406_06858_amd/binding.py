@@ -25,6 +25,7 @@ FLUX_FLAG_NO_TAIL_SPLIT = 0x10
 FLUX_FLAG_RS_WRITE_ONLY = 0x20
 FLUX_FLAG_AG_ABSENT_OWNERS = 0x40
 FLUX_FLAG_NO_RESIDENT_GRID = 0x100
+FLUX_FLAG_AG_COPY_UPFRONT = 0x200
 FLUX_FLAG_RS_ATOMIC = 0x80
 FLUX_PHASE_GEMM, FLUX_PHASE_COMM = 0x1, 0x2
 FLUX_MAX_RANKS = 16
@@ -37,7 +38,7 @@ EXPORTS = [
     "flux_chunked_workspace_bytes", "flux_rs_reduce_slice",
     "flux_autotune_rs", "flux_autotune_ag", "flux_autotune_workspace_bytes", "flux_autotune_signal_count",
     "flux_trace_next_call", "flux_gemm_rs_static",
-    "flux_gemm_rs_notify", "flux_rs_reduce_slice_ready", "flux_rs_ready_count", "flux_rs_resident_grid",
+    "flux_gemm_rs_notify", "flux_rs_reduce_slice_ready", "flux_rs_ready_count", "flux_rs_resident_grid", "flux_ag_deferred_tiles",
 ]
 
 
@@ -81,6 +82,8 @@ def lib():
         L.flux_rs_reduce_slice_ready.restype = C.c_int
         L.flux_rs_ready_count.argtypes = [pp]
         L.flux_rs_ready_count.restype = C.c_int32
+        L.flux_ag_deferred_tiles.argtypes = [pp]
+        L.flux_ag_deferred_tiles.restype = C.c_int32
         L.flux_rs_resident_grid.argtypes = [pp, C.POINTER(C.c_uint32)]
         L.flux_rs_resident_grid.restype = C.c_int32
         L.flux_ag_gemm.argtypes = [pp, pvp, vp, vp, vp, vp, pi32, vp, C.c_size_t, vp, vp]
@@ -184,6 +187,10 @@ def flux_gemm_rs_static(p, A, B, peer_partials, out_slices, stream=None):
 
 def flux_rs_ready_count(p) -> int:
     return int(lib().flux_rs_ready_count(C.byref(p)))
+
+
+def flux_ag_deferred_tiles(p) -> int:
+    return int(lib().flux_ag_deferred_tiles(C.byref(p)))
 
 
 def flux_rs_resident_grid(p) -> tuple[int, int]:

@@ -269,6 +269,8 @@ struct Plan {
   int copy_help;            // waiting GEMM workgroups may take pieces
   int copy_self;            // no copy kernel at all: the GEMM grid moves everything
   int copy_owners;          // ... its first copy_owners workgroups sharing the pieces out by index
+  int defer_tiles;          // ... the last defer_tiles remote communication tiles carried inside the first round's main loops,
+  int defer_steps;          //     defer_steps vectors per thread and tile
   int resident;             // reduce-scatter: one resident workgroup per compute unit walks the blocks ...
   uint32_t resident_delay_ticks;   // ... every second group of eight starting this late (100 MHz ticks)
   size_t claim_bytes;       // claim words in the workspace, after the header
@@ -468,7 +470,7 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     pl->resident_delay_ticks = (uint32_t)std::min(20000.0, (main_ticks + epi_ticks) / 2);
   }
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
-  pl->copy_wgs = 0; pl->copy_pieces = 0; pl->copy_help = 0; pl->copy_self = 0; pl->copy_owners = 0; pl->claim_bytes = 0;
+  pl->copy_wgs = 0; pl->copy_pieces = 0; pl->copy_help = 0; pl->copy_self = 0; pl->copy_owners = 0; pl->claim_bytes = 0; pl->defer_tiles = 0; pl->defer_steps = 0;
   if (op == FLUX_OP_AG) {
     // Driver: one piece of every communication tile per workgroup.  A small driver: it keeps the
     // later chunks coming in the background while waiting GEMM workgroups pull what they need now;
@@ -503,6 +505,26 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
       const long long grid = (long long)pl->full_tiles + (long long)pl->split_tiles * pl->split_k;
       pl->copy_owners = (int)std::min<long long>(grid, (long long)N_CU * g_cfgs[cfg].occupancy);
       if (p->flags & FLUX_FLAG_AG_ABSENT_OWNERS) pl->copy_owners = (int)std::min<long long>(2 * grid, 1 << 20);
+      // A grid of several rounds needs only the chunks of its first round's tiles before it can
+      // start.  The others are carried inside the first round's main loops, a 16-byte vector per
+      // thread and K slab, where they cost neither matrix-core time nor a wait: workgroup w moves
+      // piece w of each of them.  Asked of the two-stage kernel on shapes the tile divides, with one
+      // signal per chunk and the swizzled order (a band of tiles per chunk), a first round of whole
+      // tiles that covers every piece, and a K long enough for all of a workgroup's vectors.
+      const int S = p->M / p->R;
+      const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
+      const long long band_sz = (S % pl->bm == 0) ? (long long)(S / pl->bm) * pl->tiles_n : 0;
+      if (!(p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_AG_ABSENT_OWNERS | FLUX_FLAG_AG_COPY_UPFRONT)) && pl->ctpc == 1 &&
+          g_cfgs[cfg].stages == 2 && g_cfgs[cfg].occupancy == 1 && pl->edge == 0 && band_sz > 0 && grid > slots &&
+          (pl->split_k == 1 ? tiles : (long long)pl->full_tiles) >= slots && pl->copy_pieces <= pl->copy_owners && tile_vec * 16ull < (1ull << 31)) {
+        const long long bands_first = (slots + band_sz - 1) / band_sz;       // bands the first round touches, the local one included
+        const long long deferred = (long long)p->R - bands_first;             // remote chunks nobody needs before the second round
+        const long long steps = (long long)((tile_vec + (unsigned long long)pl->copy_pieces * 256 - 1) / ((unsigned long long)pl->copy_pieces * 256));
+        if (deferred >= 1 && deferred * steps + 8 <= kt) {
+          pl->defer_tiles = (int)deferred;
+          pl->defer_steps = (int)steps;
+        }
+      }
     }
     pl->claim_bytes = (((size_t)p->R * pl->ctpc * pl->copy_pieces * 4) + 255) / 256 * 256;
   }
@@ -847,6 +869,12 @@ int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_
   return FLUX_OK;
 }
 
+int32_t flux_ag_deferred_tiles(const flux_problem_t* p) {
+  Plan pl;
+  if (p == nullptr || make_plan(FLUX_OP_AG, p, &pl) != FLUX_OK) return 0;
+  return pl.defer_tiles;
+}
+
 int32_t flux_rs_resident_grid(const flux_problem_t* p, uint32_t* delay_ticks) {
   Plan pl;
   if (delay_ticks) *delay_ticks = 0;
@@ -1055,6 +1083,8 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
     if (pl.copy_self) {
       a.copy_owner_wgs = pl.copy_owners;
       a.copy_n_tiles = (p->R - 1) * pl.ctpc;
+      a.copy_defer_tiles = pl.defer_tiles;
+      a.copy_defer_steps = pl.defer_steps;
       static_assert(FLUX_MAX_RANKS <= 16, "chunk indices are packed four bits each");
       for (int i = 0; i < p->R - 1; ++i) a.copy_order4 |= (unsigned long long)order[i] << (4 * i);
     }

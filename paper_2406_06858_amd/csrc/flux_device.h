@@ -124,6 +124,11 @@ struct GemmArgs {
   uint32_t copy_call_id;     // 0: take the id from copy_call_seq (calls without a copy kernel)
   int32_t copy_driver_wgs;   // workgroups of the copy kernel launched beside this grid (0: none)
   int32_t copy_n_tiles;
+  // The last copy_defer_tiles remote communication tiles of the transfer order are not moved before
+  // the signal wait: the workgroups of the first round carry them inside their main loops (piece w
+  // of each such tile by workgroup w, copy_defer_steps 16-byte vectors per thread and tile).
+  int32_t copy_defer_tiles;
+  int32_t copy_defer_steps;
   // ---- split-K hand-over, reduce-scatter epilogue ----
   int32_t write_only;        // 1: reduce-scatter epilogue without the reduction (Write branch of Alg. 1);
                              // 2: no peers are read, the tile is added to the slice with atomic additions
@@ -596,7 +601,7 @@ __device__ __forceinline__ void transfer_own_pieces(const GemmArgs& a, int* lds,
   if ((int)blockIdx.x >= a.copy_owner_wgs) return;
   const int tid = threadIdx.x;
   const int ctpc = a.n_signals / a.R;
-  const int total = a.copy_n_tiles * a.copy_pieces;
+  const int total = (a.copy_n_tiles - a.copy_defer_tiles) * a.copy_pieces;
   const int G = a.copy_owner_wgs;
   if (total <= G && a.copy_tile_vec <= (unsigned long long)a.copy_pieces * 256 * COPY_DEPTH) {
     // A small transfer (decode): at most one piece per owner, moved in one pass.  Then the whole
@@ -835,6 +840,104 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   __syncthreads();
   return ok;
 }
+
+// The transfer carried inside the main loop (Sec. 3.2: the tiles whose data has arrived compute while
+// the rest is still on its way).  A workgroup of the first round owns piece `blockIdx.x` of every
+// deferred communication tile and moves it one 16-byte vector per thread and K slab, tile after tile:
+// a load at the end of a slab, the store of what was loaded two slabs earlier at the start of one, so
+// that neither is ever waited for.  All addressing goes through buffer resources whose size is the
+// tile's (or zero for a workgroup with nothing to move, a tile taken over by somebody else, or when
+// all tiles are done), so a lane past the end, and everything such a workgroup issues, is dropped by
+// the range check: the loop has one shape for every workgroup and no branch around a memory access.
+struct SideCopy {
+  __amdgpu_buffer_rsrc_t rs, rd;     // source chunk / its place in the gathered matrix, for the tile being loaded / stored
+  uint32_t first, ld_off, st_off;    // this lane's first vector of a piece, next to load, next to store (byte offsets in the tile)
+  uint32_t stride;                   // bytes between a lane's vectors
+  int n_tiles, n_steps;              // deferred tiles; vectors per thread and tile
+  int ld_t, ld_s, st_t, st_s;        // cursors: tile and step
+  uint32_t mine;                     // bit t: this workgroup claimed its piece of deferred tile t
+  int done_steps;                    // stores issued so far (over all tiles)
+
+  __device__ __forceinline__ int tile_index(const GemmArgs& a, int t) const {      // communication tile (= signal) of deferred tile t
+    return (int)((a.copy_order4 >> (4 * (a.copy_n_tiles - a.copy_defer_tiles + t))) & 15);
+  }
+  __device__ __forceinline__ unsigned records(const GemmArgs& a, int t) const {
+    return (t < n_tiles && ((mine >> t) & 1u)) ? (unsigned)(a.copy_tile_vec * 16ull) : 0u;
+  }
+  __device__ __forceinline__ void set_src(const GemmArgs& a, void* const* lds_srcs, int t) {
+    const int f = t < n_tiles ? tile_index(a, t) : 0;
+    const uint64_t addr = reinterpret_cast<uint64_t>(lds_srcs[f]);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr), hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
+    rs = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0, (int)records(a, t), 0x00027000);
+  }
+  __device__ __forceinline__ void set_dst(const GemmArgs& a, int t) {
+    const int f = t < n_tiles ? tile_index(a, t) : 0;
+    unsigned char* base = reinterpret_cast<unsigned char*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec * 16ull;
+    rd = __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)records(a, t), 0x00027000);
+  }
+
+  // Claims this workgroup's pieces (one exchange per deferred tile, all in one round trip) and sets
+  // the cursors up.  `lds` is one int shared by the workgroup.  All threads call this.
+  __device__ __forceinline__ void begin(const GemmArgs& a, int* lds, void* const* lds_srcs) {
+    const int tid = threadIdx.x;
+    n_tiles = 0; mine = 0u; n_steps = a.copy_defer_steps;
+    const int deferred = a.copy_defer_tiles;
+    if (deferred > 0 && (int)blockIdx.x < a.copy_pieces && (int)blockIdx.x < a.copy_owner_wgs) n_tiles = deferred;
+    if (n_tiles > 0) {           // (uniform)
+      if (tid < 64) {
+        bool won = false;
+        if (tid < n_tiles)
+          won = claim_piece(a.copy_claims + (size_t)tile_index(a, tid) * a.copy_pieces + blockIdx.x, transfer_call_id(a));
+        const unsigned long long w = __ballot(won);
+        if (tid == 0) *lds = (int)(uint32_t)w;
+      }
+      __syncthreads();
+      mine = (uint32_t)__builtin_amdgcn_readfirstlane(*lds);
+      __syncthreads();
+    }
+    first = ((uint32_t)blockIdx.x * 256u + (uint32_t)tid) * 16u;
+    stride = (uint32_t)a.copy_pieces * 256u * 16u;
+    ld_off = st_off = first;
+    ld_t = ld_s = st_t = st_s = 0;
+    done_steps = 0;
+    set_src(a, lds_srcs, 0);
+    set_dst(a, 0);
+  }
+  __device__ __forceinline__ bool pending() const { return mine != 0u; }
+  __device__ __forceinline__ bool all_stored() const { return done_steps >= n_tiles * n_steps; }
+
+  __device__ __forceinline__ u32x4 load(const GemmArgs& a, void* const* lds_srcs) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)ld_off, 0, 2);      // streamed: not kept in the caches
+    ld_off += stride;
+    if (++ld_s == n_steps) { ld_s = 0; ld_off = first; set_src(a, lds_srcs, ++ld_t); }
+    return v;
+  }
+  __device__ __forceinline__ void store(const GemmArgs& a, const u32x4& v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, rd, (int)st_off, 0, 16);                 // device scope: written through the die's L2
+    st_off += stride;
+    ++done_steps;
+    if (++st_s == n_steps) { st_s = 0; st_off = first; set_dst(a, ++st_t); }
+  }
+  // After the last store: the pieces are counted in, a tile whose last piece this was gets its
+  // signal (SetSignal of Alg. 3).  All threads call this.
+  __device__ __forceinline__ void finish(const GemmArgs& a) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int t = 0; t < n_tiles; ++t) {
+        if (!((mine >> t) & 1u)) continue;
+        const int f = tile_index(a, t);
+        const uint32_t prev = __hip_atomic_fetch_add(a.copy_counters + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1u == (uint32_t)a.copy_pieces) {
+          __hip_atomic_store(a.copy_counters + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+          __hip_atomic_store(a.signals + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+      }
+    }
+    mine = 0u;
+    __syncthreads();
+  }
+};
 
 // Reduce by atomic additions on device memory (Sec. 4.2, "Reduce", first form): the owner's fp32 slice
 // already holds what the other ranks have added; every element of the tile is added to it with one
@@ -1327,6 +1430,20 @@ __device__ __forceinline__ void mma_stage_dma_opaque(const unsigned char* cur_p,
   }
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vm_at_most() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));   // expcnt and lgkmcnt: no wait
+}
+
+// Workgroup barrier that lets this wave's younger loads stay in flight.  The compiler puts a wait
+// for ALL outstanding memory operations in front of every barrier instruction it can see, which
+// would empty the pipeline once per slab; it does not look inside this one.  What the barrier has
+// to order is covered by the counter wait placed before it.
+__device__ __forceinline__ void barrier_keeping_loads_in_flight() {
+  asm volatile("s_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ void wait_vm0_and_barrier() {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's LDS-bound loads have landed
   __syncthreads();
@@ -1354,9 +1471,19 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   if (EPI == EPI_RS || WAIT) {      // output slices (reduce-scatter) or chunk sources (all-gather), by rank
     fill_lds_outs(a, lds_outs, tid);
   }
+  SideCopy side;
   if (WAIT) {
     transfer_own_pieces(a, lds_misc, lds_outs);
-    if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) { trace_stamp(a, TRACE_END); return; }
+    side.begin(a, lds_misc, lds_outs);     // (also orders fill_lds_outs before the reads of lds_outs below)
+    if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) {
+      // given up: the pieces this workgroup claimed still have to be moved, or their tiles' signals never come
+      if (side.pending()) {
+        while (!side.all_stored()) side.store(a, side.load(a, lds_outs));
+        side.finish(a);
+      }
+      trace_stamp(a, TRACE_END);
+      return;
+    }
     trace_stamp(a, TRACE_READY);
   }
 
@@ -1381,6 +1508,35 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   // copy of it that the register allocator handles badly.
   const int k_last = k_begin + (KT - 1) * C::BK;
   int kt = 0;
+  if (WAIT && side.pending()) {
+    // With the transfer aboard (a workgroup of the first round with pieces to move; everybody else
+    // runs the plain loop below): per slab one store (of the vector loaded two slabs ago) ahead of
+    // the slab's operand loads and one load behind them.  "All but the youngest operation have
+    // completed" then means that the operand loads have landed (loads complete in order, and the one
+    // store is older than all of them), and the barrier must not make the compiler wait for that
+    // last load.  When the last vector is out, the pieces are counted in and the plain loop takes
+    // over for the rest of K.
+    u32x4 d0 = side.load(a, lds_outs), d1 = side.load(a, lds_outs);
+    for (; kt + 2 <= KT && side.pending(); kt += 2) {
+      side.store(a, d0);
+      mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
+      d0 = side.load(a, lds_outs);
+      wait_vm_at_most<1>();
+      barrier_keeping_loads_in_flight();
+      side.store(a, d1);
+      const int k2 = k_begin + (kt + 2) * C::BK;
+      mma_stage_dma<C, true>(stage1, stage0, ld, a, k2 < k_last ? k2 : k_last, wave, wm, wn, lane, acc);
+      d1 = side.load(a, lds_outs);
+      wait_vm_at_most<1>();
+      barrier_keeping_loads_in_flight();
+      if (side.all_stored()) side.finish(a);
+    }
+    wait_vm0_and_barrier();
+    if (side.pending()) {          // a K too short for the pieces: the rest goes now (the host does not plan this)
+      while (!side.all_stored()) { side.store(a, d0); d0 = d1; d1 = side.load(a, lds_outs); }
+      side.finish(a);
+    }
+  }
   for (; kt + 2 <= KT; kt += 2) {
     mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
     wait_vm0_and_barrier();
@@ -1472,20 +1628,6 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma_resident(const 
 // Stages are separate arrays (see above); the epilogue has its own staging area, so the tail of
 // the load pipeline need not drain before it starts.
 // ---------------------------------------------------------------------------------------------
-template <int N>
-__device__ __forceinline__ void wait_vm_at_most() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));   // expcnt and lgkmcnt: no wait
-}
-
-// Workgroup barrier that lets this wave's younger loads stay in flight.  The compiler puts a wait
-// for ALL outstanding memory operations in front of every barrier instruction it can see, which
-// would empty the pipeline once per slab; it does not look inside this one.  What the barrier has
-// to order is covered by the counter wait placed before it.
-__device__ __forceinline__ void barrier_keeping_loads_in_flight() {
-  asm volatile("s_barrier" ::: "memory");
-}
-
 // MASK: M is not a multiple of the tile height.  Rows past M are read as zeros (they lie outside
 // the buffer resource of A) and the epilogue leaves them out.
 // Counter wait of the first pass of the deep pipeline when the weights' part of the first slabs

@@ -493,6 +493,55 @@ def test_ag_gathered_matrix_not_line_aligned(cw):
         assert torch.equal(A_agg.cpu().view(torch.int16), want)
 
 
+AG_TWO_ROUNDS = fi.Workload("int_ag_two_rounds", "ag", 8192, 4608, 2048, 8, a_dist=("int", 2), b_dist=("int", 2), seed=84)
+
+
+@pytest.mark.parametrize("order", ["ring", "random"])
+def test_ag_later_chunks_travel_inside_the_main_loops(order):
+    """A grid of more than one round moves only the chunks its first round needs before the signal
+    wait; the others are carried inside the first round's main loops (Sec. 3.2: compute on what has
+    arrived while the rest is on its way).  Same bits as with everything moved up front, and as the
+    oracle's; the gathered matrix is complete; the second call finds the state the first one left."""
+    w, rank = AG_TWO_ROUNDS, 5
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    if order == "ring":
+        arrival = fo.default_order(rank, w.R)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank)
+    q = fb.problem(w.M, w.N, w.K, w.R, rank, flags=fb.FLUX_FLAG_AG_COPY_UPFRONT)
+    assert fb.flux_ag_deferred_tiles(p) == 4 and fb.flux_ag_deferred_tiles(q) == 0
+    _say("ag deferred transfer", order, "plan", fb.flux_split_plan(fb.FLUX_OP_AG, p))
+    _, want = gh.oracle_ag(w, chunks, B)
+    Cd, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, repeat=2)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_bits_equal(Cd, want, "C, later chunks inside the main loops")
+    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+    assert signals.tolist() == [1 if r == rank else 0 for r in range(w.R)]
+    Cu, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, flags=fb.FLUX_FLAG_AG_COPY_UPFRONT)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_bits_equal(Cu, want, "C, everything up front")
+
+
+def test_ag_deferred_pieces_are_moved_even_by_workgroups_that_give_up():
+    """Failure handling forced from the host: with a spin limit of one tick every workgroup that finds a
+    signal missing gives up at once.  The kernel exits, the status block reports a timeout, and the
+    gathered matrix is complete all the same: a workgroup moves the pieces it owns before it waits, and
+    those it was to carry inside its main loop before it leaves."""
+    w, rank = AG_TWO_ROUNDS, 1
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    assert fb.flux_ag_deferred_tiles(fb.problem(w.M, w.N, w.K, w.R, rank)) == 4
+    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, timeout_ticks=1)
+    code, detail = status
+    assert code == fb.FLUX_ERR_TIMEOUT and 0 <= detail < w.R and detail != rank
+    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg after a call that gave up")
+    _, want = gh.oracle_ag(w, chunks, B)
+    lo, hi = rank * w.S, (rank + 1) * w.S
+    gh.assert_bits_equal(Cg[lo:hi], want[lo:hi], "rows of the local chunk")
+    # after flux_init_buffers (run_ag does it) the same problem runs clean
+    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_bits_equal(Cg, want, "C after re-initialisation")
+
+
 def test_ag_signal_wait_times_out_cleanly():
     """Failure handling, forced from the host: the copy stream is held back and the spin limit
     is one tick, so waiting tiles give up, the kernel still exits, and the status block says

@@ -294,3 +294,19 @@ def test_resident_grid_is_planned_for_many_short_reduce_scatter_tiles():
     # the blocks and their order do not depend on the form
     assert fb.flux_split_plan(fb.FLUX_OP_RS, c4) == fb.flux_split_plan(
         fb.FLUX_OP_RS, fb.problem(8192, 12288, 1536, 8, 2, flags=fb.FLUX_FLAG_NO_RESIDENT_GRID))
+
+
+def test_deferred_transfer_is_planned_for_grids_of_several_rounds():
+    """flux_ag_deferred_tiles: the chunks the first round of workgroups does not touch, when every condition holds."""
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2)) == 4        # 2.25 rounds; the first covers 4 bands of 72 tiles
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 6144, 12288, 8, 2)) == 5        # three rounds, bands of 96 tiles
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, flags=fb.FLUX_FLAG_AG_COPY_UPFRONT)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, flags=fb.FLUX_FLAG_NO_SWIZZLE)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, comm_tiles_per_chunk=2)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, copy_workgroups=16)) == 0   # a copy kernel moves the data
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, link_gbps=400)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(4096, 3584, 8192, 8, 2)) == 0         # one round: every chunk is needed at once
+    assert fb.flux_ag_deferred_tiles(fb.problem(2048, 6144, 12288, 8, 2)) == 0        # the first round touches every chunk
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 512, 8, 2)) == 0          # K too short to carry the vectors
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, tile_config=2)) == 0   # other kernel
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 1, 0)) == 0
