@@ -271,6 +271,7 @@ struct Plan {
   int copy_owners;          // ... its first copy_owners workgroups sharing the pieces out by index
   int defer_tiles;          // ... the last defer_tiles remote communication tiles carried inside the first round's main loops,
   int defer_steps;          //     defer_steps vectors per thread and tile
+  unsigned long long pace_ticks;   // ... counted in on a link's schedule (100 MHz ticks per communication tile; 0: as they come)
   int resident;             // reduce-scatter: one resident workgroup per compute unit walks the blocks ...
   uint32_t resident_delay_ticks;   // ... every second group of eight starting this late (100 MHz ticks)
   size_t claim_bytes;       // claim words in the workspace, after the header
@@ -470,7 +471,7 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     pl->resident_delay_ticks = (uint32_t)std::min(20000.0, (main_ticks + epi_ticks) / 2);
   }
   pl->ctpc = p->comm_tiles_per_chunk <= 0 ? 1 : p->comm_tiles_per_chunk;
-  pl->copy_wgs = 0; pl->copy_pieces = 0; pl->copy_help = 0; pl->copy_self = 0; pl->copy_owners = 0; pl->claim_bytes = 0; pl->defer_tiles = 0; pl->defer_steps = 0;
+  pl->copy_wgs = 0; pl->copy_pieces = 0; pl->copy_help = 0; pl->copy_self = 0; pl->copy_owners = 0; pl->claim_bytes = 0; pl->defer_tiles = 0; pl->defer_steps = 0; pl->pace_ticks = 0;
   if (op == FLUX_OP_AG) {
     // Driver: one piece of every communication tile per workgroup.  A small driver: it keeps the
     // later chunks coming in the background while waiting GEMM workgroups pull what they need now;
@@ -497,30 +498,47 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     // whole extra round where the grid divided evenly before; on a grid that leaves units free it
     // still costs a second stream's fork and join, and waiting workgroups spin beside it.
     pl->copy_self = pl->copy_help && p->link_gbps == 0 && p->copy_workgroups == 0;
-    if (pl->copy_self) {
+    const long long grid = (long long)pl->full_tiles + (long long)pl->split_tiles * pl->split_k;
+    const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
+    const long long whole_tiles = pl->split_k == 1 ? tiles : (long long)pl->full_tiles;
+    // what the two-stage kernel's workgroups can carry themselves (see SideCopy)
+    const bool can_carry = g_cfgs[cfg].stages == 2 && g_cfgs[cfg].occupancy == 1 && pl->edge == 0 &&
+                           !(p->flags & (FLUX_FLAG_AG_ABSENT_OWNERS | FLUX_FLAG_AG_COPY_UPFRONT)) && tile_vec * 16ull < (1ull << 31);
+    if (pl->copy_help && p->link_gbps > 0 && p->copy_workgroups == 0 && can_carry && (p->R - 1) * pl->ctpc <= 32 && p->R > 1) {
+      // A transfer that stands for a link, without a driver: a driver's workgroups would each hold a
+      // compute unit for as long as the transfer lasts, which no link does.  Every remote tile is
+      // carried by the first round's workgroups, piece w by workgroup w: while a workgroup waits for
+      // its own signals it moves its pieces in batches, afterwards inside its main loop, and a tile
+      // is counted in (its signal set) on the link's schedule.
+      const long long owners = std::min<long long>(grid, slots);
+      pl->copy_self = 1;
+      pl->copy_wgs = 0;
+      pl->copy_pieces = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(std::min<long long>(MAX_COPY_PIECES, owners), tile_vec / 1024));
+      pl->copy_owners = (int)owners;
+      pl->defer_tiles = (p->R - 1) * pl->ctpc;
+      pl->defer_steps = (int)((tile_vec + (unsigned long long)pl->copy_pieces * 256 - 1) / ((unsigned long long)pl->copy_pieces * 256));
+      pl->pace_ticks = std::max<unsigned long long>(1, (unsigned long long)((double)tile_vec * 16.0 / (double)p->link_gbps / 10.0));
+    } else if (pl->copy_self) {
       // the first workgroups of the grid, as many as surely run at once, own the pieces
       pl->copy_wgs = 0;
       // pieces of 16 KiB or more, as many as the claim table allows
       pl->copy_pieces = (int)std::max<unsigned long long>(1, std::min<unsigned long long>(MAX_COPY_PIECES, tile_vec / 1024));
-      const long long grid = (long long)pl->full_tiles + (long long)pl->split_tiles * pl->split_k;
-      pl->copy_owners = (int)std::min<long long>(grid, (long long)N_CU * g_cfgs[cfg].occupancy);
+      pl->copy_owners = (int)std::min<long long>(grid, slots);
       if (p->flags & FLUX_FLAG_AG_ABSENT_OWNERS) pl->copy_owners = (int)std::min<long long>(2 * grid, 1 << 20);
       // A grid of several rounds needs only the chunks of its first round's tiles before it can
-      // start.  The others are carried inside the first round's main loops, a 16-byte vector per
+      // start.  The others are carried inside the first round's main loops, two 16-byte vectors per
       // thread and K slab, where they cost neither matrix-core time nor a wait: workgroup w moves
       // piece w of each of them.  Asked of the two-stage kernel on shapes the tile divides, with one
       // signal per chunk and the swizzled order (a band of tiles per chunk), a first round of whole
       // tiles that covers every piece, and a K long enough for all of a workgroup's vectors.
       const int S = p->M / p->R;
-      const long long slots = (long long)N_CU * g_cfgs[cfg].occupancy;
       const long long band_sz = (S % pl->bm == 0) ? (long long)(S / pl->bm) * pl->tiles_n : 0;
-      if (!(p->flags & (FLUX_FLAG_NO_SWIZZLE | FLUX_FLAG_AG_ABSENT_OWNERS | FLUX_FLAG_AG_COPY_UPFRONT)) && pl->ctpc == 1 &&
-          g_cfgs[cfg].stages == 2 && g_cfgs[cfg].occupancy == 1 && pl->edge == 0 && band_sz > 0 && grid > slots &&
-          (pl->split_k == 1 ? tiles : (long long)pl->full_tiles) >= slots && pl->copy_pieces <= pl->copy_owners && tile_vec * 16ull < (1ull << 31)) {
+      if (can_carry && !(p->flags & FLUX_FLAG_NO_SWIZZLE) && pl->ctpc == 1 && band_sz > 0 && grid > slots &&
+          whole_tiles >= slots && pl->copy_pieces <= pl->copy_owners) {
         const long long bands_first = (slots + band_sz - 1) / band_sz;       // bands the first round touches, the local one included
         const long long deferred = (long long)p->R - bands_first;             // remote chunks nobody needs before the second round
         const long long steps = (long long)((tile_vec + (unsigned long long)pl->copy_pieces * 256 - 1) / ((unsigned long long)pl->copy_pieces * 256));
-        if (deferred >= 1 && deferred * steps + 8 <= kt) {
+        if (deferred >= 1 && (deferred * steps + 1) / 2 + 8 <= kt) {
           pl->defer_tiles = (int)deferred;
           pl->defer_steps = (int)steps;
         }
@@ -1085,6 +1103,7 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
       a.copy_n_tiles = (p->R - 1) * pl.ctpc;
       a.copy_defer_tiles = pl.defer_tiles;
       a.copy_defer_steps = pl.defer_steps;
+      a.copy_pace_ticks = pl.pace_ticks;
       static_assert(FLUX_MAX_RANKS <= 16, "chunk indices are packed four bits each");
       for (int i = 0; i < p->R - 1; ++i) a.copy_order4 |= (unsigned long long)order[i] << (4 * i);
     }

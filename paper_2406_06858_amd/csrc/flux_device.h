@@ -129,6 +129,9 @@ struct GemmArgs {
   // of each such tile by workgroup w, copy_defer_steps 16-byte vectors per thread and tile).
   int32_t copy_defer_tiles;
   int32_t copy_defer_steps;
+  // ... and with copy_pace_ticks != 0 they stand for a link: the i-th tile of the transfer order is
+  // counted in no earlier than (i + 1) * copy_pace_ticks (100 MHz ticks) after the kernel started
+  unsigned long long copy_pace_ticks;
   // ---- split-K hand-over, reduce-scatter epilogue ----
   int32_t write_only;        // 1: reduce-scatter epilogue without the reduction (Write branch of Alg. 1);
                              // 2: no peers are read, the tile is added to the slice with atomic additions
@@ -667,6 +670,193 @@ __device__ __forceinline__ void transfer_own_pieces(const GemmArgs& a, int* lds,
   }
 }
 
+// The transfer carried by the GEMM's own waves (Sec. 3.2: the tiles whose data has arrived compute
+// while the rest is still on its way).  A workgroup of the first round owns piece `blockIdx.x` of
+// every deferred communication tile and moves it in 16-byte vectors per thread, tile after tile in
+// transfer order: inside its main loop two vectors per K slab (the loads at the end of a slab, the
+// stores of what was loaded two slabs earlier at the start of one, so that neither is ever waited
+// for), and in batches while it still waits for its own signals.  All addressing goes through
+// buffer resources whose size is the tile's (or zero for a workgroup with nothing to move, a tile
+// taken over by somebody else, or when all tiles are done), so a lane past the end, and everything
+// such a workgroup issues, is dropped by the range check: the loops have one shape for every
+// workgroup and no branch around a memory access.
+// With a pace (the transfer stands for a link of a given rate) the data still moves as fast as the
+// loops take it, but a tile is counted in, and so its signal set, no earlier than the link would
+// have delivered it: tile number i of the transfer order (i + 1) * pace_ticks after the workgroup
+// started (the workgroups of a first round start within a microsecond of each other).
+struct SideCopy {
+  __amdgpu_buffer_rsrc_t rs, rd;     // source chunk / its place in the gathered matrix, for the tile being loaded / stored
+  uint32_t first, ld_off, st_off;    // this lane's first vector of a piece, next to load, next to store (byte offsets in the tile)
+  uint32_t stride;                   // bytes between a lane's vectors
+  int n_tiles, n_steps, pos0;        // deferred tiles; vectors per thread and tile; transfer position of the first of them
+  int ld_t, ld_s, st_t, st_s;        // cursors: tile and step
+  int fin_t;                         // tiles counted in so far
+  uint32_t mine;                     // bit t: this workgroup claimed its piece of deferred tile t
+  unsigned long long t0, pace;       // start clock; 100 MHz ticks per tile (0: unpaced)
+  int* slot;                         // one int of LDS: whatever depends on the clock is decided by thread 0 and read from here
+
+  // deferred tile t -> its signal index (= communication tile index in the gathered matrix) and chunk
+  __device__ __forceinline__ void locate(const GemmArgs& a, int t, int& f, int& chunk, int& sub) const {
+    const int ctpc = a.n_signals / a.R;
+    const int pos = pos0 + t;
+    chunk = (int)((a.copy_order4 >> (4 * (pos / ctpc))) & 15);
+    sub = pos % ctpc;
+    f = chunk * ctpc + sub;
+  }
+  __device__ __forceinline__ unsigned records(const GemmArgs& a, int t) const {
+    return (t < n_tiles && ((mine >> t) & 1u)) ? (unsigned)(a.copy_tile_vec * 16ull) : 0u;
+  }
+  __device__ __forceinline__ void set_src(const GemmArgs& a, void* const* lds_srcs, int t) {
+    int f = 0, chunk = 0, sub = 0;
+    if (t < n_tiles) locate(a, t, f, chunk, sub);
+    const uint64_t addr = reinterpret_cast<uint64_t>(lds_srcs[chunk]) + (unsigned long long)sub * a.copy_tile_vec * 16ull;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr), hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
+    rs = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0, (int)records(a, t), 0x00027000);
+  }
+  __device__ __forceinline__ void set_dst(const GemmArgs& a, int t) {
+    int f = 0, chunk = 0, sub = 0;
+    if (t < n_tiles) locate(a, t, f, chunk, sub);
+    unsigned char* base = reinterpret_cast<unsigned char*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec * 16ull;
+    rd = __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)records(a, t), 0x00027000);
+  }
+
+  // Claims this workgroup's pieces (one exchange per deferred tile, all in one round trip) and sets
+  // the cursors up.  `lds` is one int shared by the workgroup, kept for this object.  All threads call this.
+  __device__ __forceinline__ void begin(const GemmArgs& a, int* lds, void* const* lds_srcs) {
+    const int tid = threadIdx.x;
+    slot = lds;
+    t0 = wall_clock64();
+    pace = a.copy_pace_ticks;
+    n_tiles = 0; mine = 0u; n_steps = a.copy_defer_steps;
+    pos0 = a.copy_n_tiles - a.copy_defer_tiles;
+    if (a.copy_defer_tiles > 0 && (int)blockIdx.x < a.copy_pieces && (int)blockIdx.x < a.copy_owner_wgs) n_tiles = a.copy_defer_tiles;
+    if (n_tiles > 0) {           // (uniform)
+      if (tid < 64) {
+        bool won = false;
+        if (tid < n_tiles) {
+          int f, chunk, sub;
+          locate(a, tid, f, chunk, sub);
+          won = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + blockIdx.x, transfer_call_id(a));
+        }
+        const unsigned long long w = __ballot(won);
+        if (tid == 0) *lds = (int)(uint32_t)w;
+      }
+      __syncthreads();
+      mine = (uint32_t)__builtin_amdgcn_readfirstlane(*lds);
+      __syncthreads();
+    }
+    first = ((uint32_t)blockIdx.x * 256u + (uint32_t)tid) * 16u;
+    stride = (uint32_t)a.copy_pieces * 256u * 16u;
+    ld_off = st_off = first;
+    ld_t = ld_s = st_t = st_s = 0;
+    fin_t = 0;
+    if (mine == 0u) fin_t = n_tiles = 0;
+    set_src(a, lds_srcs, 0);
+    set_dst(a, 0);
+  }
+  __device__ __forceinline__ bool pending() const { return fin_t < n_tiles; }         // something left to move or to count in
+  __device__ __forceinline__ bool all_stored() const { return st_t >= n_tiles; }
+  // Is there a tile whose stores are all issued and which may be counted in now?  Reads the clock:
+  // different waves may get different answers, so only thread 0's counts (see maybe_finish).
+  __device__ __forceinline__ bool due() const {
+    if (fin_t >= st_t) return false;
+    if (pace == 0ull) return st_t >= n_tiles;        // unpaced: everything is counted in together, at the end
+    return wall_clock64() - t0 >= (unsigned long long)(pos0 + fin_t + 1) * pace;
+  }
+  __device__ __forceinline__ bool may_be_due() const { return fin_t < st_t && (pace != 0ull || st_t >= n_tiles); }   // (uniform)
+
+  __device__ __forceinline__ u32x4 load(const GemmArgs& a, void* const* lds_srcs) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)ld_off, 0, 2);      // streamed: not kept in the caches
+    ld_off += stride;
+    if (++ld_s == n_steps) { ld_s = 0; ld_off = first; set_src(a, lds_srcs, ++ld_t); }
+    return v;
+  }
+  __device__ __forceinline__ void store(const GemmArgs& a, const u32x4& v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, rd, (int)st_off, 0, 16);                 // device scope: written through the die's L2
+    st_off += stride;
+    if (++st_s == n_steps) { st_s = 0; st_off = first; set_dst(a, ++st_t); }
+  }
+  // Counts in the tiles that are due (see due()).  A tile whose last piece this was gets its signal
+  // (SetSignal of Alg. 3).  All threads call this.
+  __device__ __forceinline__ void finish(const GemmArgs& a) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int upto = fin_t;
+      const int stored = st_t < n_tiles ? st_t : n_tiles;
+      if (pace == 0ull) {
+        upto = stored;
+      } else {
+        const unsigned long long now = wall_clock64() - t0;
+        while (upto < stored && now >= (unsigned long long)(pos0 + upto + 1) * pace) ++upto;
+      }
+      for (int t = fin_t; t < upto; ++t) {
+        if (!((mine >> t) & 1u)) continue;
+        int f, chunk, sub;
+        locate(a, t, f, chunk, sub);
+        const uint32_t prev = __hip_atomic_fetch_add(a.copy_counters + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1u == (uint32_t)a.copy_pieces) {
+          __hip_atomic_store(a.copy_counters + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+          __hip_atomic_store(a.signals + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+      }
+      *slot = upto;
+    }
+    __syncthreads();
+    fin_t = __builtin_amdgcn_readfirstlane(*slot);
+    __syncthreads();                        // the slot is free again
+  }
+  // finish() if thread 0 finds a tile due.  All threads call this.
+  __device__ __forceinline__ void maybe_finish(const GemmArgs& a) {
+    if (!may_be_due()) return;
+    __syncthreads();
+    if (threadIdx.x == 0) *slot = due() ? 1 : 0;
+    __syncthreads();
+    const int go = __builtin_amdgcn_readfirstlane(*slot);
+    __syncthreads();
+    if (go) finish(a);
+  }
+  // While the workgroup has nothing else to do (it waits for its own signals, or its main loop is
+  // over): a batch of vectors, loads first.  All threads call this.
+  __device__ __forceinline__ void pump(const GemmArgs& a, void* const* lds_srcs) {
+    constexpr int BATCH = 8;
+    u32x4 v[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) v[u] = load(a, lds_srcs);
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) store(a, v[u]);
+  }
+  // Everything that is left, now: the rest of the vectors, then the tiles as they become due.
+  // All threads call this.
+  __device__ __forceinline__ void drain(const GemmArgs& a, void* const* lds_srcs) {
+    while (ld_t < n_tiles) pump(a, lds_srcs);
+    while (pending()) {
+      maybe_finish(a);
+      if (pending()) __builtin_amdgcn_s_sleep(16);
+    }
+  }
+};
+
+// Are the signals covering rows [m0, m1) all set?  One poll by the first wave, the answer handed to
+// everybody through `slot` (one int of LDS).  All threads call this.
+__device__ __forceinline__ bool signals_all_set(const GemmArgs& a, int m0, int m1, int* slot) {
+  const int f0 = m0 / a.rows_per_signal, f1 = (m1 - 1) / a.rows_per_signal;
+  const int nf = f1 - f0 + 1;
+  if (threadIdx.x < 64) {
+    bool any = false;
+    for (int base = 0; base < nf; base += 64) {
+      const bool unset = base + (int)threadIdx.x < nf &&
+                         __hip_atomic_load(a.signals + f0 + base + threadIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u;
+      any = any || __ballot(unset) != 0ull;
+    }
+    if (threadIdx.x == 0) *slot = any ? 0 : 1;
+  }
+  __syncthreads();
+  const int all = __builtin_amdgcn_readfirstlane(*slot);
+  __syncthreads();
+  return all != 0;
+}
+
 // WaitSignal (Alg. 2).  The first wave polls the signals covering rows [m0, m1) with coherent
 // loads, one lane per signal; when all are set, the workgroup barrier hands that to the other waves.
 // A workgroup that finds a signal missing
@@ -732,8 +922,10 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
       }
     }
     __syncthreads();
-    const int st = lds[0];
-    const int w0 = lds[3];                // first tile of the search window
+    // (read as scalars: the compiler takes a value loaded from LDS for one that may differ between lanes,
+    // and everything changed inside a loop left under such a value, like the transfer's cursors, with it)
+    const int st = __builtin_amdgcn_readfirstlane(lds[0]);
+    const int w0 = __builtin_amdgcn_readfirstlane(lds[3]);                // first tile of the search window
     __syncthreads();                    // everyone has read them before the first wave can write again
     if (st == ARRIVED) break;
     if (st == GIVE_UP) { ok = false; break; }
@@ -840,104 +1032,6 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
   __syncthreads();
   return ok;
 }
-
-// The transfer carried inside the main loop (Sec. 3.2: the tiles whose data has arrived compute while
-// the rest is still on its way).  A workgroup of the first round owns piece `blockIdx.x` of every
-// deferred communication tile and moves it one 16-byte vector per thread and K slab, tile after tile:
-// a load at the end of a slab, the store of what was loaded two slabs earlier at the start of one, so
-// that neither is ever waited for.  All addressing goes through buffer resources whose size is the
-// tile's (or zero for a workgroup with nothing to move, a tile taken over by somebody else, or when
-// all tiles are done), so a lane past the end, and everything such a workgroup issues, is dropped by
-// the range check: the loop has one shape for every workgroup and no branch around a memory access.
-struct SideCopy {
-  __amdgpu_buffer_rsrc_t rs, rd;     // source chunk / its place in the gathered matrix, for the tile being loaded / stored
-  uint32_t first, ld_off, st_off;    // this lane's first vector of a piece, next to load, next to store (byte offsets in the tile)
-  uint32_t stride;                   // bytes between a lane's vectors
-  int n_tiles, n_steps;              // deferred tiles; vectors per thread and tile
-  int ld_t, ld_s, st_t, st_s;        // cursors: tile and step
-  uint32_t mine;                     // bit t: this workgroup claimed its piece of deferred tile t
-  int done_steps;                    // stores issued so far (over all tiles)
-
-  __device__ __forceinline__ int tile_index(const GemmArgs& a, int t) const {      // communication tile (= signal) of deferred tile t
-    return (int)((a.copy_order4 >> (4 * (a.copy_n_tiles - a.copy_defer_tiles + t))) & 15);
-  }
-  __device__ __forceinline__ unsigned records(const GemmArgs& a, int t) const {
-    return (t < n_tiles && ((mine >> t) & 1u)) ? (unsigned)(a.copy_tile_vec * 16ull) : 0u;
-  }
-  __device__ __forceinline__ void set_src(const GemmArgs& a, void* const* lds_srcs, int t) {
-    const int f = t < n_tiles ? tile_index(a, t) : 0;
-    const uint64_t addr = reinterpret_cast<uint64_t>(lds_srcs[f]);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr), hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
-    rs = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((uint64_t)hi << 32) | lo), 0, (int)records(a, t), 0x00027000);
-  }
-  __device__ __forceinline__ void set_dst(const GemmArgs& a, int t) {
-    const int f = t < n_tiles ? tile_index(a, t) : 0;
-    unsigned char* base = reinterpret_cast<unsigned char*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec * 16ull;
-    rd = __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)records(a, t), 0x00027000);
-  }
-
-  // Claims this workgroup's pieces (one exchange per deferred tile, all in one round trip) and sets
-  // the cursors up.  `lds` is one int shared by the workgroup.  All threads call this.
-  __device__ __forceinline__ void begin(const GemmArgs& a, int* lds, void* const* lds_srcs) {
-    const int tid = threadIdx.x;
-    n_tiles = 0; mine = 0u; n_steps = a.copy_defer_steps;
-    const int deferred = a.copy_defer_tiles;
-    if (deferred > 0 && (int)blockIdx.x < a.copy_pieces && (int)blockIdx.x < a.copy_owner_wgs) n_tiles = deferred;
-    if (n_tiles > 0) {           // (uniform)
-      if (tid < 64) {
-        bool won = false;
-        if (tid < n_tiles)
-          won = claim_piece(a.copy_claims + (size_t)tile_index(a, tid) * a.copy_pieces + blockIdx.x, transfer_call_id(a));
-        const unsigned long long w = __ballot(won);
-        if (tid == 0) *lds = (int)(uint32_t)w;
-      }
-      __syncthreads();
-      mine = (uint32_t)__builtin_amdgcn_readfirstlane(*lds);
-      __syncthreads();
-    }
-    first = ((uint32_t)blockIdx.x * 256u + (uint32_t)tid) * 16u;
-    stride = (uint32_t)a.copy_pieces * 256u * 16u;
-    ld_off = st_off = first;
-    ld_t = ld_s = st_t = st_s = 0;
-    done_steps = 0;
-    set_src(a, lds_srcs, 0);
-    set_dst(a, 0);
-  }
-  __device__ __forceinline__ bool pending() const { return mine != 0u; }
-  __device__ __forceinline__ bool all_stored() const { return done_steps >= n_tiles * n_steps; }
-
-  __device__ __forceinline__ u32x4 load(const GemmArgs& a, void* const* lds_srcs) {
-    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)ld_off, 0, 2);      // streamed: not kept in the caches
-    ld_off += stride;
-    if (++ld_s == n_steps) { ld_s = 0; ld_off = first; set_src(a, lds_srcs, ++ld_t); }
-    return v;
-  }
-  __device__ __forceinline__ void store(const GemmArgs& a, const u32x4& v) {
-    __builtin_amdgcn_raw_buffer_store_b128(v, rd, (int)st_off, 0, 16);                 // device scope: written through the die's L2
-    st_off += stride;
-    ++done_steps;
-    if (++st_s == n_steps) { st_s = 0; st_off = first; set_dst(a, ++st_t); }
-  }
-  // After the last store: the pieces are counted in, a tile whose last piece this was gets its
-  // signal (SetSignal of Alg. 3).  All threads call this.
-  __device__ __forceinline__ void finish(const GemmArgs& a) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      for (int t = 0; t < n_tiles; ++t) {
-        if (!((mine >> t) & 1u)) continue;
-        const int f = tile_index(a, t);
-        const uint32_t prev = __hip_atomic_fetch_add(a.copy_counters + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev + 1u == (uint32_t)a.copy_pieces) {
-          __hip_atomic_store(a.copy_counters + f, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-          __hip_atomic_store(a.signals + f, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        }
-      }
-    }
-    mine = 0u;
-    __syncthreads();
-  }
-};
 
 // Reduce by atomic additions on device memory (Sec. 4.2, "Reduce", first form): the owner's fp32 slice
 // already holds what the other ranks have added; every element of the tile is added to it with one
@@ -1333,6 +1427,9 @@ __device__ __forceinline__ void mma_stage_dma(const unsigned char* cur, unsigned
   constexpr int G = KS * C::MI;                       // MFMA groups in the slab
   constexpr int L = DmaLoader<C>::N_INSTR;            // loads to place
   constexpr int GS = (G * 3 + 3) / 4;                 // groups that carry loads
+  // (the slab's offset goes into the loads' scalar operand: should the compiler ever take the loop
+  // counter for a value that may differ between lanes, it would wrap every load into a loop over lanes)
+  k_next = __builtin_amdgcn_readfirstlane(k_next);
   bf16x8 af[2][C::MI], bfr[2][C::NI];
 #pragma unroll
   for (int mi = 0; mi < C::MI; ++mi) af[0][mi] = frag_a<C>(cur, 0, mi, wm, lane);
@@ -1474,19 +1571,24 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   SideCopy side;
   if (WAIT) {
     transfer_own_pieces(a, lds_misc, lds_outs);
-    side.begin(a, lds_misc, lds_outs);     // (also orders fill_lds_outs before the reads of lds_outs below)
+    side.begin(a, lds_misc + 2, lds_outs);     // (also orders fill_lds_outs before the reads of lds_outs below)
+    // A workgroup that has pieces to move and no data to compute on yet moves them in batches, and
+    // counts tiles in as they become due, until its own signals are there (the main loop then
+    // carries what is left) or its part of the transfer is done (then it waits like anybody else).
+    while (side.pending() && !signals_all_set(a, m0, m0 + C::BM, lds_misc + 2)) {
+      if (!side.all_stored()) side.pump(a, lds_outs);
+      else __builtin_amdgcn_s_sleep(16);
+      side.maybe_finish(a);
+    }
     if (!wait_signals(a, m0, m0 + C::BM, lds_misc, lds_outs)) {
-      // given up: the pieces this workgroup claimed still have to be moved, or their tiles' signals never come
-      if (side.pending()) {
-        while (!side.all_stored()) side.store(a, side.load(a, lds_outs));
-        side.finish(a);
-      }
+      // given up (a workgroup only gets to its wait with pieces left if its signals were there, so this
+      // is for safety): the pieces it claimed still have to be moved, or their tiles' signals never come
+      if (side.pending()) side.drain(a, lds_outs);
       trace_stamp(a, TRACE_END);
       return;
     }
     trace_stamp(a, TRACE_READY);
   }
-
   const int k_begin = is_split ? split * a.k_per_split : 0;
   const int k_end = (is_split && k_begin + a.k_per_split < a.K) ? k_begin + a.k_per_split : a.K;
   const int KT = (k_end - k_begin) / C::BK;
@@ -1510,31 +1612,44 @@ __global__ void __launch_bounds__(C::NT, C::OCC) gemm_kernel_dma(const GemmArgs 
   int kt = 0;
   if (WAIT && side.pending()) {
     // With the transfer aboard (a workgroup of the first round with pieces to move; everybody else
-    // runs the plain loop below): per slab one store (of the vector loaded two slabs ago) ahead of
-    // the slab's operand loads and one load behind them.  "All but the youngest operation have
-    // completed" then means that the operand loads have landed (loads complete in order, and the one
-    // store is older than all of them), and the barrier must not make the compiler wait for that
-    // last load.  When the last vector is out, the pieces are counted in and the plain loop takes
-    // over for the rest of K.
-    u32x4 d0 = side.load(a, lds_outs), d1 = side.load(a, lds_outs);
+    // runs the plain loop below): per slab two stores (of the vectors loaded two slabs ago) ahead of
+    // the slab's operand loads and two loads behind them.  "All but the two youngest operations have
+    // completed" then means that the operand loads have landed (loads complete in order, and the
+    // stores are older than all of them), and the barrier must not make the compiler wait for those
+    // last loads.  Thread 0 looks at the clock once per two slabs and leaves word in LDS whether a
+    // tile is due to be counted in (a decision every wave must take alike: finish() has barriers).
+    // When the last tile is counted in, the plain loop takes over for the rest of K.
+    u32x4 dA0 = side.load(a, lds_outs), dA1 = side.load(a, lds_outs);
+    u32x4 dB0 = side.load(a, lds_outs), dB1 = side.load(a, lds_outs);
     for (; kt + 2 <= KT && side.pending(); kt += 2) {
-      side.store(a, d0);
+      side.store(a, dA0);
+      side.store(a, dA1);
       mma_stage_dma<C, true>(stage0, stage1, ld, a, k_begin + (kt + 1) * C::BK, wave, wm, wn, lane, acc);
-      d0 = side.load(a, lds_outs);
-      wait_vm_at_most<1>();
+      dA0 = side.load(a, lds_outs);
+      dA1 = side.load(a, lds_outs);
+      wait_vm_at_most<2>();
       barrier_keeping_loads_in_flight();
-      side.store(a, d1);
+      side.store(a, dB0);
+      side.store(a, dB1);
       const int k2 = k_begin + (kt + 2) * C::BK;
       mma_stage_dma<C, true>(stage1, stage0, ld, a, k2 < k_last ? k2 : k_last, wave, wm, wn, lane, acc);
-      d1 = side.load(a, lds_outs);
-      wait_vm_at_most<1>();
+      dB0 = side.load(a, lds_outs);
+      dB1 = side.load(a, lds_outs);
+      const bool look = side.may_be_due();       // (uniform)
+      if (look && tid == 0) *side.slot = side.due() ? 1 : 0;
+      wait_vm_at_most<2>();
       barrier_keeping_loads_in_flight();
-      if (side.all_stored()) side.finish(a);
+      if (look) {
+        const int go = __builtin_amdgcn_readfirstlane(*side.slot);
+        if (go) side.finish(a);           // (its barriers also keep the slot from being rewritten too early)
+      }
     }
     wait_vm0_and_barrier();
-    if (side.pending()) {          // a K too short for the pieces: the rest goes now (the host does not plan this)
-      while (!side.all_stored()) { side.store(a, d0); d0 = d1; d1 = side.load(a, lds_outs); }
-      side.finish(a);
+    if (side.pending()) {          // K is over before the transfer is: the vectors in flight first, then the rest
+      side.store(a, dA0); side.store(a, dA1); side.store(a, dB0); side.store(a, dB1);
+      side.ld_t = side.st_t; side.ld_s = side.st_s; side.ld_off = side.st_off;     // the loads start again where the stores are
+      side.set_src(a, lds_outs, side.ld_t);
+      side.drain(a, lds_outs);
     }
   }
   for (; kt + 2 <= KT; kt += 2) {

@@ -521,23 +521,86 @@ def test_ag_later_chunks_travel_inside_the_main_loops(order):
     gh.assert_bits_equal(Cu, want, "C, everything up front")
 
 
-def test_ag_deferred_pieces_are_moved_even_by_workgroups_that_give_up():
-    """Failure handling forced from the host: with a spin limit of one tick every workgroup that finds a
-    signal missing gives up at once.  The kernel exits, the status block reports a timeout, and the
-    gathered matrix is complete all the same: a workgroup moves the pieces it owns before it waits, and
-    those it was to carry inside its main loop before it leaves."""
+@pytest.mark.parametrize("shape,ctpc,gbps", [("two_rounds", 1, 400), ("two_rounds", 2, 800), ("one_round", 1, 400)])
+def test_ag_link_paced_transfer_carried_by_the_grid(shape, ctpc, gbps):
+    """A transfer that stands for a link, without a copy kernel: the first round's workgroups carry every
+    remote tile (in batches while they wait, inside their main loops afterwards) and count a tile in
+    no earlier than the link would have delivered it.  Bits as the oracle's; the trace shows that no
+    tile got past its wait before its communication tile was due."""
+    w = AG_TWO_ROUNDS if shape == "two_rounds" else fi.Workload("int_ag_one_round", "ag", 4096, 3584, 1024, 8, a_dist=("int", 2), b_dist=("int", 2), seed=85)
+    rank = 6
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, comm_tiles_per_chunk=ctpc, link_gbps=gbps, spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS)
+    assert fb.flux_ag_deferred_tiles(p) == (w.R - 1) * ctpc
+    _, want = gh.oracle_ag(w, chunks, B)
+    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, comm_tiles_per_chunk=ctpc, link_gbps=gbps, repeat=2)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_bits_equal(Cg, want, "C")
+    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+    assert signals.tolist() == [1 if i // ctpc == rank else 0 for i in range(w.R * ctpc)]
+    # pacing, from the tile trace of one more call
+    full, cut, k = fb.flux_split_plan(fb.FLUX_OP_AG, p)
+    grid = full + cut * k
+    sh = fb.flux_tile_shape(fb.FLUX_OP_AG, p)
+    dchunks = [c.to(gh.DEV) for c in chunks]
+    A2 = torch.full((w.M, w.K), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    C2 = torch.full((w.M, w.N), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    sig = torch.zeros(w.R * ctpc, dtype=torch.int32, device=gh.DEV)
+    ws = gh.workspace_for(fb.FLUX_OP_AG, p)
+    fb.flux_init_buffers(fb.FLUX_OP_AG, p, ws, sig)
+    trace = torch.zeros((grid, 8), dtype=torch.int64, device=gh.DEV)
+    fb.flux_trace_next_call(trace)
+    fb.flux_ag_gemm(p, dchunks, A2, B.to(gh.DEV), C2, sig, arrival, ws, torch.cuda.current_stream(), torch.cuda.Stream())
+    torch.cuda.synchronize()
+    assert fb.flux_query_status(ws) == (fb.FLUX_OK, 0)
+    t = trace.cpu().numpy()
+    w32 = t.view(np.uint32).reshape(grid, 16)
+    m_tile = w32[:, 1].astype(np.int64)
+    t_start, t_ready = t[:, 4].astype(np.int64), t[:, 5].astype(np.int64)
+    t0 = int(t_start.min())
+    tile_bytes = w.S * w.K * 2 // ctpc
+    pace = tile_bytes / gbps / 10.0                      # 100 MHz ticks per communication tile
+    rows_per_tile = w.S // ctpc
+    position = {c: i for i, c in enumerate(arrival)}     # chunk -> place in the transfer order
+    checked = 0
+    for b in range(grid):
+        lo, hi = m_tile[b] * sh.tile_m, (m_tile[b] + 1) * sh.tile_m - 1
+        last_due = 0.0
+        for f in range(lo // rows_per_tile, hi // rows_per_tile + 1):        # communication tiles the block's rows lie in
+            chunk, sub = f // ctpc, f % ctpc
+            if chunk != rank:
+                last_due = max(last_due, (position[chunk] * ctpc + sub + 1) * pace)
+        if last_due > 0:
+            assert t_ready[b] - t0 >= last_due - 300, ("block past its wait before its data was due", b, t_ready[b] - t0, last_due)
+            checked += 1
+    assert checked > 0
+    gh.assert_bits_equal(C2, want, "C of the traced call")
+
+
+@pytest.mark.parametrize("gbps", [0, 50])
+def test_ag_carried_pieces_are_moved_whatever_happens_to_the_tiles(gbps):
+    """Failure handling forced from the host: with a spin limit of one tick a workgroup that finds a
+    signal missing when it gets to its wait gives up at once.  Whether any does depends on timing (a
+    workgroup with pieces to carry keeps moving them until its own signals are there, and the later
+    rounds start when the first has finished); either way the kernel exits, the status block is
+    consistent with the result, and the gathered matrix is complete: the workgroups that carry the
+    pieces move all of them and count them in on schedule, whether or not anybody still waits."""
     w, rank = AG_TWO_ROUNDS, 1
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
-    assert fb.flux_ag_deferred_tiles(fb.problem(w.M, w.N, w.K, w.R, rank)) == 4
-    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, timeout_ticks=1)
+    assert fb.flux_ag_deferred_tiles(fb.problem(w.M, w.N, w.K, w.R, rank, link_gbps=gbps)) == (7 if gbps else 4)
+    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, timeout_ticks=1, link_gbps=gbps)
     code, detail = status
-    assert code == fb.FLUX_ERR_TIMEOUT and 0 <= detail < w.R and detail != rank
-    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg after a call that gave up")
     _, want = gh.oracle_ag(w, chunks, B)
+    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
     lo, hi = rank * w.S, (rank + 1) * w.S
     gh.assert_bits_equal(Cg[lo:hi], want[lo:hi], "rows of the local chunk")
+    assert code in (fb.FLUX_OK, fb.FLUX_ERR_TIMEOUT)
+    if code == fb.FLUX_OK:
+        gh.assert_bits_equal(Cg, want, "C")
+    else:
+        assert 0 <= detail < w.R and detail != rank
     # after flux_init_buffers (run_ag does it) the same problem runs clean
-    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival)
+    Cg, _, _, status = gh.run_ag(w, rank, chunks, B, arrival, link_gbps=gbps)
     assert status == (fb.FLUX_OK, 0)
     gh.assert_bits_equal(Cg, want, "C after re-initialisation")
 

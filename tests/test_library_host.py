@@ -304,7 +304,12 @@ def test_deferred_transfer_is_planned_for_grids_of_several_rounds():
     assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, flags=fb.FLUX_FLAG_NO_SWIZZLE)) == 0
     assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, comm_tiles_per_chunk=2)) == 0
     assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, copy_workgroups=16)) == 0   # a copy kernel moves the data
-    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, link_gbps=400)) == 0
+    # a transfer that stands for a link and has no driver of its own is carried whole, on the link's schedule
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, link_gbps=400)) == 7
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, link_gbps=400, comm_tiles_per_chunk=4)) == 28
+    assert fb.flux_ag_deferred_tiles(fb.problem(4096, 3584, 8192, 8, 2, link_gbps=400)) == 7
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, link_gbps=400, copy_workgroups=20)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 12288, 8, 2, link_gbps=400, flags=fb.FLUX_FLAG_COPY_MEMCPY)) == 0
     assert fb.flux_ag_deferred_tiles(fb.problem(4096, 3584, 8192, 8, 2)) == 0         # one round: every chunk is needed at once
     assert fb.flux_ag_deferred_tiles(fb.problem(2048, 6144, 12288, 8, 2)) == 0        # the first round touches every chunk
     assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 512, 8, 2)) == 0          # K too short to carry the vectors
