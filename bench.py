@@ -276,7 +276,7 @@ def main() -> int:
             more["ms_fused_graph_replay"] = round(t_graph, 4)
         if t_atomic is not None:
             more["ms_atomic_reduce_f32"] = round(t_atomic, 4)
-        if hasattr(op, "copy_upfront") and op.p.flags == 0 and fb.flux_ag_deferred_tiles(op.p) > 0:
+        if hasattr(op, "copy_upfront") and op.p.flags == 0 and op.p.link_gbps == 0 and fb.flux_ag_deferred_tiles(op.p) > 0:
             more["chunks_moved_inside_main_loops"] = fb.flux_ag_deferred_tiles(op.p)
             more["ms_fused_all_chunks_up_front"] = round(time_calls(op.copy_upfront, reps, warm), 4)
         if hasattr(op, "one_workgroup_per_tile") and fb.flux_rs_resident_grid(op.p)[0] > 0:
@@ -496,16 +496,20 @@ def main() -> int:
             del op
             torch.cuda.empty_cache()
         extra["op_level_sweep"] = sweep
-        # Secondary, labelled: the copy driver paced to an inbound link of 7 x 153 GB/s (what one
-        # rank of an 8-GPU xGMI mesh receives), so that communication is a paper-like fraction
-        # of the GEMM time; communication tile = chunk / ctpc (Sec. 4.3), swizzle on and off.
+        # Secondary, labelled: the transfer paced to an inbound link of 7 x 153 GB/s (what one rank
+        # of an 8-GPU xGMI mesh receives), so that communication is a paper-like fraction of the GEMM
+        # time; communication tile = chunk / ctpc (Sec. 4.3), swizzle on and off.  Without a driver
+        # (the grid carries the tiles itself and counts them in on the link's schedule), and for
+        # comparison with the paced copy kernel as driver (54 workgroups move 1071 GB/s).
         link = {}
-        for name, variants in (("c4_ag", ((1, 0), (2, 0), (4, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE))), ("c2_ag", ((1, 0), (2, 0)))):
-            for ctpc, flags in variants:
-                op = AG(W[name], 2, link_gbps=1071, comm_tiles_per_chunk=ctpc, flags=flags)
-                key = f"{name}_ctpc{ctpc}" + ("_noswizzle" if flags else "")
+        for name, variants in (("c4_ag", ((1, 0, 0), (2, 0, 0), (4, 0, 0), (2, fb.FLUX_FLAG_NO_SWIZZLE, 0), (1, 0, 54))),
+                               ("c2_ag", ((1, 0, 0), (2, 0, 0)))):
+            for ctpc, flags, driver in variants:
+                op = AG(W[name], 2, link_gbps=1071, comm_tiles_per_chunk=ctpc, flags=flags, copy_workgroups=driver)
+                key = f"{name}_ctpc{ctpc}" + ("_noswizzle" if flags else "") + (f"_driver{driver}" if driver else "")
                 say(f"extra: link-paced {key}")
                 link[key] = overlap_block(op)
+                link[key]["tiles_carried_by_the_grid"] = fb.flux_ag_deferred_tiles(op.p)
                 del op
                 torch.cuda.empty_cache()
         extra["link_paced_1071GBps"] = link

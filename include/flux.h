@@ -119,9 +119,10 @@ typedef struct flux_problem {
                                copy kernel at all unless link_gbps is set, see flux_ag_gemm).  The
                                fused call uses at most 256: a communication tile moves in one
                                piece per workgroup.                                                */
-  int32_t link_gbps;        /* AG copy kernel: 0 = copy at memory speed; else emulate an inbound
-                               link of that many GB/s: communication tile i is not signalled
-                               before (i+1)*tile_bytes/link_gbps after the driver started       */
+  int32_t link_gbps;        /* AG transfer: 0 = at memory speed; else it stands for an inbound link
+                               of that many GB/s: communication tile i of the transfer order is
+                               not signalled before (i+1)*tile_bytes/link_gbps after the
+                               transfer started (its data may move earlier)                      */
   int32_t reserved;         /* must be 0                                                          */
   uint64_t spin_timeout_ticks;  /* AG: bound on one signal wait, in 100 MHz wall-clock ticks;
                                    0 = library default (10 s).  The paper spins without bound.   */
@@ -163,11 +164,23 @@ int flux_gemm_rs_static(const flux_problem_t* p, const void* A, const void* B,
  * setting each tile's signal when it is complete) depends on the problem:
  *   - link_gbps == 0, copy_workgroups == 0, no FLUX_FLAG_COPY_MEMCPY (the default): no copy kernel
  *     is launched and copy_stream stays unused.  The first workgroups of the GEMM grid (as many as
- *     run at once) share the pieces of all tiles out among themselves by index and move them
- *     before they look at their own signals.  A GEMM workgroup takes the whole register file of
- *     its compute unit, so a separate driver cannot run beside it: it would hold units the grid
- *     wants, and a waiting workgroup holds its unit anyway.
- *   - copy_workgroups > 0 or link_gbps > 0: the driver of Alg. 3 is a kernel on copy_stream.  A
+ *     run at once) share the pieces of the tiles out among themselves by index and move them
+ *     before they look at their own signals; in a grid of several rounds they move only the chunks
+ *     the first round reads that way and carry the others inside their main loops (see
+ *     flux_ag_deferred_tiles, FLUX_FLAG_AG_COPY_UPFRONT).  A GEMM workgroup takes the whole
+ *     register file of its compute unit, so a separate driver cannot run beside it: it would hold
+ *     units the grid wants, and a waiting workgroup holds its unit anyway.
+ *   - link_gbps > 0, copy_workgroups == 0, no FLUX_FLAG_COPY_MEMCPY: a transfer on a link's schedule,
+ *     still without a copy kernel.  Workgroup w of the first round carries piece w of every remote
+ *     tile: in batches while it waits for its own signals, two 16-byte vectors per thread and K slab
+ *     inside its main loop, and it counts a tile in (the last piece sets the signal) no earlier
+ *     than the link would have delivered it.  A driver that stands for a link would hold its
+ *     compute units for as long as the transfer lasts, which no link does.  (Where the kernel
+ *     cannot carry - tile configurations other than 256x256 two-stage, ragged shapes, more than 32
+ *     remote tiles - this falls back to the paced copy kernel below.)  The same holds for stream
+ *     capture as for the default form.
+ *   - copy_workgroups > 0 (or link_gbps > 0 where the grid cannot carry): the driver of Alg. 3 is a
+ *     kernel on copy_stream, paced if link_gbps > 0.  A
  *     GEMM workgroup that has to wait for a tile moves pieces of that tile which no one has started
  *     on (pieces are claimed, so nothing is moved twice); the call therefore also completes when
  *     the GEMM grid takes every compute unit before the driver got one.  A paced driver
@@ -363,10 +376,11 @@ int flux_split_plan(int op, const flux_problem_t* p, int32_t* full_tiles, int32_
 int32_t flux_rs_resident_grid(const flux_problem_t* p, uint32_t* delay_ticks);
 
 /*
- * How many of the R-1 remote chunks flux_ag_gemm (default form: no copy kernel) would move inside the
- * main loops of its first round of workgroups instead of before the signal wait (Sec. 3.2: tiles whose
- * data has arrived compute while the rest is on its way): the last that many chunks of the arrival
- * order.  0: everything is moved up front.  Host function.
+ * How many of the (R-1) * comm_tiles_per_chunk remote communication tiles flux_ag_gemm (forms without a
+ * copy kernel) has its first round of workgroups carry themselves instead of moving them before the
+ * signal wait (Sec. 3.2: tiles whose data has arrived compute while the rest is on its way): the last
+ * that many tiles of the transfer order; all of them when link_gbps > 0.  0: everything is moved up
+ * front, or a copy kernel moves it.  Host function.
  */
 int32_t flux_ag_deferred_tiles(const flux_problem_t* p);
 
