@@ -480,7 +480,7 @@ def main() -> int:
                 op.ws = torch.zeros(n // 4 + 1, dtype=torch.int32, device=dev) if n else None
                 t, ms_best, ms_def = fb.flux_autotune_rs(op.p, op.A, op.B, op.peers, op.outs, op.ws, compute, reps=5)
             tuned[name] = {"tile_config": t.tile_config, "split_k": t.split_k, "comm_tiles_per_chunk": t.comm_tiles_per_chunk,
-                           "ms_tuned": round(ms_best, 4), "ms_library_pick": round(ms_def, 4)}
+                           "flags": int(t.flags), "ms_tuned": round(ms_best, 4), "ms_library_pick": round(ms_def, 4)}
             del op
             torch.cuda.empty_cache()
         extra["autotune"] = tuned

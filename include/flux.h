@@ -336,9 +336,11 @@ size_t flux_chunked_workspace_bytes(int op, const flux_problem_t* p);
  * on the caller's own buffers for every tile configuration that accepts the shape, for few-row
  * shapes (M <= 256) also with half and twice the library's number of K parts, and, for the
  * AllGather, for communication tiles of the chunk height halved down to the GEMM tile height (at
- * most 8 per chunk), against what the library picks by itself, and writes the fastest problem
- * description to *tuned (a copy of *p with tile_config, split_k and comm_tiles_per_chunk filled in; the
- * library's own pick wins unless a candidate is more than 2 % faster).  *ms_best / *ms_default
+ * most 8 per chunk), and with the other form of prologue or epilogue where the library would pick
+ * one by rule (FLUX_FLAG_AG_COPY_UPFRONT, FLUX_FLAG_NO_RESIDENT_GRID), against what the library picks
+ * by itself, and writes the fastest problem description to *tuned (a copy of *p with tile_config,
+ * split_k, comm_tiles_per_chunk and such a flag filled in; the library's own pick wins unless a
+ * candidate is more than 2 % faster).  *ms_best / *ms_default
  * (either may be NULL) receive the median time per call of the winner and of the library's pick.
  * Buffers as for flux_gemm_rs / flux_ag_gemm; outputs are overwritten with the (same) result.  The
  * workspace must hold flux_autotune_workspace_bytes(op, p) bytes (candidates that need more than

@@ -1413,7 +1413,7 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
 // ------------------------------------------------------------------------------------------
 namespace {
 
-struct Candidate { int32_t tile_config, ctpc, split_k; };
+struct Candidate { int32_t tile_config, ctpc, split_k; uint32_t flags = 0; };   // flags: added to the caller's
 
 // Every tile configuration that accepts the shape; for AllGather each with the communication tile
 // halved from the chunk down to the GEMM tile height (Sec. 4.3), at most 8 tiles per chunk.
@@ -1428,6 +1428,11 @@ std::vector<Candidate> tune_candidates(int op, const flux_problem_t* p) {
     Plan pl;
     if (make_plan(op, &q, &pl) != FLUX_OK) continue;
     out.push_back({cfg, 1, 0});
+    // the forms of prologue and epilogue the plan would pick by rule are knobs too (Sec. 4.4): all chunks
+    // moved before the first main loop instead of carried inside it; one workgroup per tile instead of
+    // a resident grid
+    if (op == FLUX_OP_AG && pl.defer_tiles > 0 && pl.pace_ticks == 0) out.push_back({cfg, 1, 0, FLUX_FLAG_AG_COPY_UPFRONT});
+    if (op == FLUX_OP_RS && pl.resident) out.push_back({cfg, 1, 0, FLUX_FLAG_NO_RESIDENT_GRID});
     // few rows: how K is cut decides how well the grid fills the chip and what the hand-over costs;
     // half and twice the library's number of parts are candidates too
     if (p->M <= 256 && pl.full_tiles == 0) {
@@ -1514,6 +1519,7 @@ int tune(int op, const flux_problem_t* p, const TuneBuffers& b, int reps, flux_p
       q.tile_config = c.tile_config;
       q.comm_tiles_per_chunk = c.ctpc;
       q.split_k = c.split_k;
+      q.flags |= c.flags;
       if (flux_workspace_bytes(op, &q) > b.ws_bytes) continue;     // the caller's workspace does not hold this one
       float t = 0.f;
       const int sc = tune_time(op, &q, b, reps, e0, e1, &t);
@@ -1528,7 +1534,7 @@ int tune(int op, const flux_problem_t* p, const TuneBuffers& b, int reps, flux_p
     st = tune_time(op, &base, b, reps, e0, e1, &t_again);
     if (st == FLUX_OK && t_again < t_default) {
       t_default = t_again;
-      if (best.tile_config == 0 && best.comm_tiles_per_chunk == 0 && best.split_k == 0) t_best = t_again;
+      if (best.tile_config == 0 && best.comm_tiles_per_chunk == 0 && best.split_k == 0 && best.flags == base.flags) t_best = t_again;
       else if (t_best >= t_default * 0.98f) { best = base; t_best = t_default; }
     }
   }
