@@ -521,6 +521,26 @@ def test_ag_later_chunks_travel_inside_the_main_loops(order):
     gh.assert_bits_equal(Cu, want, "C, everything up front")
 
 
+@pytest.mark.parametrize("R,gbps", [(2, 0), (16, 0), (16, 800), (4, 0)])
+def test_ag_carried_transfer_with_other_rank_counts(R, gbps):
+    """Two ranks: the first round is all local tiles and the one remote chunk travels inside its main
+    loops, nothing is moved up front.  Sixteen ranks: half as many pieces per chunk as the first round
+    has workgroups, so half of them carry nothing."""
+    w = fi.Workload(f"int_ag_two_rounds_r{R}", "ag", 8192, 4608, 2048, R, a_dist=("int", 2), b_dist=("int", 2), seed=86 + R)
+    rank = R - 1
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, link_gbps=gbps)
+    deferred = fb.flux_ag_deferred_tiles(p)
+    _say("ag carried transfer, ranks", R, "link", gbps, "tiles carried", deferred)
+    assert deferred == (R - 1 if gbps else {2: 1, 4: 2, 16: 8}[R])
+    _, want = gh.oracle_ag(w, chunks, B)
+    Cg, A_agg, signals, status = gh.run_ag(w, rank, chunks, B, arrival, link_gbps=gbps, repeat=2)
+    assert status == (fb.FLUX_OK, 0)
+    gh.assert_bits_equal(Cg, want, "C")
+    gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+    assert signals.tolist() == [1 if r == rank else 0 for r in range(w.R)]
+
+
 @pytest.mark.parametrize("shape,ctpc,gbps", [("two_rounds", 1, 400), ("two_rounds", 2, 800), ("one_round", 1, 400)])
 def test_ag_link_paced_transfer_carried_by_the_grid(shape, ctpc, gbps):
     """A transfer that stands for a link, without a copy kernel: the first round's workgroups carry every
