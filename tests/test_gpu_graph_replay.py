@@ -18,13 +18,17 @@ def _say(*a):
     print(*a, flush=True)
 
 
-@pytest.mark.parametrize("shape", [dict(M=64, N=1024, K=2048), dict(M=1024, N=1024, K=512), dict(M=2048, N=2560, K=256)])
-def test_ag_gemm_replays_from_a_graph(shape):
+@pytest.mark.parametrize("shape,gbps", [(dict(M=64, N=1024, K=2048), 0), (dict(M=1024, N=1024, K=512), 0), (dict(M=2048, N=2560, K=256), 0),
+                                        (dict(M=8192, N=4608, K=2048), 0),        # two rounds: four chunks travel inside the main loops
+                                        (dict(M=8192, N=4608, K=2048), 800)])     # ... all seven, on a link's schedule
+def test_ag_gemm_replays_from_a_graph(shape, gbps):
     w = fi.scaled(fi.WORKLOADS["c2_ag"], **shape)
     rank = 5
     chunks, B, arrival = fi.make_ag_inputs(w, rank)
     C64, _ = gh.oracle_ag(w, chunks, B)
-    p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS, link_gbps=gbps)
+    if shape["M"] == 8192:
+        assert fb.flux_ag_deferred_tiles(p) == (7 if gbps else 4)
     dB = B.to(DEV)
     dchunks = [c.to(DEV) for c in chunks]
     A_agg = torch.full((w.M, w.K), float("nan"), dtype=torch.bfloat16, device=DEV)
@@ -70,13 +74,16 @@ def test_ag_gemm_replays_from_a_graph(shape):
             assert torch.equal(Cout.view(torch.int16), eager.view(torch.int16))
 
 
-@pytest.mark.parametrize("shape,split", [(dict(M=64, N=2048, K=1024), 4), (dict(M=1024, N=1024, K=512), 0)])
+@pytest.mark.parametrize("shape,split", [(dict(M=64, N=2048, K=1024), 4), (dict(M=1024, N=1024, K=512), 0),
+                                         (dict(M=8192, N=8192, K=256), 0)])       # four rounds of short tiles: the resident grid
 def test_gemm_rs_replays_from_a_graph(shape, split):
     w = fi.scaled(fi.WORKLOADS["c3_rs"], **shape)
     rank = 1
     A, B, peers = fi.make_rs_inputs(w, rank)
     want64, _ = gh.oracle_rs(w, rank, A, B, peers)
     p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype, split_k=split)
+    if shape["M"] == 8192:
+        assert fb.flux_rs_resident_grid(p)[0] == 256
     dA, dB = A.to(DEV), B.to(DEV)
     dpeers = [None if t is None else t.to(DEV) for t in peers]
     outs = [torch.full((w.S, w.N), float("nan"), dtype=torch.bfloat16, device=DEV) for _ in range(w.R)]
