@@ -557,10 +557,15 @@ __device__ __forceinline__ void finish_pieces(uint32_t* counter, uint32_t* signa
   __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t prev = __hip_atomic_fetch_add(counter, (uint32_t)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (prev + (uint32_t)n == (uint32_t)pieces) {
-      __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+    if (n == pieces) {
+      // the whole tile was this workgroup's (a small transfer: one piece per tile): nobody else counts, no round trip
       __hip_atomic_store(signal, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    } else {
+      const uint32_t prev = __hip_atomic_fetch_add(counter, (uint32_t)n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (prev + (uint32_t)n == (uint32_t)pieces) {
+        __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+        __hip_atomic_store(signal, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
     }
   }
   // Callers loop: without a barrier here, this one-thread block and the one-thread block that
