@@ -8,7 +8,7 @@ followed by the fused GEMM-ReduceScatter of the attention output projection ([81
 [1536,12288], 7 peer partials added in the epilogue, 8 row slices written).  Inputs are seeded
 synthetic tensors, already resident in HBM when the timed region starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the README names the fields).
 """
 from __future__ import annotations
 

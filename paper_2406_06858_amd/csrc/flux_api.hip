@@ -185,7 +185,7 @@ struct ReadyReduceArgs {
 // workgroup sums the producers' staged rows of that tile in rank order, fp32, and writes the slice.
 // Staged data is read at device scope (past this die's L2): the producers wrote it through.
 __global__ void __launch_bounds__(256) rs_ready_reduce_kernel(const ReadyReduceArgs a) {
-  __shared__ int verdict;
+  __shared__ int outcome;
   const int n_tiles = a.n_mt * a.tiles_n;
   const int elem = a.partial_f32 ? 4 : 2;
   constexpr int SC1 = 16;                                     // cache-policy bit: device scope
@@ -203,10 +203,10 @@ __global__ void __launch_bounds__(256) rs_ready_reduce_kernel(const ReadyReduceA
         }
         __builtin_amdgcn_s_sleep(32);
       }
-      verdict = ok;
+      outcome = ok;
     }
     __syncthreads();
-    const int ok = verdict;
+    const int ok = outcome;
     __syncthreads();                    // everyone has read it before thread 0 writes the next one
     if (!ok) continue;                  // the tile stays unwritten; the status block says which
     // rows of the tile that belong to this slice, as local rows
