@@ -21,8 +21,10 @@
  * plus the non-overlapped baseline used for the overlap-efficiency metric (Sec. 2.3, Eq. 1-2).
  *
  * Conventions
- *   - All matrices are row-major and densely packed: A [M,K], B [K,N], partials / C [M,N],
- *     slices [M/R,N].  A and B are bf16; partials and outputs are bf16 or f32 (flux_dtype_t).
+ *   - All matrices are row-major: A [M,K], B [K,N], partials / C [M,N], slices [M/R,N]; densely
+ *     packed unless the problem gives a row pitch (lda / ldb / ldc of flux_problem_t, which also says
+ *     which matrices each applies to).  A and B are bf16; partials and outputs are bf16 or f32
+ *     (flux_dtype_t).
  *   - M % R == 0; N % 8 == 0; K % 8 == 0; every base pointer 16-byte aligned; R <= FLUX_MAX_RANKS.
  *   - Every pointer marked "device" must be device memory of the current HIP device, allocated
  *     and freed by the caller.  The library never allocates or frees device memory.  Pointer
@@ -126,6 +128,17 @@ typedef struct flux_problem {
   int32_t reserved;         /* must be 0                                                          */
   uint64_t spin_timeout_ticks;  /* AG: bound on one signal wait, in 100 MHz wall-clock ticks;
                                    0 = library default (10 s).  The paper spins without bound.   */
+  int64_t lda, ldb, ldc;    /* row pitches in elements, 0 = packed (K, N, N).  Multiples of 8, at
+                               least a row long, below FLUX_MAX_N (ldc), the last element's index
+                               below 2^31.
+                               lda: A (flux_gemm_rs, the references) and the gathered matrix A_agg
+                                    (flux_ag_gemm); the chunk sources A_chunks[r] are packed [M/R,K].
+                               ldb: B.
+                               ldc: C, every out slice, and the staged slices that
+                                    FLUX_FLAG_RS_WRITE_ONLY / flux_gemm_rs_notify write and
+                                    flux_rs_reduce_slice / flux_rs_reduce_slice_ready read.
+                               Peer partials are packed [M,N].  What lies between the end of a
+                               row and the next row is neither read nor written.                  */
 } flux_problem_t;
 
 /*
@@ -197,9 +210,9 @@ int flux_gemm_rs_static(const flux_problem_t* p, const void* A, const void* B,
  * driver take a fresh claim id from the host on every call: under stream capture they return
  * FLUX_ERR_UNSUPPORTED.
  *   A_chunks        host array [R] of device pointers, chunk r = [M/R,K] bf16 ("A_list").
- *   A_agg           device [M,K] bf16, written by the call.  If A_chunks[rank] already points
- *                   at A_agg + rank*(M/R)*K the local chunk is not copied.  16-byte alignment is
- *                   required; with 128-byte alignment and K a multiple of 64 no cache line holds
+ *   A_agg           device [M,K] bf16 (row pitch lda), written by the call.  If A_chunks[rank] already points
+ *                   at A_agg + rank*(M/R)*lda the local chunk is not copied.  16-byte alignment is
+ *                   required; with 128-byte alignment and a row pitch that is a multiple of 64 no cache line holds
  *                   rows of two communication tiles, and a workgroup leaves its signal wait without
  *                   invalidating its die's L2 (one to two microseconds per workgroup otherwise).
  *   B, C            device, [K,N] bf16 and [M,N] out_dtype.

@@ -56,7 +56,6 @@ struct CopyArgs {
   int32_t order[FLUX_MAX_RANKS];      // chunks to move, in transfer order
   int32_t n_order;
   int32_t tiles_per_chunk;            // communication tiles per chunk
-  unsigned long long chunk_vec;       // 16-byte vectors per chunk
   unsigned long long tile_vec;        // 16-byte vectors per communication tile
   uint32_t* signals;                  // may be null (baseline copy: nothing to claim, count or signal)
   uint32_t* counters;
@@ -65,6 +64,8 @@ struct CopyArgs {
   uint32_t call_id;
   uint32_t* started;                  // may be null
   unsigned long long pace_ticks;      // 100 MHz ticks per communication tile, 0 = unpaced
+  AggPitch pitch;                     // rows of the gathered matrix: vectors in one, vectors from one to the next
+  int32_t rows_per_tile;
 };
 
 // Copy driver as one kernel: all workgroups move communication tile after communication tile
@@ -88,7 +89,7 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
     const int t = idx % c.tiles_per_chunk;
     const int flag = chunk * c.tiles_per_chunk + t;
     const uint4* src = c.src[chunk] + (unsigned long long)t * c.tile_vec;
-    uint4* dst = c.dst + (unsigned long long)chunk * c.chunk_vec + (unsigned long long)t * c.tile_vec;
+    uint4* dst = c.dst + (unsigned long long)flag * c.rows_per_tile * c.pitch.pitch_v;
     int moved = 0;
     for (int piece = (int)blockIdx.x; piece < c.pieces; piece += (int)gridDim.x) {
       if (c.signals != nullptr) {
@@ -98,7 +99,7 @@ __global__ void __launch_bounds__(256) ag_copy_kernel(const CopyArgs c) {
         __syncthreads();
         if (!take) continue;
       }
-      copy_piece(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x);
+      copy_piece(src, dst, c.tile_vec, piece, c.pieces, (int)threadIdx.x, c.pitch);
       ++moved;
     }
     if (moved == 0) continue;
@@ -117,6 +118,7 @@ struct ReduceArgs {
   int32_t M, N, R, rank, S, partial_f32, out_f32;
   int32_t c_f32;                      // dtype of C
   int32_t row0, rows;                 // rows [row0, row0 + rows) of the [M,N] matrices
+  int32_t ld_c, ld_peer, ld_out;      // row pitches in elements
 };
 
 // Baseline reduce-scatter: out[r] = C + sum of peer partials, 8 columns per thread.
@@ -126,7 +128,7 @@ __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
   for (long long v = (long long)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (long long)gridDim.x * blockDim.x) {
     const int gm = a.row0 + (int)(v / nv_row);
     const int gn = (int)(v % nv_row) * 8;
-    const size_t off = (size_t)gm * a.N + gn;
+    const size_t off = (size_t)gm * a.ld_c + gn, off_peer = (size_t)gm * a.ld_peer + gn;
     float x[8];
     if (a.c_f32) {
       const float* p = static_cast<const float*>(a.C) + off;
@@ -141,18 +143,18 @@ __global__ void __launch_bounds__(256) rs_reduce_kernel(const ReduceArgs a) {
     for (int j = 0; j < a.R; ++j) {
       if (j == a.rank) continue;
       if (a.partial_f32) {
-        const float* p = static_cast<const float*>(a.peers[j]) + off;
+        const float* p = static_cast<const float*>(a.peers[j]) + off_peer;
         const uint4 u = ld_stream16(p), w = ld_stream16(p + 4);
         x[0] += __uint_as_float(u.x); x[1] += __uint_as_float(u.y); x[2] += __uint_as_float(u.z); x[3] += __uint_as_float(u.w);
         x[4] += __uint_as_float(w.x); x[5] += __uint_as_float(w.y); x[6] += __uint_as_float(w.z); x[7] += __uint_as_float(w.w);
       } else {
-        const uint4 w = ld_stream16(static_cast<const __bf16*>(a.peers[j]) + off);
+        const uint4 w = ld_stream16(static_cast<const __bf16*>(a.peers[j]) + off_peer);
         x[0] += bf16_lo(w.x); x[1] += bf16_hi(w.x); x[2] += bf16_lo(w.y); x[3] += bf16_hi(w.y);
         x[4] += bf16_lo(w.z); x[5] += bf16_hi(w.z); x[6] += bf16_lo(w.w); x[7] += bf16_hi(w.w);
       }
     }
     const int r = gm / a.S;
-    const size_t o = (size_t)(gm - r * a.S) * a.N + gn;
+    const size_t o = (size_t)(gm - r * a.S) * a.ld_out + gn;
     if (a.out_f32) {
       float* q = static_cast<float*>(a.outs[r]) + o;
       st_stream16(q, make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])));
@@ -173,6 +175,7 @@ struct ReadyReduceArgs {
   uint32_t* status;                     // status block (code, detail)
   unsigned long long timeout_ticks;
   int32_t S, N, R, partial_f32, out_f32;
+  int32_t ld;                           // row pitch of the staged matrices and of out, in elements
   int32_t bm, bn, tiles_n;              // the producers' tile shape
   int32_t row0;                         // first global row of the slice
   int32_t mt_lo, n_mt;                  // m-tiles that overlap the slice
@@ -216,12 +219,12 @@ __global__ void __launch_bounds__(256) rs_ready_reduce_kernel(const ReadyReduceA
     const int vec_per_row = (c1 - c0) / 8;
     const int nvec = (g1 - g0) * vec_per_row;
     // the staged matrices through buffer resources based at the first row of the tile within the
-    // slice (uniform; a lane's offset from there stays below 256 rows * N * 4 bytes < 2^31)
-    const size_t tile_base = (size_t)(g0 - a.row0) * a.N;
+    // slice (uniform; a lane's offset from there stays below 256 rows * pitch * 4 bytes < 2^31)
+    const size_t tile_base = (size_t)(g0 - a.row0) * a.ld;
     for (int v = (int)threadIdx.x; v < nvec; v += (int)blockDim.x) {
       const int tr = v / vec_per_row, col = c0 + (v % vec_per_row) * 8;
-      const size_t o = tile_base + (size_t)tr * a.N + col;
-      const int voff = (int)(((uint32_t)tr * (uint32_t)a.N + (uint32_t)col) * (uint32_t)elem);
+      const size_t o = tile_base + (size_t)tr * a.ld + col;
+      const int voff = (int)(((uint32_t)tr * (uint32_t)a.ld + (uint32_t)col) * (uint32_t)elem);
       float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int j = 0; j < a.R; ++j) {
         __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
@@ -279,6 +282,11 @@ struct Plan {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Row pitches in elements (0 in the problem: packed).
+static inline long long pitch_a(const flux_problem_t* p) { return p->lda ? p->lda : p->K; }
+static inline long long pitch_b(const flux_problem_t* p) { return p->ldb ? p->ldb : p->N; }
+static inline long long pitch_c(const flux_problem_t* p) { return p->ldc ? p->ldc : p->N; }
+
 static int validate_problem(int op, const flux_problem_t* p) {
   if (p == nullptr) return FLUX_ERR_INVALID_ARG;
   if (op != FLUX_OP_RS && op != FLUX_OP_AG) return FLUX_ERR_INVALID_ARG;
@@ -289,9 +297,15 @@ static int validate_problem(int op, const flux_problem_t* p) {
   // every matrix stays below 2^31 elements: the kernels address operands through 32-bit buffer offsets
   if ((long long)p->M * p->N >= (1ll << 31) || (long long)p->M * p->K >= (1ll << 31) ||
       (long long)p->K * p->N >= (1ll << 31)) return FLUX_ERR_SHAPE;
+  // row pitches: at least a row, rows stay 16-byte aligned, and the last element's index stays below 2^31 too
+  if (p->lda < 0 || p->ldb < 0 || p->ldc < 0) return FLUX_ERR_INVALID_ARG;
+  if (pitch_a(p) < p->K || pitch_b(p) < p->N || pitch_c(p) < p->N) return FLUX_ERR_SHAPE;
+  if (pitch_a(p) % 8 != 0 || pitch_b(p) % 8 != 0 || pitch_c(p) % 8 != 0) return FLUX_ERR_SHAPE;
+  if ((long long)(p->M - 1) * pitch_a(p) + p->K >= (1ll << 31) || (long long)(p->K - 1) * pitch_b(p) + p->N >= (1ll << 31) ||
+      (long long)(p->M - 1) * pitch_c(p) + p->N >= (1ll << 31)) return FLUX_ERR_SHAPE;
   // the reduce-scatter epilogue addresses a tile of fp32 partials (up to 256 rows) through a signed
   // 31-bit offset from the tile's origin: 256 rows of 4-byte elements must stay below 2^31 bytes
-  if (p->N >= FLUX_MAX_N) return FLUX_ERR_SHAPE;
+  if (p->N >= FLUX_MAX_N || pitch_c(p) >= FLUX_MAX_N) return FLUX_ERR_SHAPE;
   if (p->out_dtype != FLUX_BF16 && p->out_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
   if (op == FLUX_OP_RS && p->partial_dtype != FLUX_BF16 && p->partial_dtype != FLUX_F32) return FLUX_ERR_INVALID_ARG;
   if (p->tile_config < 0 || p->tile_config > NUM_CFGS) return FLUX_ERR_INVALID_ARG;
@@ -503,7 +517,8 @@ static int make_plan(int op, const flux_problem_t* p, Plan* pl) {
     const long long whole_tiles = pl->split_k == 1 ? tiles : (long long)pl->full_tiles;
     // what the two-stage kernel's workgroups can carry themselves (see SideCopy)
     const bool can_carry = g_cfgs[cfg].stages == 2 && g_cfgs[cfg].occupancy == 1 && pl->edge == 0 &&
-                           !(p->flags & (FLUX_FLAG_AG_ABSENT_OWNERS | FLUX_FLAG_AG_COPY_UPFRONT)) && tile_vec * 16ull < (1ull << 31);
+                           !(p->flags & (FLUX_FLAG_AG_ABSENT_OWNERS | FLUX_FLAG_AG_COPY_UPFRONT)) && tile_vec * 16ull < (1ull << 31) &&
+                           pitch_a(p) == p->K;      // (a tile is one run of memory on both sides)
     if (pl->copy_help && p->link_gbps > 0 && p->copy_workgroups == 0 && can_carry && (p->R - 1) * pl->ctpc <= 32 && p->R > 1) {
       // A transfer that stands for a link, without a driver: a driver's workgroups would each hold a
       // compute unit for as long as the transfer lasts, which no link does.  Every remote tile is
@@ -637,6 +652,7 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
   std::memset(a, 0, sizeof(*a));
   a->M = p->M; a->N = p->N; a->K = p->K;
   a->R = p->R; a->rank = p->rank; a->S = p->M / p->R;
+  a->lda = (int32_t)pitch_a(p); a->ldb = (int32_t)pitch_b(p); a->ldc = (int32_t)pitch_c(p);
   a->partial_f32 = p->partial_dtype == FLUX_F32;
   a->out_f32 = p->out_dtype == FLUX_F32;
   a->split_k = pl.split_k;
@@ -700,8 +716,9 @@ static int launch_copy(const flux_problem_t* p, const Plan& pl, const void* cons
   for (int i = 0; i < n_order; ++i) c.order[i] = order[i];
   c.n_order = n_order;
   c.tiles_per_chunk = fused ? pl.ctpc : 1;
-  c.chunk_vec = chunk_vec;
   c.tile_vec = chunk_vec / c.tiles_per_chunk;
+  c.pitch = AggPitch{(uint32_t)p->K / 8u, (uint32_t)(pitch_a(p) / 8)};
+  c.rows_per_tile = (p->M / p->R) / c.tiles_per_chunk;
   // bytes / (GB/s) = ns; 10 ns per tick.  The baseline's copy is paced like the fused call's driver:
   // an emulated link delivers no faster when nothing overlaps with it.
   c.pace_ticks = p->link_gbps > 0 ? (unsigned long long)((double)c.tile_vec * 16.0 / (double)p->link_gbps / 10.0) : 0ull;
@@ -1036,6 +1053,7 @@ int flux_rs_reduce_slice_ready(const flux_problem_t* p, const void* const* stage
   r.status = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + WS_STATUS_OFF);
   r.timeout_ticks = p->spin_timeout_ticks ? p->spin_timeout_ticks : DEFAULT_TIMEOUT_TICKS;
   r.S = S; r.N = p->N; r.R = p->R;
+  r.ld = (int32_t)pitch_c(p);
   r.partial_f32 = p->partial_dtype == FLUX_F32;
   r.out_f32 = p->out_dtype == FLUX_F32;
   r.bm = pl.bm; r.bn = pl.bn; r.tiles_n = pl.tiles_n;
@@ -1086,7 +1104,7 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   a.sig_local_hi = (p->rank + 1) * pl.ctpc;
   // rows that do not start and end on cache line boundaries may share a line with a row of another
   // communication tile
-  a.acquire_l2 = (reinterpret_cast<uintptr_t>(A_agg) % 128 != 0) || (((size_t)p->K * 2) % 128 != 0);
+  a.acquire_l2 = (reinterpret_cast<uintptr_t>(A_agg) % 128 != 0) || (((size_t)pitch_a(p) * 2) % 128 != 0);
   const uint32_t call_id = next_call_id();
   if (pl.copy_help && p->R > 1) {
     a.copy_pieces = pl.copy_pieces;
@@ -1129,7 +1147,7 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
   }
 
   // local chunk (its signal is preset, so it must be in place before the kernel starts)
-  const __bf16* local_dst = static_cast<const __bf16*>(A_agg) + (size_t)p->rank * chunk_elems;
+  const __bf16* local_dst = static_cast<const __bf16*>(A_agg) + (size_t)p->rank * (p->M / p->R) * pitch_a(p);
   if (A_chunks[p->rank] != static_cast<const void*>(local_dst)) {
     int self = p->rank;
     st = launch_copy(p, pl, A_chunks, A_agg, &self, 1, false, nullptr, nullptr, 0, cs);
@@ -1148,8 +1166,10 @@ int flux_ag_gemm(const flux_problem_t* p, const void* const* A_chunks, void* A_a
       const int c = order[i];
       for (int t = 0; t < pl.ctpc; ++t) {
         const unsigned char* src = static_cast<const unsigned char*>(A_chunks[c]) + (size_t)t * tile_bytes;
-        unsigned char* dst = static_cast<unsigned char*>(A_agg) + ((size_t)c * pl.ctpc + t) * tile_bytes;
-        FLUX_HIP(hipMemcpyAsync(dst, src, tile_bytes, hipMemcpyDeviceToDevice, xs));
+        const size_t rows = (size_t)(p->M / p->R) / pl.ctpc, row_bytes = (size_t)p->K * 2, pitch = (size_t)pitch_a(p) * 2;
+        unsigned char* dst = static_cast<unsigned char*>(A_agg) + ((size_t)c * pl.ctpc + t) * rows * pitch;
+        if (pitch == row_bytes) FLUX_HIP(hipMemcpyAsync(dst, src, tile_bytes, hipMemcpyDeviceToDevice, xs));
+        else FLUX_HIP(hipMemcpy2DAsync(dst, pitch, src, row_bytes, row_bytes, rows, hipMemcpyDeviceToDevice, xs));
         FLUX_HIP(hipStreamWriteValue32(xs, signals + c * pl.ctpc + t, 1u, 0));
       }
     }
@@ -1229,6 +1249,7 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
       r.partial_f32 = p->partial_dtype == FLUX_F32;
       r.out_f32 = p->out_dtype == FLUX_F32;
       r.c_f32 = r.out_f32;
+      r.ld_c = (int32_t)pitch_c(p); r.ld_peer = p->N; r.ld_out = (int32_t)pitch_c(p);
       r.row0 = 0; r.rows = p->M;
       const long long nvec = (long long)p->M * p->N / 8;
       const int grid = (int)std::min<long long>((nvec + 255) / 256, 256 * 8);
@@ -1247,7 +1268,7 @@ int flux_gemm_ref_unfused(int op, int phases, const flux_problem_t* p, const voi
     if (chunk_elems % 8 != 0) return FLUX_ERR_SHAPE;
     for (int r = 0; r < p->R; ++r) {
       if (!A_chunks[r] || !aligned16(A_chunks[r])) return FLUX_ERR_INVALID_ARG;
-      const void* dst = static_cast<const __bf16*>(A_agg) + (size_t)r * chunk_elems;
+      const void* dst = static_cast<const __bf16*>(A_agg) + (size_t)r * (p->M / p->R) * pitch_a(p);
       if (A_chunks[r] != dst) order[n++] = r;
     }
     st = launch_copy(p, pl, A_chunks, A_agg, order, n, false, nullptr, nullptr, 0, s);
@@ -1279,6 +1300,7 @@ int flux_rs_reduce_slice(const flux_problem_t* p, const void* const* staged, voi
   r.partial_f32 = p->partial_dtype == FLUX_F32;
   r.c_f32 = r.partial_f32;
   r.out_f32 = p->out_dtype == FLUX_F32;
+  r.ld_c = r.ld_peer = r.ld_out = (int32_t)pitch_c(p);
   r.row0 = 0; r.rows = S;
   const long long nvec = (long long)S * p->N / 8;
   const int grid = (int)std::max<long long>(1, std::min<long long>((nvec + 255) / 256, 256 * 8));
@@ -1349,13 +1371,14 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
     r.partial_f32 = p->partial_dtype == FLUX_F32;
     r.out_f32 = p->out_dtype == FLUX_F32;
     r.c_f32 = r.out_f32;
+    r.ld_c = (int32_t)pitch_c(p); r.ld_peer = p->N; r.ld_out = (int32_t)pitch_c(p);
     const long long nvec = (long long)S * p->N / 8;
     const int grid = (int)std::max<long long>(1, std::min<long long>((nvec + 255) / 256, 256 * 8));
     // slices in the order of the fused kernel: the ring after the local rank, the own slice last
     for (int d = 1; d <= R; ++d) {
       const int slice = (p->rank + d) % R;
-      g.A = static_cast<const __bf16*>(A) + (size_t)slice * S * p->K;
-      g.C = static_cast<unsigned char*>(C) + (size_t)slice * S * p->N * out_size;
+      g.A = static_cast<const __bf16*>(A) + (size_t)slice * S * pitch_a(p);
+      g.C = static_cast<unsigned char*>(C) + (size_t)slice * S * pitch_c(p) * out_size;
       st = launch_gemm(plq, EPI_PLAIN, 0, g, cs);
       if (st != FLUX_OK) return st;
       FLUX_HIP(hipEventRecord(ev[slice], cs));
@@ -1382,7 +1405,7 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
   st = make_plan(FLUX_OP_AG, p, &plc);
   if (st != FLUX_OK) return st;
   const __bf16* agg = static_cast<const __bf16*>(A_agg);
-  if (A_chunks[p->rank] != static_cast<const void*>(agg + (size_t)p->rank * chunk_elems)) {
+  if (A_chunks[p->rank] != static_cast<const void*>(agg + (size_t)p->rank * S * pitch_a(p))) {
     int self = p->rank;
     st = launch_copy(p, plc, A_chunks, A_agg, &self, 1, false, nullptr, nullptr, 0, cs);
     if (st != FLUX_OK) return st;
@@ -1398,8 +1421,8 @@ int flux_gemm_ref_chunked(int op, const flux_problem_t* p, const void* A, const 
   for (int i = -1; i < R - 1; ++i) {
     const int c = i < 0 ? p->rank : order[i];
     if (i >= 0) FLUX_HIP(hipStreamWaitEvent(cs, ev[c], 0));
-    g.A = agg + (size_t)c * chunk_elems;
-    g.C = static_cast<unsigned char*>(C) + (size_t)c * S * p->N * out_size;
+    g.A = agg + (size_t)c * S * pitch_a(p);
+    g.C = static_cast<unsigned char*>(C) + (size_t)c * S * pitch_c(p) * out_size;
     st = launch_gemm(plq, EPI_PLAIN, 0, g, cs);
     if (st != FLUX_OK) return st;
   }

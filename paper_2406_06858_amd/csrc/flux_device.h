@@ -88,6 +88,7 @@ struct GemmArgs {
   void* C;                   // [M,N] of out dtype (plain epilogue)
   int32_t M, N, K;
   int32_t R, rank, S;        // S = M / R
+  int32_t lda, ldb, ldc;     // row pitches in elements: A (the gathered matrix); B; C and the out slices (peer partials are packed)
   // K split: the first `full_tiles` tiles (in TileCoord order) are computed by one workgroup
   // each; every one of the remaining `split_tiles` tiles by `split_k` workgroups that each take
   // `k_per_split` of K.  A uniform split has full_tiles = 0; splitting only the tiles of the last,
@@ -299,7 +300,7 @@ struct Loader {
       const int row = v / C::A_SLOTS, slot = v % C::A_SLOTS;
       int gr = m0 + row;
       if (EDGE) gr = gr < a.M ? gr : a.M - 1;
-      pa[p] = a.A + (size_t)gr * a.K + slot * 8;
+      pa[p] = a.A + (size_t)gr * a.lda + slot * 8;
       ka[p] = slot * 8;
       lds_a[p] = row * (C::BK * 2) + ((slot ^ swz_a<C::A_SLOTS>(row)) << 4);
     }
@@ -310,7 +311,7 @@ struct Loader {
       int gn = n0 + s * 8;
       nb_ok[p] = !EDGE || gn < a.N;
       if (EDGE && gn >= a.N) gn = 0;
-      pb[p] = a.B + (size_t)k * a.N + gn;
+      pb[p] = a.B + (size_t)k * a.ldb + gn;
       kb[p] = k;
       lds_b[p] = C::A_BYTES + k * (C::BN * 2) + ((s ^ swz_b<C::B_SLOTS>(k)) << 4);
     }
@@ -324,7 +325,7 @@ struct Loader {
     }
 #pragma unroll
     for (int p = 0; p < C::B_VEC; ++p) {
-      if (!EDGE || (nb_ok[p] && k0 + kb[p] < k_end)) rb[p] = *reinterpret_cast<const uint4*>(pb[p] + (size_t)k0 * a.N);
+      if (!EDGE || (nb_ok[p] && k0 + kb[p] < k_end)) rb[p] = *reinterpret_cast<const uint4*>(pb[p] + (size_t)k0 * a.ldb);
       else rb[p] = make_uint4(0, 0, 0, 0);
     }
   }
@@ -380,10 +381,10 @@ __device__ __forceinline__ void store_row8(const GemmArgs& a, void* const* lds_o
   if (EPI == EPI_RS) {
     const int r = gm / a.S;
     base = lds_outs[r];
-    o = (size_t)(gm - r * a.S) * a.N + gn;
+    o = (size_t)(gm - r * a.S) * a.ldc + gn;
   } else {
     base = a.C;
-    o = (size_t)gm * a.N + gn;
+    o = (size_t)gm * a.ldc + gn;
   }
   if (a.out_f32) {
     float* q = static_cast<float*>(base) + o;
@@ -507,9 +508,28 @@ __device__ __forceinline__ void epilogue_all(const GemmArgs& a, void* const* lds
 
 // DEPTH vectors per thread in flight (32 made the plain chunk copy slower: 60 against 24 us for 58.7 MB);
 // the last batch is predicated, not walked one vector (one memory round trip) at a time.
-template <int DEPTH = 16>
-__device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
-                                           int piece, int pieces, int tid) {
+//
+// The sources are packed; the gathered matrix may have a row pitch.  Vector i of a communication
+// tile then goes to row i / kv, place i % kv, counted from the tile's first row.
+struct AggPitch {
+  uint32_t kv, pitch_v;      // 16-byte vectors per row; from one row to the next
+  __device__ __forceinline__ bool packed() const { return kv == pitch_v; }
+};
+__device__ __forceinline__ AggPitch agg_pitch(const GemmArgs& a) { return AggPitch{(uint32_t)a.K / 8u, (uint32_t)a.lda / 8u}; }
+// first vector of communication tile f in the gathered matrix
+__device__ __forceinline__ uint4* agg_tile(const GemmArgs& a, int f) {
+  return reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.rows_per_signal * ((unsigned long long)a.lda / 8);
+}
+template <bool PITCHED>
+__device__ __forceinline__ unsigned long long agg_index(const AggPitch& g, unsigned long long i) {
+  if (!PITCHED) return i;
+  const uint32_t j = (uint32_t)i;          // a tile has fewer than 2^28 vectors
+  return (unsigned long long)(j / g.kv) * g.pitch_v + j % g.kv;
+}
+
+template <int DEPTH, bool PITCHED>
+__device__ __forceinline__ void copy_piece_as(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
+                                              int piece, int pieces, int tid, const AggPitch& g) {
   const unsigned long long stride = (unsigned long long)pieces * 256;
   for (unsigned long long i = (unsigned long long)piece * 256 + tid; i < tile_vec; i += DEPTH * stride) {
     u32x4 v[DEPTH];
@@ -518,8 +538,14 @@ __device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4*
       if (i + u * stride < tile_vec) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i + u * stride));
 #pragma unroll
     for (int u = 0; u < DEPTH; ++u)
-      if (i + u * stride < tile_vec) store_through(dst + i + u * stride, v[u]);
+      if (i + u * stride < tile_vec) store_through(dst + agg_index<PITCHED>(g, i + u * stride), v[u]);
   }
+}
+template <int DEPTH = 16>
+__device__ __forceinline__ void copy_piece(const uint4* __restrict__ src, uint4* __restrict__ dst, unsigned long long tile_vec,
+                                           int piece, int pieces, int tid, const AggPitch& g) {
+  if (g.packed()) copy_piece_as<DEPTH, false>(src, dst, tile_vec, piece, pieces, tid, g);       // (uniform)
+  else copy_piece_as<DEPTH, true>(src, dst, tile_vec, piece, pieces, tid, g);
 }
 
 // A piece of at most COPY_DEPTH * 256 vectors in two halves: the loads, and, once the piece is known
@@ -536,13 +562,19 @@ __device__ __forceinline__ void load_piece(const uint4* __restrict__ src, unsign
     if (i + u * stride < tile_vec) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + i + u * stride));
   }
 }
-__device__ __forceinline__ void store_piece(uint4* __restrict__ dst, unsigned long long tile_vec, int piece, int pieces,
-                                            int tid, const u32x4 (&v)[COPY_DEPTH]) {
+template <bool PITCHED>
+__device__ __forceinline__ void store_piece_as(uint4* __restrict__ dst, unsigned long long tile_vec, int piece, int pieces,
+                                               int tid, const u32x4 (&v)[COPY_DEPTH], const AggPitch& g) {
   const unsigned long long stride = (unsigned long long)pieces * 256;
   const unsigned long long i = (unsigned long long)piece * 256 + tid;
 #pragma unroll
   for (int u = 0; u < COPY_DEPTH; ++u)
-    if (i + u * stride < tile_vec) store_through(dst + i + u * stride, v[u]);
+    if (i + u * stride < tile_vec) store_through(dst + agg_index<PITCHED>(g, i + u * stride), v[u]);
+}
+__device__ __forceinline__ void store_piece(uint4* __restrict__ dst, unsigned long long tile_vec, int piece, int pieces,
+                                            int tid, const u32x4 (&v)[COPY_DEPTH], const AggPitch& g) {
+  if (g.packed()) store_piece_as<false>(dst, tile_vec, piece, pieces, tid, v, g);               // (uniform)
+  else store_piece_as<true>(dst, tile_vec, piece, pieces, tid, v, g);
 }
 
 // true if the caller now owns the piece.  One exchange, one round trip: whoever swaps the call's id
@@ -623,13 +655,13 @@ __device__ __forceinline__ void transfer_own_pieces(const GemmArgs& a, int* lds,
     const int chunk = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15), t = j % ctpc;
     const int f = chunk * ctpc + t;
     const uint4* src = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)t * a.copy_tile_vec;
-    uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
+    uint4* dst = agg_tile(a, f);
     u32x4 v[COPY_DEPTH];
     load_piece(src, a.copy_tile_vec, piece, a.copy_pieces, tid, v);
     if (tid == 0) lds[2] = claim_piece(a.copy_claims + (size_t)f * a.copy_pieces + piece, call_id) ? 1 : 0;
     __syncthreads();
     if (lds[2]) {
-      store_piece(dst, a.copy_tile_vec, piece, a.copy_pieces, tid, v);
+      store_piece(dst, a.copy_tile_vec, piece, a.copy_pieces, tid, v, agg_pitch(a));
       finish_pieces(a.copy_counters + f, a.signals + f, a.copy_pieces, 1);
     }
     return;
@@ -655,8 +687,7 @@ __device__ __forceinline__ void transfer_own_pieces(const GemmArgs& a, int* lds,
       const int chunk = (int)((a.copy_order4 >> (4 * (j / ctpc))) & 15), t = j % ctpc;
       const int f = chunk * ctpc + t;
       const uint4* src = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)t * a.copy_tile_vec;
-      uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
-      copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
+      copy_piece(src, agg_tile(a, f), a.copy_tile_vec, piece, a.copy_pieces, tid, agg_pitch(a));
     }
     // count the pieces in, all at once: lane l of the first wave for the piece it claimed
     __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's write-through stores are acknowledged
@@ -955,7 +986,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
           const unsigned long long col = (vv < nvec ? vv : 0) % vec_per_row;
           const int chunk = row / a.S;
           src[u] = static_cast<const uint4*>(lds_srcs[chunk]) + (unsigned long long)(row - chunk * a.S) * vec_per_row + col;
-          dst[u] = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)row * vec_per_row + col;
+          dst[u] = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)row * ((unsigned long long)a.lda / 8) + col;
           if (vv < nvec) x[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src[u]));
         }
 #pragma unroll
@@ -993,8 +1024,7 @@ __device__ __forceinline__ bool wait_signals(const GemmArgs& a, int m0, int m1, 
       if (lds[2]) {
         const int ctpc = a.n_signals / a.R;
         const uint4* src = static_cast<const uint4*>(lds_srcs[f / ctpc]) + (unsigned long long)(f % ctpc) * a.copy_tile_vec;
-        uint4* dst = reinterpret_cast<uint4*>(const_cast<__bf16*>(a.A)) + (unsigned long long)f * a.copy_tile_vec;
-        copy_piece(src, dst, a.copy_tile_vec, piece, a.copy_pieces, tid);
+        copy_piece(src, agg_tile(a, f), a.copy_tile_vec, piece, a.copy_pieces, tid, agg_pitch(a));
         finish_pieces(a.copy_counters + f, a.signals + f, a.copy_pieces, 1);
       }
     } else {
@@ -1063,7 +1093,7 @@ __device__ __forceinline__ void epilogue_all_atomic(const GemmArgs& a, void* con
       const int r = r0 + r_in;
       const int gm = m0 + wm * C::WTM + mi * 32 + r;
       const int owner = gm / a.S;
-      float* row = static_cast<float*>(lds_outs[owner]) + (size_t)(gm - owner * a.S) * a.N + n0 + wn * C::WTN;
+      float* row = static_cast<float*>(lds_outs[owner]) + (size_t)(gm - owner * a.S) * a.ldc + n0 + wn * C::WTN;
 #pragma unroll
       for (int c0 = 0; c0 < C::WTN; c0 += W) {
         const int c = c0 + c_in;
@@ -1301,12 +1331,12 @@ struct DmaLoader {
   uint32_t K2, N2;               // row pitches in bytes
 
   __device__ __forceinline__ void init(const GemmArgs& a, int m0, int n0, int wave, int lane) {
-    ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.A), 0, (int)((unsigned)a.M * (unsigned)a.K * 2u), 0x00027000);
-    rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0, (int)((unsigned)a.K * (unsigned)a.N * 2u), 0x00027000);
+    ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.A), 0, (int)(((unsigned)(a.M - 1) * (unsigned)a.lda + (unsigned)a.K) * 2u), 0x00027000);
+    rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0, (int)(((unsigned)(a.K - 1) * (unsigned)a.ldb + (unsigned)a.N) * 2u), 0x00027000);
     const int r_in = lane / C::A_SLOTS, sp = lane % C::A_SLOTS;
     const int row = A_RPI * wave + r_in;
-    K2 = (uint32_t)a.K * 2u;
-    N2 = (uint32_t)a.N * 2u;
+    K2 = (uint32_t)a.lda * 2u;
+    N2 = (uint32_t)a.ldb * 2u;
     voff_a = (uint32_t)(m0 + row) * K2 + ((uint32_t)(sp ^ swz_a<C::A_SLOTS>(row)) << 4);
     const int k_in = lane / C::B_SLOTS, spb = lane % C::B_SLOTS;
     const int k = RPI * wave + k_in;

@@ -24,10 +24,11 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 
 def test_problem_struct_layout_matches_header():
-    # 14 int32/uint32 fields + one uint64, naturally aligned
+    # 14 int32/uint32 fields, one uint64, three int64 row pitches, naturally aligned
     import ctypes
-    assert ctypes.sizeof(fb.flux_problem_t) == 64
+    assert ctypes.sizeof(fb.flux_problem_t) == 88
     assert fb.flux_problem_t.spin_timeout_ticks.offset == 56
+    assert (fb.flux_problem_t.lda.offset, fb.flux_problem_t.ldb.offset, fb.flux_problem_t.ldc.offset) == (64, 72, 80)
 
 
 def test_status_strings():
@@ -266,6 +267,34 @@ def test_offsets_stay_in_32_bits_at_the_edges_of_validation():
     assert e.value.status == fb.FLUX_ERR_SHAPE
     assert fb.flux_tile_shape(fb.FLUX_OP_RS, fb.problem(8, (1 << 21) - 8, 8, 8, 0)).tile_n > 0
     assert 256 * ((1 << 21) - 8) * 4 < 2 ** 31
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(lda=248), fb.FLUX_ERR_SHAPE),              # shorter than a row
+    (dict(ldb=260), fb.FLUX_ERR_SHAPE),              # rows would lose their 16-byte alignment
+    (dict(ldc=250), fb.FLUX_ERR_SHAPE),
+    (dict(lda=-8), fb.FLUX_ERR_INVALID_ARG),
+    (dict(ldc=1 << 21), fb.FLUX_ERR_SHAPE),          # a tile of the slice would pass 2^31 bytes
+    (dict(lda=1 << 25), fb.FLUX_ERR_SHAPE),          # the last element's index would pass 2^31
+])
+def test_row_pitches_are_validated(bad, status):
+    p = fb.problem(128, 256, 256, 8, 0, **bad)
+    with pytest.raises(fb.FluxError) as e:
+        fb.flux_tile_shape(fb.FLUX_OP_RS, p)
+    assert e.value.status == status
+
+
+def test_row_pitches_in_planning():
+    """A pitch equal to the row length is the packed layout; a gathered matrix with a longer pitch is
+    moved before the signal wait (its communication tiles are not single runs of memory)."""
+    packed = fb.problem(8192, 4608, 2048, 8, 1)
+    same = fb.problem(8192, 4608, 2048, 8, 1, lda=2048, ldb=4608, ldc=4608)
+    assert fb.flux_ag_deferred_tiles(packed) == fb.flux_ag_deferred_tiles(same) > 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 2048, 8, 1, lda=2048 + 64)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 2048, 8, 1, lda=2048 + 64, link_gbps=400)) == 0
+    assert fb.flux_ag_deferred_tiles(fb.problem(8192, 4608, 2048, 8, 1, ldb=4608 + 64, ldc=4608 + 8)) > 0
+    # the largest pitch that keeps the last element's index below 2^31
+    assert fb.flux_tile_shape(fb.FLUX_OP_RS, fb.problem(128, 256, 256, 8, 0, lda=(2 ** 31 - 256) // 127 // 8 * 8)).tile_m > 0
 
 
 def test_trace_request_arguments():
