@@ -141,6 +141,15 @@ def main() -> int:
             fb.flux_ag_gemm(self.p_up, self.chunks, self.A_agg, self.next_B(), self.C, self.signals, self.arrival,
                             self.ws, compute, copy)
 
+        def b_as_n_by_k(self):
+            # the same fused call with the weight handed over as [N,K] (a linear layer's own layout)
+            if not hasattr(self, "p_nk"):
+                w = self.w
+                self.p_nk = fb.problem(w.M, w.N, w.K, w.R, self.rank, "bf16", w.out_dtype, spin_timeout_ticks=TIMEOUT_TICKS, b_is_nk=1)
+                self.B_nk = self.B.t().contiguous()
+            fb.flux_ag_gemm(self.p_nk, self.chunks, self.A_agg, self.B_nk, self.C, self.signals, self.arrival,
+                            self.ws, compute, copy)
+
         def alg_bytes(self):     # fused kernel: A_agg + B read once, C written once; the default call has no
             w = self.w           # copy kernel, so the R-1 remote chunks are read and written by this kernel too
             return 2.0 * (w.M * w.K + w.K * w.N + w.M * w.N) + 2 * 2.0 * (w.R - 1) * w.S * w.K
@@ -207,6 +216,13 @@ def main() -> int:
                                         flags=fb.FLUX_FLAG_NO_RESIDENT_GRID)
             fb.flux_gemm_rs(self.p_1pt, self.A, self.next_B(), self.peers, self.outs, self.ws, compute)
 
+        def b_as_n_by_k(self):
+            if not hasattr(self, "p_nk"):
+                w = self.w
+                self.p_nk = fb.problem(w.M, w.N, w.K, w.R, self.rank, w.partial_dtype, w.out_dtype, b_is_nk=1)
+                self.B_nk = self.B.t().contiguous()
+            fb.flux_gemm_rs(self.p_nk, self.A, self.B_nk, self.peers, self.outs, self.ws, compute)
+
         def alg_bytes(self):
             w = self.w
             ps = 2 if w.partial_dtype == "bf16" else 4
@@ -235,7 +251,7 @@ def main() -> int:
             ts.append(e0.elapsed_ms(e1) / batch)
         return statistics.median(ts)
 
-    def overlap_block(op, reps=20, warm=5, graph=False):
+    def overlap_block(op, reps=20, warm=5, graph=False, nk=False):
         """Eq. 1-2 with GEMM_non-split := the plain kernel of the same tile configuration."""
         t_gemm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_GEMM), reps, warm)
         t_comm = time_calls(lambda: op.unfused(fb.FLUX_PHASE_COMM), reps, warm)
@@ -282,6 +298,8 @@ def main() -> int:
         if hasattr(op, "one_workgroup_per_tile") and fb.flux_rs_resident_grid(op.p)[0] > 0:
             more["resident_grid"] = dict(zip(("workgroups", "late_start_ticks_100MHz"), fb.flux_rs_resident_grid(op.p)))
             more["ms_fused_one_workgroup_per_tile"] = round(time_calls(op.one_workgroup_per_tile, reps, warm), 4)
+        if nk:
+            more["ms_fused_b_as_n_by_k"] = round(time_calls(op.b_as_n_by_k, reps, warm), 4)
         return {**more, "ms_gemm_only": round(t_gemm, 4), "ms_comm_only": round(t_comm, 4), "ms_unfused": round(t_unf, 4),
                 "ms_fused": round(t_fus, 4), "ms_fused_kernel": round(t_k, 4), "ms_chunked": round(t_chk, 4),
                 "overlap_efficiency_chunked": None if ect_no <= 0 else round(1.0 - (t_chk - t_gemm) / ect_no, 4),
@@ -427,9 +445,9 @@ def main() -> int:
     extra = {}
     if not args.no_extra:
         say("extra: c4_ag")
-        extra["c4_ag"] = overlap_block(ag)
+        extra["c4_ag"] = overlap_block(ag, nk=True)
         say("extra: c4_rs")
-        extra["c4_rs"] = overlap_block(rs)
+        extra["c4_rs"] = overlap_block(rs, nk=True)
         say("extra: vendor library GEMM on the same operands")
         # Context, not a target and not part of the path: the vendor library's plain GEMM (hipBLASLt
         # behind torch.matmul) on the same operands, and on zeros.  With normally distributed operands

@@ -21,7 +21,7 @@
  * plus the non-overlapped baseline used for the overlap-efficiency metric (Sec. 2.3, Eq. 1-2).
  *
  * Conventions
- *   - All matrices are row-major: A [M,K], B [K,N], partials / C [M,N], slices [M/R,N]; densely
+ *   - All matrices are row-major: A [M,K], B [K,N] (or [N,K], see b_is_nk), partials / C [M,N], slices [M/R,N]; densely
  *     packed unless the problem gives a row pitch (lda / ldb / ldc of flux_problem_t, which also says
  *     which matrices each applies to).  A and B are bf16; partials and outputs are bf16 or f32
  *     (flux_dtype_t).
@@ -133,17 +133,22 @@ typedef struct flux_problem {
                                below 2^31.
                                lda: A (flux_gemm_rs, the references) and the gathered matrix A_agg
                                     (flux_ag_gemm); the chunk sources A_chunks[r] are packed [M/R,K].
-                               ldb: B.
+                               ldb: B (rows of N values, or of K values with b_is_nk).
                                ldc: C, every out slice, and the staged slices that
                                     FLUX_FLAG_RS_WRITE_ONLY / flux_gemm_rs_notify write and
                                     flux_rs_reduce_slice / flux_rs_reduce_slice_ready read.
                                Peer partials are packed [M,N].  What lies between the end of a
                                row and the next row is neither read nor written.                  */
+  int32_t b_is_nk;          /* 0: B is [K,N] (row k holds the N values B[k,:]).
+                               1: B is [N,K], row n holding the K values B[:,n] -- the layout of a
+                                  linear layer's weight, out features by in features; ldb is then the
+                                  pitch of those rows (0 = K).  Same results bit for bit.          */
+  int32_t reserved2;        /* must be 0                                                          */
 } flux_problem_t;
 
 /*
  * GEMM-ReduceScatter, fused (Alg. 1 with the Reduce branch).
- *   A, B            device, bf16, [M,K] and [K,N].
+ *   A, B            device, bf16, [M,K] and [K,N] ([N,K] with b_is_nk).
  *   peer_partials   (NULL allowed with FLUX_FLAG_RS_WRITE_ONLY / FLUX_FLAG_RS_ATOMIC) host array [R] of device pointers to [M,N] matrices of partial_dtype;
  *                   entry [rank] is ignored (may be NULL).
  *   out_slices      host array [R] of device pointers to [M/R,N] matrices of out_dtype, all
@@ -215,7 +220,7 @@ int flux_gemm_rs_static(const flux_problem_t* p, const void* A, const void* B,
  *                   required; with 128-byte alignment and a row pitch that is a multiple of 64 no cache line holds
  *                   rows of two communication tiles, and a workgroup leaves its signal wait without
  *                   invalidating its die's L2 (one to two microseconds per workgroup otherwise).
- *   B, C            device, [K,N] bf16 and [M,N] out_dtype.
+ *   B, C            device, [K,N] bf16 ([N,K] with b_is_nk) and [M,N] out_dtype.
  *   signals         device uint32[R * comm_tiles_per_chunk] ("signal_list").  Must be in the preset
  *                   state on entry (local communication tiles 1, the others 0): preset once
  *                   with flux_init_buffers, as the paper presets at operator initialisation;

@@ -53,6 +53,7 @@ class flux_problem_t(C.Structure):
         ("link_gbps", C.c_int32), ("reserved", C.c_int32),
         ("spin_timeout_ticks", C.c_uint64),
         ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
+        ("b_is_nk", C.c_int32), ("reserved2", C.c_int32),
     ]
 
 
@@ -128,10 +129,10 @@ _DT = {"bf16": FLUX_BF16, "f32": FLUX_F32, torch.bfloat16: FLUX_BF16, torch.floa
 
 def problem(M, N, K, R, rank, partial_dtype="bf16", out_dtype="bf16", tile_config=0, split_k=0,
             flags=0, comm_tiles_per_chunk=0, copy_workgroups=0, spin_timeout_ticks=0, link_gbps=0,
-            lda=0, ldb=0, ldc=0) -> flux_problem_t:
+            lda=0, ldb=0, ldc=0, b_is_nk=0) -> flux_problem_t:
     return flux_problem_t(M, N, K, R, rank, _DT[partial_dtype], _DT[out_dtype], tile_config, split_k,
                           flags, comm_tiles_per_chunk, copy_workgroups, link_gbps, 0, spin_timeout_ticks,
-                          lda, ldb, ldc)
+                          lda, ldb, ldc, b_is_nk, 0)
 
 
 def _ptr(t) -> int:

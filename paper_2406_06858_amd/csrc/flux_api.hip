@@ -284,7 +284,7 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Row pitches in elements (0 in the problem: packed).
 static inline long long pitch_a(const flux_problem_t* p) { return p->lda ? p->lda : p->K; }
-static inline long long pitch_b(const flux_problem_t* p) { return p->ldb ? p->ldb : p->N; }
+static inline long long pitch_b(const flux_problem_t* p) { return p->ldb ? p->ldb : (p->b_is_nk ? p->K : p->N); }
 static inline long long pitch_c(const flux_problem_t* p) { return p->ldc ? p->ldc : p->N; }
 
 static int validate_problem(int op, const flux_problem_t* p) {
@@ -298,10 +298,11 @@ static int validate_problem(int op, const flux_problem_t* p) {
   if ((long long)p->M * p->N >= (1ll << 31) || (long long)p->M * p->K >= (1ll << 31) ||
       (long long)p->K * p->N >= (1ll << 31)) return FLUX_ERR_SHAPE;
   // row pitches: at least a row, rows stay 16-byte aligned, and the last element's index stays below 2^31 too
-  if (p->lda < 0 || p->ldb < 0 || p->ldc < 0) return FLUX_ERR_INVALID_ARG;
-  if (pitch_a(p) < p->K || pitch_b(p) < p->N || pitch_c(p) < p->N) return FLUX_ERR_SHAPE;
+  if (p->lda < 0 || p->ldb < 0 || p->ldc < 0 || (p->b_is_nk != 0 && p->b_is_nk != 1) || p->reserved2 != 0) return FLUX_ERR_INVALID_ARG;
+  const long long b_rows = p->b_is_nk ? p->N : p->K, b_cols = p->b_is_nk ? p->K : p->N;      // B as it lies in memory
+  if (pitch_a(p) < p->K || pitch_b(p) < b_cols || pitch_c(p) < p->N) return FLUX_ERR_SHAPE;
   if (pitch_a(p) % 8 != 0 || pitch_b(p) % 8 != 0 || pitch_c(p) % 8 != 0) return FLUX_ERR_SHAPE;
-  if ((long long)(p->M - 1) * pitch_a(p) + p->K >= (1ll << 31) || (long long)(p->K - 1) * pitch_b(p) + p->N >= (1ll << 31) ||
+  if ((long long)(p->M - 1) * pitch_a(p) + p->K >= (1ll << 31) || (b_rows - 1) * pitch_b(p) + b_cols >= (1ll << 31) ||
       (long long)(p->M - 1) * pitch_c(p) + p->N >= (1ll << 31)) return FLUX_ERR_SHAPE;
   // the reduce-scatter epilogue addresses a tile of fp32 partials (up to 256 rows) through a signed
   // 31-bit offset from the tile's origin: 256 rows of 4-byte elements must stay below 2^31 bytes
@@ -653,6 +654,7 @@ static void fill_common(GemmArgs* a, const flux_problem_t* p, const Plan& pl, vo
   a->M = p->M; a->N = p->N; a->K = p->K;
   a->R = p->R; a->rank = p->rank; a->S = p->M / p->R;
   a->lda = (int32_t)pitch_a(p); a->ldb = (int32_t)pitch_b(p); a->ldc = (int32_t)pitch_c(p);
+  a->b_is_nk = p->b_is_nk;
   a->partial_f32 = p->partial_dtype == FLUX_F32;
   a->out_f32 = p->out_dtype == FLUX_F32;
   a->split_k = pl.split_k;

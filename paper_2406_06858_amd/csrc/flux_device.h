@@ -89,6 +89,7 @@ struct GemmArgs {
   int32_t M, N, K;
   int32_t R, rank, S;        // S = M / R
   int32_t lda, ldb, ldc;     // row pitches in elements: A (the gathered matrix); B; C and the out slices (peer partials are packed)
+  int32_t b_is_nk;           // B is [N,K] (the kernels built for that layout are launched)
   // K split: the first `full_tiles` tiles (in TileCoord order) are computed by one workgroup
   // each; every one of the remaining `split_tiles` tiles by `split_k` workgroups that each take
   // `k_per_split` of K.  A uniform split has full_tiles = 0; splitting only the tiles of the last,
@@ -260,10 +261,14 @@ __device__ __forceinline__ void st_out16(void* p, const uint4& v, bool through) 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int OCC_>
+// B_NK: B is given as [N,K] (row n holds the K values of output column n, the layout of a linear
+// layer's weight).  Its tile then sits in LDS like A's (rows of BK values, the same slot swizzle) and a
+// fragment is one 16-byte read per lane, as for A, instead of two transposing reads.
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int OCC_, bool B_NK_ = false>
 struct TileCfg {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NSTAGE = NSTAGE_, OCC = OCC_;
+  static constexpr bool B_NK = B_NK_;
   static constexpr int NT = WAVES_M * WAVES_N * 64;
   static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   static constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -307,13 +312,23 @@ struct Loader {
 #pragma unroll
     for (int p = 0; p < C::B_VEC; ++p) {
       const int v = tid + C::NT * p;
-      const int k = v / C::B_SLOTS, s = v % C::B_SLOTS;
-      int gn = n0 + s * 8;
-      nb_ok[p] = !EDGE || gn < a.N;
-      if (EDGE && gn >= a.N) gn = 0;
-      pb[p] = a.B + (size_t)k * a.ldb + gn;
-      kb[p] = k;
-      lds_b[p] = C::A_BYTES + k * (C::BN * 2) + ((s ^ swz_b<C::B_SLOTS>(k)) << 4);
+      if constexpr (C::B_NK) {
+        const int n = v / C::A_SLOTS, slot = v % C::A_SLOTS;
+        int gn = n0 + n;
+        nb_ok[p] = !EDGE || gn < a.N;
+        if (EDGE && gn >= a.N) gn = 0;
+        pb[p] = a.B + (size_t)gn * a.ldb + slot * 8;
+        kb[p] = slot * 8;
+        lds_b[p] = C::A_BYTES + n * (C::BK * 2) + ((slot ^ swz_a<C::A_SLOTS>(n)) << 4);
+      } else {
+        const int k = v / C::B_SLOTS, s = v % C::B_SLOTS;
+        int gn = n0 + s * 8;
+        nb_ok[p] = !EDGE || gn < a.N;
+        if (EDGE && gn >= a.N) gn = 0;
+        pb[p] = a.B + (size_t)k * a.ldb + gn;
+        kb[p] = k;
+        lds_b[p] = C::A_BYTES + k * (C::BN * 2) + ((s ^ swz_b<C::B_SLOTS>(k)) << 4);
+      }
     }
   }
 
@@ -325,7 +340,8 @@ struct Loader {
     }
 #pragma unroll
     for (int p = 0; p < C::B_VEC; ++p) {
-      if (!EDGE || (nb_ok[p] && k0 + kb[p] < k_end)) rb[p] = *reinterpret_cast<const uint4*>(pb[p] + (size_t)k0 * a.ldb);
+      if (!EDGE || (nb_ok[p] && k0 + kb[p] < k_end))
+        rb[p] = *reinterpret_cast<const uint4*>(pb[p] + (C::B_NK ? (size_t)k0 : (size_t)k0 * a.ldb));
       else rb[p] = make_uint4(0, 0, 0, 0);
     }
   }
@@ -354,14 +370,20 @@ __device__ __forceinline__ void mma_stage(const unsigned char* stage, int wm, in
     }
 #pragma unroll
     for (int ni = 0; ni < C::NI; ++ni) {
-      const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
-      const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);
-      const int off = C::A_BYTES + k * (C::BN * 2) + ((((n >> 3) ^ swz_b<C::B_SLOTS>(k))) << 4) + ((n >> 2) & 1) * 8;
-      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off + 4 * C::BN * 2));
-      s16x8 w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-      bfr[ni] = __builtin_bit_cast(bf16x8, w);
+      if constexpr (C::B_NK) {
+        const int row = wn * C::WTN + ni * 32 + (lane & 31);
+        const int q = ks * 2 + (lane >> 5);
+        bfr[ni] = *reinterpret_cast<const bf16x8*>(stage + C::A_BYTES + row * (C::BK * 2) + ((q ^ swz_a<C::A_SLOTS>(row)) << 4));
+      } else {
+        const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
+        const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);
+        const int off = C::A_BYTES + k * (C::BN * 2) + ((((n >> 3) ^ swz_b<C::B_SLOTS>(k))) << 4) + ((n >> 2) & 1) * 8;
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(stage + off + 4 * C::BN * 2));
+        s16x8 w = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        bfr[ni] = __builtin_bit_cast(bf16x8, w);
+      }
     }
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi)
@@ -1318,11 +1340,11 @@ struct DmaLoader {
   static constexpr int NW = C::NT / 64;
   static constexpr int A_RPI = 8;                              // A rows per instruction (1 KiB of 128-byte rows)
   static constexpr int A_INSTR = C::BM / A_RPI / NW;           // per wave
-  static constexpr int RPI = 512 / C::BN;                      // B k-rows per instruction
-  static constexpr int B_INSTR = C::BK / RPI / NW;             // per wave
+  static constexpr int RPI = C::B_NK ? A_RPI : 512 / C::BN;    // B rows per instruction: k-rows of BN values, or ([N,K]) n-rows of BK
+  static constexpr int B_INSTR = (C::B_NK ? C::BN : C::BK) / RPI / NW;   // per wave
   static_assert(C::BK == 64, "A rows must be 128 B");
   static_assert(NW % 2 == 0 && (RPI * NW) % 4 == 0, "swizzle must not depend on the instruction index");
-  static_assert(C::BM % (A_RPI * NW) == 0 && C::BK % (RPI * NW) == 0 && 512 % C::BN == 0, "loader shape");
+  static_assert(C::BM % (A_RPI * NW) == 0 && (C::B_NK ? C::BN : C::BK) % (RPI * NW) == 0 && 512 % C::BN == 0, "loader shape");
 
   // Offsets into A and B are unsigned 32-bit byte offsets (a matrix has fewer than 2^31 elements, so
   // fewer than 2^32 bytes); the hardware adds the vector and the scalar part as unsigned numbers.
@@ -1332,17 +1354,22 @@ struct DmaLoader {
 
   __device__ __forceinline__ void init(const GemmArgs& a, int m0, int n0, int wave, int lane) {
     ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.A), 0, (int)(((unsigned)(a.M - 1) * (unsigned)a.lda + (unsigned)a.K) * 2u), 0x00027000);
-    rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0, (int)(((unsigned)(a.K - 1) * (unsigned)a.ldb + (unsigned)a.N) * 2u), 0x00027000);
+    rb = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(a.B), 0,
+                                           (int)((C::B_NK ? (unsigned)(a.N - 1) * (unsigned)a.ldb + (unsigned)a.K
+                                                          : (unsigned)(a.K - 1) * (unsigned)a.ldb + (unsigned)a.N) * 2u), 0x00027000);
     const int r_in = lane / C::A_SLOTS, sp = lane % C::A_SLOTS;
     const int row = A_RPI * wave + r_in;
     K2 = (uint32_t)a.lda * 2u;
     N2 = (uint32_t)a.ldb * 2u;
     voff_a = (uint32_t)(m0 + row) * K2 + ((uint32_t)(sp ^ swz_a<C::A_SLOTS>(row)) << 4);
-    const int k_in = lane / C::B_SLOTS, spb = lane % C::B_SLOTS;
-    const int k = RPI * wave + k_in;
-    voff_b = (uint32_t)k * N2 + (uint32_t)n0 * 2u + ((uint32_t)(spb ^ swz_b<C::B_SLOTS>(k)) << 4);
+    if constexpr (C::B_NK) {
+      voff_b = (uint32_t)(n0 + row) * N2 + ((uint32_t)(sp ^ swz_a<C::A_SLOTS>(row)) << 4);      // as for A, rows of n
+    } else {
+      const int k_in = lane / C::B_SLOTS, spb = lane % C::B_SLOTS;
+      const int k = RPI * wave + k_in;
+      voff_b = (uint32_t)k * N2 + (uint32_t)n0 * 2u + ((uint32_t)(spb ^ swz_b<C::B_SLOTS>(k)) << 4);
+    }
   }
-
   static constexpr int N_INSTR = A_INSTR + B_INSTR;
 
   // same with an index that is constant after loop unrolling
@@ -1353,7 +1380,7 @@ struct DmaLoader {
     } else {
       const int p = idx - A_INSTR;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, (int)voff_b,
-                                               (int)((uint32_t)(k0 + p * RPI * NW) * N2), 0, 0);
+                                               (int)(C::B_NK ? (uint32_t)k0 * 2u + (uint32_t)(p * RPI * NW) * N2 : (uint32_t)(k0 + p * RPI * NW) * N2), 0, 0);
     }
   }
 
@@ -1369,7 +1396,7 @@ struct DmaLoader {
 #pragma unroll
     for (int p = 0; p < B_INSTR; ++p)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t*)(stage + C::A_BYTES + (p * NW + wave) * 1024), 16, (int)voff_b,
-                                               (int)((uint32_t)(k0 + p * RPI * NW) * N2), 0, 0);
+                                               (int)(C::B_NK ? (uint32_t)k0 * 2u + (uint32_t)(p * RPI * NW) * N2 : (uint32_t)(k0 + p * RPI * NW) * N2), 0, 0);
     // keep the loads where they are written: scheduled late they would be issued just before
     // the wait for them, and nothing would overlap
     __builtin_amdgcn_sched_barrier(0);
@@ -1390,6 +1417,11 @@ __device__ __forceinline__ bf16x8 frag_a(const unsigned char* stage, int ks, int
 
 template <class C>
 __device__ __forceinline__ bf16x8 frag_b(const unsigned char* stage, int ks, int ni, int wn, int lane) {
+  if constexpr (C::B_NK) {
+    const int row = wn * C::WTN + ni * 32 + (lane & 31);
+    const int q = ks * 2 + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(stage + C::A_BYTES + row * (C::BK * 2) + ((q ^ swz_a<C::A_SLOTS>(row)) << 4));
+  }
   const int g = lane >> 4, i = lane & 15;
   const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
   const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);
@@ -1423,6 +1455,14 @@ __device__ __forceinline__ bf16x8 frag_a_opaque(uint32_t stage, int ks, int mi, 
 
 template <class C>
 __device__ __forceinline__ bf16x8 frag_b_opaque(uint32_t stage, int ks, int ni, int wn, int lane) {
+  if constexpr (C::B_NK) {
+    const int row = wn * C::WTN + ni * 32 + (lane & 31);
+    const int q = ks * 2 + (lane >> 5);
+    const uint32_t addr = stage + C::A_BYTES + row * (C::BK * 2) + ((q ^ swz_a<C::A_SLOTS>(row)) << 4);
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return __builtin_bit_cast(bf16x8, v);
+  }
   const int g = lane >> 4, i = lane & 15;
   const int k = ks * 16 + 8 * (g >> 1) + (i >> 2);
   const int n = wn * C::WTN + ni * 32 + 16 * (g & 1) + 4 * (i & 3);

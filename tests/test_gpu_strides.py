@@ -1,6 +1,6 @@
-"""GPU parity with row pitches (lda / ldb / ldc of the problem): the operands and results sit in
-wider allocations, the oracle gets the packed views.  Integer inputs, so every comparison is bit
-for bit.  What lies between the end of a row and the next row is NaN on the input side (a kernel
+"""GPU parity with row pitches (lda / ldb / ldc of the problem) and with B given as [N,K]
+(b_is_nk): the operands and results sit in wider allocations, B may be handed over transposed, the
+oracle gets the packed [K,N] views.  Integer inputs, so every comparison is bit for bit.  What lies between the end of a row and the next row is NaN on the input side (a kernel
 that read it would poison its result) and a sentinel on the output side that must survive."""
 import numpy as np
 import pytest
@@ -41,13 +41,20 @@ def assert_gap_untouched(store: torch.Tensor, cols: int, what: str):
     assert gap.numel() == 0 or bool((gap == SENTINEL).all()), f"{what}: the gap between rows was written"
 
 
-def _rs_call(w, rank, A, B, peers, pads, tile_config=0, split_k=0, flags=0, static=False):
+def b_operand(B: torch.Tensor, pad: int, nk: bool):
+    """B on the device as the library is to see it: [K,N], or its transpose [N,K], in rows `pad` elements longer."""
+    Bm = B.t().contiguous() if nk else B
+    ldb = Bm.shape[1] + pad
+    return wide(Bm.to(gh.DEV), ldb)[1], (ldb if pad else 0)
+
+
+def _rs_call(w, rank, A, B, peers, pads, tile_config=0, split_k=0, flags=0, static=False, nk=False):
     pa, pb, pc = pads
-    lda, ldb, ldc = w.K + pa, w.N + pb, w.N + pc
+    lda, ldc = w.K + pa, w.N + pc
+    dB, ldb = b_operand(B, pb, nk)
     p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype, tile_config, split_k, flags,
-                   lda=lda if pa else 0, ldb=ldb if pb else 0, ldc=ldc if pc else 0)
+                   lda=lda if pa else 0, ldb=ldb, ldc=ldc if pc else 0, b_is_nk=int(nk))
     _, dA = wide(A.to(gh.DEV), lda)
-    _, dB = wide(B.to(gh.DEV), ldb)
     dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
     outs = [wide_out(w.S, w.N, ldc, w.out_dtype) for _ in range(w.R)]
     if flags & fb.FLUX_FLAG_RS_ATOMIC:
@@ -164,15 +171,79 @@ def test_rs_atomic_with_row_pitches():
 
 
 # ---------------------------------------------------------------------------------------------
+# B as [N,K] (a linear layer's weight as it is stored): same bits as with its transpose
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("cfg", list(range(0, 11)))
+@pytest.mark.parametrize("pads", [(0, 0, 0), (8, 24, 16)])
+def test_rs_with_b_as_n_by_k(cfg, pads):
+    for shape in RS_SHAPES:
+        w = RS_SHAPES[shape]
+        rank = 1
+        _say("rs, B as [N,K], cfg", cfg, shape, pads)
+        A, B, peers = fi.make_rs_inputs(w, rank)
+        _, want = gh.oracle_rs(w, rank, A, B, peers)
+        _, outs = _rs_call(w, rank, A, B, peers, pads, tile_config=cfg, nk=True)
+        for r in range(w.R):
+            gh.assert_bits_equal(outs[r][1], want[r], f"{shape} slice {r}")
+
+
+def test_rs_with_b_as_n_by_k_k_cut_and_resident_grid():
+    w = RS_SHAPES["tiles"]
+    A, B, peers = fi.make_rs_inputs(w, 2)
+    _, want = gh.oracle_rs(w, 2, A, B, peers)
+    for static in (False, True):
+        _say("rs, B as [N,K], split_k 2, static", static)
+        _, outs = _rs_call(w, 2, A, B, peers, (0, 8, 0), tile_config=1, split_k=2, static=static, nk=True)
+        for r in range(w.R):
+            gh.assert_bits_equal(outs[r][1], want[r], f"split slice {r}")
+    wr = fi.Workload("nk_rs_resident", "rs", 8192, 8192, 256, 8, a_dist=("int", 2), b_dist=("int", 2), peer_dist=("int", 8), seed=94)
+    A, B, peers = fi.make_rs_inputs(wr, 3)
+    _, want = gh.oracle_rs(wr, 3, A, B, peers)
+    _say("rs, B as [N,K], resident grid")
+    p, outs = _rs_call(wr, 3, A, B, peers, (0, 0, 0), nk=True)
+    assert fb.flux_rs_resident_grid(p)[0] > 0
+    for r in range(wr.R):
+        gh.assert_bits_equal(outs[r][1], want[r], f"resident slice {r}")
+
+
+@pytest.mark.parametrize("cfg", list(range(0, 11)))
+@pytest.mark.parametrize("pads", [(0, 0, 0), (8, 24, 16)])
+def test_ag_with_b_as_n_by_k(cfg, pads):
+    for shape in ("tiles", "ragged", "few_rows"):
+        w = AG_SHAPES[shape]
+        rank = 2
+        _say("ag, B as [N,K], cfg", cfg, shape, pads)
+        chunks, B, arrival = fi.make_ag_inputs(w, rank)
+        _, want = gh.oracle_ag(w, chunks, B)
+        _, Cg, A_agg = _ag_call(w, rank, chunks, B, arrival, pads, tile_config=cfg, nk=True)
+        gh.assert_bits_equal(Cg, want, f"{shape} C")
+        gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+
+
+def test_ag_with_b_as_n_by_k_chunks_carried_inside_the_main_loops():
+    w = AG_SHAPES["two_rounds"]
+    rank = 5
+    chunks, B, arrival = fi.make_ag_inputs(w, rank)
+    _, want = gh.oracle_ag(w, chunks, B)
+    for kw in (dict(), dict(link_gbps=800)):
+        _say("ag, B as [N,K], carried transfer", kw)
+        p, Cg, A_agg = _ag_call(w, rank, chunks, B, arrival, (0, 0, 0), nk=True, **kw)
+        assert fb.flux_ag_deferred_tiles(p) > 0
+        gh.assert_bits_equal(Cg, want, "C")
+        gh.assert_bits_equal(A_agg, np.concatenate([fi.to_numpy(c) for c in chunks]), "A_agg")
+
+
+# ---------------------------------------------------------------------------------------------
 # AllGather-GEMM: the gathered matrix, B and C pitched; the chunk sources stay packed
 # ---------------------------------------------------------------------------------------------
 
-def _ag_call(w, rank, chunks, B, arrival, pads, repeat=2, local_in_place=False, **kw):
+def _ag_call(w, rank, chunks, B, arrival, pads, repeat=2, local_in_place=False, nk=False, **kw):
     pa, pb, pc = pads
-    lda, ldb, ldc = w.K + pa, w.N + pb, w.N + pc
+    lda, ldc = w.K + pa, w.N + pc
+    dB, ldb = b_operand(B, pb, nk)
     p = fb.problem(w.M, w.N, w.K, w.R, rank, "bf16", w.out_dtype, spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS,
-                   lda=lda if pa else 0, ldb=ldb if pb else 0, ldc=ldc if pc else 0, **kw)
-    _, dB = wide(B.to(gh.DEV), ldb)
+                   lda=lda if pa else 0, ldb=ldb, ldc=ldc if pc else 0, b_is_nk=int(nk), **kw)
     agg_store = torch.full((w.M, lda), SENTINEL, dtype=torch.bfloat16, device=gh.DEV)
     A_agg = agg_store[:, :w.K]
     dchunks = [c.to(gh.DEV) for c in chunks]
@@ -204,7 +275,7 @@ AG_SHAPES = {
     "tiles": fi.Workload("pitch_ag", "ag", 1024, 512, 448, 4, a_dist=("int", 2), b_dist=("int", 2), seed=95),
     "ragged": fi.Workload("pitch_ag_ragged", "ag", 1000, 520, 200, 8, a_dist=("int", 2), b_dist=("int", 2), seed=96),
     "few_rows": fi.Workload("pitch_ag_decode", "ag", 64, 1792, 1024, 8, a_dist=("int", 2), b_dist=("int", 2), seed=97),
-    "two_rounds": fi.Workload("pitch_ag_two_rounds", "ag", 8192, 4608, 512, 8, a_dist=("int", 2), b_dist=("int", 2), seed=98),
+    "two_rounds": fi.Workload("pitch_ag_two_rounds", "ag", 8192, 4608, 1024, 8, a_dist=("int", 2), b_dist=("int", 2), seed=98),
 }
 
 AG_FORMS = {
@@ -252,16 +323,17 @@ def test_ag_with_row_pitches_local_chunk_in_place_and_every_configuration():
 # the unfused and chunked references take the same pitches
 # ---------------------------------------------------------------------------------------------
 
-def test_references_with_row_pitches():
+@pytest.mark.parametrize("nk", [False, True])
+def test_references_with_row_pitches(nk):
     pads = (8, 16, 24)
     w = RS_SHAPES["ragged"]
     rank = 2
-    lda, ldb, ldc = w.K + pads[0], w.N + pads[1], w.N + pads[2]
+    lda, ldc = w.K + pads[0], w.N + pads[2]
     A, B, peers = fi.make_rs_inputs(w, rank)
     _, want = gh.oracle_rs(w, rank, A, B, peers)
-    p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype, lda=lda, ldb=ldb, ldc=ldc)
+    dB, ldb = b_operand(B, pads[1], nk)
+    p = fb.problem(w.M, w.N, w.K, w.R, rank, w.partial_dtype, w.out_dtype, lda=lda, ldb=ldb, ldc=ldc, b_is_nk=int(nk))
     _, dA = wide(A.to(gh.DEV), lda)
-    _, dB = wide(B.to(gh.DEV), ldb)
     dpeers = [None if t is None else t.to(gh.DEV) for t in peers]
     for which in ("unfused", "chunked"):
         _say("rs reference with pitches:", which)
@@ -285,11 +357,11 @@ def test_references_with_row_pitches():
             gh.assert_bits_equal(outs[r][1], want[r], f"{which} slice {r}")
 
     wa = AG_SHAPES["ragged"]
-    lda, ldb, ldc = wa.K + pads[0], wa.N + pads[1], wa.N + pads[2]
+    lda, ldc = wa.K + pads[0], wa.N + pads[2]
     chunks, B, arrival = fi.make_ag_inputs(wa, rank)
     _, want = gh.oracle_ag(wa, chunks, B)
-    p = fb.problem(wa.M, wa.N, wa.K, wa.R, rank, "bf16", wa.out_dtype, lda=lda, ldb=ldb, ldc=ldc)
-    _, dB = wide(B.to(gh.DEV), ldb)
+    dB, ldb = b_operand(B, pads[1], nk)
+    p = fb.problem(wa.M, wa.N, wa.K, wa.R, rank, "bf16", wa.out_dtype, lda=lda, ldb=ldb, ldc=ldc, b_is_nk=int(nk))
     dchunks = [c.to(gh.DEV) for c in chunks]
     for which in ("unfused", "chunked"):
         _say("ag reference with pitches:", which)

@@ -24,9 +24,10 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 
 def test_problem_struct_layout_matches_header():
-    # 14 int32/uint32 fields, one uint64, three int64 row pitches, naturally aligned
+    # 14 int32/uint32 fields, one uint64, three int64 row pitches, two int32, naturally aligned
     import ctypes
-    assert ctypes.sizeof(fb.flux_problem_t) == 88
+    assert ctypes.sizeof(fb.flux_problem_t) == 96
+    assert fb.flux_problem_t.b_is_nk.offset == 88
     assert fb.flux_problem_t.spin_timeout_ticks.offset == 56
     assert (fb.flux_problem_t.lda.offset, fb.flux_problem_t.ldb.offset, fb.flux_problem_t.ldc.offset) == (64, 72, 80)
 
@@ -276,12 +277,15 @@ def test_offsets_stay_in_32_bits_at_the_edges_of_validation():
     (dict(lda=-8), fb.FLUX_ERR_INVALID_ARG),
     (dict(ldc=1 << 21), fb.FLUX_ERR_SHAPE),          # a tile of the slice would pass 2^31 bytes
     (dict(lda=1 << 25), fb.FLUX_ERR_SHAPE),          # the last element's index would pass 2^31
+    (dict(b_is_nk=2), fb.FLUX_ERR_INVALID_ARG),
+    (dict(b_is_nk=1, ldb=256), fb.FLUX_ERR_SHAPE),   # rows of B as [N,K] hold K = 512 values
 ])
 def test_row_pitches_are_validated(bad, status):
-    p = fb.problem(128, 256, 256, 8, 0, **bad)
+    p = fb.problem(128, 256, 512 if "b_is_nk" in bad else 256, 8, 0, **bad)
     with pytest.raises(fb.FluxError) as e:
         fb.flux_tile_shape(fb.FLUX_OP_RS, p)
     assert e.value.status == status
+    assert fb.flux_tile_shape(fb.FLUX_OP_RS, fb.problem(128, 256, 512, 8, 0, b_is_nk=1, ldb=512)).tile_m > 0
 
 
 def test_row_pitches_in_planning():
