@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 # bytes per launch behind the L2 of the two kernels of the timed step (rocprofv3 FETCH_SIZE + WRITE_SIZE)
-TRAFFIC_BYTES = {"rs": 2171.4e6 + 205.8e6, "ag": 2640.9e6 + 318.9e6}     # profiles/bench_c4_pmc_traffic.txt
+TRAFFIC_BYTES = {"rs": 2170.7e6 + 205.8e6, "ag": 2619.6e6 + 319.2e6}     # profiles/bench_c4_pmc_traffic.txt
 HBM_PEAK_GBS = 8000.0
 TIMEOUT_TICKS = 500_000_000        # 5 s: a lost signal ends the run with an error, not a hang
 
@@ -412,7 +412,7 @@ def main() -> int:
 
     # Traffic behind the L2 per launch, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
     # `bench.py --serial-kernels 5`, each scaled by what the same counter reads for the 176.2 MB chunk
-    # copy of the same run (1.9977 and 1.0000 KiB per count); profiles/bench_c4_pmc_traffic.txt.
+    # copy of the same run (1.9986 and 1.0000 KiB per count); profiles/bench_c4_pmc_traffic.txt.
     traffic = TRAFFIC_BYTES
     alg = {"rs": rs.alg_bytes(), "ag": ag.alg_bytes()}
 
