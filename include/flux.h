@@ -132,7 +132,8 @@ typedef struct flux_problem {
                                least a row long, below FLUX_MAX_N (ldc), the last element's index
                                below 2^31.
                                lda: A (flux_gemm_rs, the references) and the gathered matrix A_agg
-                                    (flux_ag_gemm); the chunk sources A_chunks[r] are packed [M/R,K].
+                                    (flux_ag_gemm); the chunk sources A_chunks[r] are packed [M/R,K]
+                                    (a local chunk handed over in place has A_agg's pitch).
                                ldb: B (rows of N values, or of K values with b_is_nk).
                                ldc: C, every out slice, and the staged slices that
                                     FLUX_FLAG_RS_WRITE_ONLY / flux_gemm_rs_notify write and

@@ -170,6 +170,46 @@ def test_rs_atomic_with_row_pitches():
         gh.assert_bits_equal(outs[r][1], want[r], f"slice {r}")
 
 
+@pytest.mark.parametrize("nk", [False, True])
+def test_tile_ready_producers_and_reducer_with_row_pitches(nk):
+    """Reduce with tile-ready counters (Sec. 4.2, second form): producers write pitched staging slices and
+    count their tiles in, the owner's reducer reads them at that pitch and writes a pitched slice."""
+    from oracle import flux_oracle as fo
+    R, owner, dt = 4, 2, "bf16"
+    w = fi.Workload("pitch_rs_ready", "rs", 1024, 1280, 512, R, partial_dtype=dt, out_dtype=dt, seed=99,
+                    a_dist=("int", 2), b_dist=("int", 2))
+    pads = (8, 16, 40)
+    lda, ldc = w.K + pads[0], w.N + pads[2]
+    prods = []
+    for j in range(R):
+        A, B, _ = fi.make_rs_inputs(w, j)
+        dB, ldb = b_operand(B, pads[1], nk)
+        p = fb.problem(w.M, w.N, w.K, R, j, dt, dt, lda=lda, ldb=ldb, ldc=ldc, b_is_nk=int(nk), spin_timeout_ticks=gh.TEST_TIMEOUT_TICKS)
+        outs = [wide_out(w.S, w.N, ldc, dt) for _ in range(R)]
+        prods.append(dict(p=p, A=A, B=B, dA=wide(A.to(gh.DEV), lda)[1], dB=dB, outs=outs, stream=torch.cuda.Stream()))
+    ready = torch.zeros(fb.flux_rs_ready_count(prods[0]["p"]), dtype=torch.int32, device=gh.DEV)
+    cws = torch.zeros(16384, dtype=torch.int32, device=gh.DEV)
+    fb.flux_init_buffers(fb.FLUX_OP_RS, prods[0]["p"], cws)
+    store, out = wide_out(w.S, w.N, ldc, dt)
+    torch.cuda.synchronize()
+    _say("tile-ready with pitches, B as [N,K]:", nk)
+    for d in prods:
+        fb.flux_gemm_rs_notify(d["p"], d["dA"], d["dB"], [v for _, v in d["outs"]], ready, None, d["stream"])
+    fb.flux_rs_reduce_slice_ready(prods[owner]["p"], [d["outs"][owner][1] for d in prods], out, ready, R, cws, torch.cuda.Stream())
+    torch.cuda.synchronize()
+    assert fb.flux_query_status(cws) == (fb.FLUX_OK, 0)
+    assert (ready == R).all()
+    staged = []
+    for j, d in enumerate(prods):
+        _, sbits = fo.gemm_scatter(fi.to_numpy(d["A"]), fi.to_numpy(d["B"]), R, dt)
+        for r in range(R):
+            assert_gap_untouched(d["outs"][r][0], w.N, f"producer {j} slice {r}")
+            gh.assert_bits_equal(d["outs"][r][1], sbits[r], f"producer {j} slice {r}")
+        staged.append(sbits[owner])
+    assert_gap_untouched(store, w.N, "reduced slice")
+    gh.assert_bits_equal(out, fo.reduce_slice(staged, dt, dt)[1], "reduced slice")
+
+
 # ---------------------------------------------------------------------------------------------
 # B as [N,K] (a linear layer's weight as it is stored): same bits as with its transpose
 # ---------------------------------------------------------------------------------------------
