@@ -29,8 +29,9 @@ Pins (tests/test_oracle_*.py): literal triple-loop brute force on tiny shapes, e
 closed forms, the reduce-scatter and all-gather invariants, one-hot placement probes, the
 communication-order example printed in Sec. 4.3, exhaustive bf16 round trips and hand-built
 rounding midpoints, and the limits of Eq. 2.  The protocol simulation `simulate_ag_protocol`
-has no value in the paper to compare with: parity unpinned by the paper, pinned by
-construction (poison must never be read) in tests.
+has no value in the paper to compare with; it is pinned by the all-gather invariant (for every
+arrival order and driver pace its result is the plain gathered GEMM, with every row poisoned until
+its transfer) and by closed-form counts of the tiles that have to wait.
 """
 from __future__ import annotations
 

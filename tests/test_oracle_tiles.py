@@ -162,6 +162,30 @@ def test_protocol_replay_waits_only_when_copy_lags():
         fo.visit_order_ag(rank, R, [0, 1])
 
 
+@pytest.mark.parametrize("R", [2, 3, 5, 8])
+def test_protocol_replay_wait_counts_have_a_closed_form(R):
+    """Alg. 2 + Alg. 3 replayed with a driver that delivers a chunk of its own accord every `mult`
+    bands of tiles (a band = the tiles of one chunk, visited in arrival order, Sec. 4.1): the first
+    tile of band j finds its signal unset exactly when j is not a multiple of `mult` (the chunks
+    before it were forced in by the bands before, the driver's own step comes only at multiples), so
+    the number of waiting tiles is #{1 <= j < R : j mod mult != 0}.  Whatever the pace and the
+    arrival order, the result is the plain gathered GEMM and no poisoned row is ever read."""
+    rng = np.random.default_rng(50 + R)
+    S, K, N, BM, BN = 4, 6, 8, 2, 4
+    band = (S // BM) * (N // BN)
+    to_bits = lambda a: fo.f64_to_bf16_bits(a)
+    chunks = [to_bits(rng.integers(-3, 4, (S, K)).astype(np.float64)) for _ in range(R)]
+    B = to_bits(rng.integers(-3, 4, (K, N)).astype(np.float64))
+    want, _ = fo.ag_gemm(chunks, B, "f32")
+    for rank in range(R):
+        orders = [None, list(reversed(fo.default_order(rank, R)))]
+        for order in orders:
+            for mult in (1, 2, 3):
+                C, waits = fo.simulate_ag_protocol(chunks, B, rank, BM, BN, order, tiles_per_step=mult * band)
+                assert np.array_equal(C, want)
+                assert waits == sum(1 for j in range(1, R) if j % mult != 0)
+
+
 @pytest.mark.parametrize("ctpc", [1, 2, 4, 8])
 @pytest.mark.parametrize("n_xcd", [1, 8])
 def test_ag_bands_follow_the_communication_tile(ctpc, n_xcd):
